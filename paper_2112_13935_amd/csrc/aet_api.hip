@@ -1,0 +1,491 @@
+// C ABI and host scheduler of the AET-SGD library: per-client round counters, the
+// threshold s_i = a*i + b, the round step size, sample counters, the message queue with
+// its deterministic delays, and the order in which arrivals are aggregated.  All of it
+// is integer bookkeeping on the host; the floating-point work is enqueued as kernels.
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/aet_sgd.h"
+#include "aet_device.h"
+#include "aet_internal.h"
+
+using namespace aet;
+
+namespace {
+
+constexpr int kRing = 4;            // pinned staging buffers in flight
+constexpr int kDebugIdx = 65536;    // capacity of the debug index buffer
+constexpr uint64_t kTagSample = 0;  // stream purposes of the counter hash
+constexpr uint64_t kTagNet = 1;
+
+struct Msg {
+    int32_t c, k;
+    float eta;
+    int64_t arrival;
+    int slot;
+};
+
+struct RoundRec {
+    int64_t s, m, q0, t0, start, arrival;
+    float eta;
+};
+
+struct Layout {
+    size_t Wg, W, U, loss, params, arrivals, partial, debug, labels;
+    size_t act[AET_MAX_LAYERS + 1], del[AET_MAX_LAYERS + 1], amax[AET_MAX_LAYERS];
+    size_t total;
+    int max_chunks;
+};
+
+std::string g_init_error;
+
+size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Geometry of every layer, or false if the description is not supported.
+bool resolve(const aet_model_desc *m, LayerGeom *lay, int64_t *P, std::string *why) {
+    if (!m || m->n_layers < 1 || m->n_layers > AET_MAX_LAYERS) { *why = "n_layers out of range"; return false; }
+    if (m->batch < 1 || m->batch > 256) { *why = "batch must be 1..256"; return false; }
+    if (m->in_c < 1 || m->in_h < 1 || m->in_w < 1) { *why = "bad input shape"; return false; }
+    int c = m->in_c, h = m->in_h, w = m->in_w;
+    int64_t off = 0;
+    for (int l = 0; l < m->n_layers; ++l) {
+        const aet_layer &q = m->layers[l];
+        LayerGeom &o = lay[l];
+        std::memset(&o, 0, sizeof o);
+        o.type = q.type; o.relu = q.relu ? 1 : 0; o.k = q.k; o.pad = q.pad;
+        o.ic = c; o.ih = h; o.iw = w;
+        o.in_size = (int64_t)c * h * w;
+        if (q.type == AET_CONV) {
+            if (!(q.k == 1 || q.k == 2 || q.k == 3 || q.k == 5)) { *why = "conv kernel size must be 1, 2, 3 or 5"; return false; }
+            if (q.pad < 0 || q.pad >= q.k || q.cout < 1) { *why = "bad conv layer"; return false; }
+            o.oc = q.cout; o.oh = h + 2 * q.pad - q.k + 1; o.ow = w + 2 * q.pad - q.k + 1;
+            if (o.oh < 1 || o.ow < 1) { *why = "conv output is empty"; return false; }
+            o.w_off = off; off += (int64_t)q.cout * c * q.k * q.k;
+            o.b_off = off; off += q.cout;
+        } else if (q.type == AET_POOL) {
+            if ((h & 1) || (w & 1)) { *why = "pool input must have even height and width"; return false; }
+            if (l == 0) { *why = "first layer cannot be a pool"; return false; }
+            o.oc = c; o.oh = h / 2; o.ow = w / 2; o.relu = 0;
+        } else if (q.type == AET_DENSE) {
+            if (q.cout < 1) { *why = "bad dense layer"; return false; }
+            o.oc = q.cout; o.oh = 1; o.ow = 1;
+            o.w_off = off; off += (int64_t)q.cout * o.in_size;
+            o.b_off = off; off += q.cout;
+        } else { *why = "unknown layer type"; return false; }
+        o.out_size = (int64_t)o.oc * o.oh * o.ow;
+        if (o.in_size > (1 << 28) || o.out_size > (1 << 28)) { *why = "layer too large"; return false; }
+        c = o.oc; h = o.oh; w = o.ow;
+    }
+    const aet_layer &last = m->layers[m->n_layers - 1];
+    if (last.type != AET_DENSE || last.relu) { *why = "last layer must be dense without ReLU"; return false; }
+    if (last.cout > 1024) { *why = "too many classes"; return false; }
+    *P = off;
+    return true;
+}
+
+bool make_layout(const LayerGeom *lay, int L, int64_t P, int B, int n, int inflight, int rounds,
+                 Layout *lo) {
+    if (n < 1 || inflight < 1 || rounds < 1) return false;
+    const size_t Ps = (size_t)((P + 63) / 64 * 64);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    lo->Wg = take(Ps * 4);
+    lo->W = take(Ps * 4 * n);
+    lo->U = take(Ps * 4 * (size_t)n * inflight);
+    lo->loss = take((size_t)n * rounds * 4);
+    lo->params = take((size_t)n * sizeof(RoundParams));
+    lo->arrivals = take((size_t)n * inflight * sizeof(Arrival));
+    lo->max_chunks = (n * inflight + 15) / 16;
+    lo->partial = take(Ps * 4 * (size_t)lo->max_chunks);
+    lo->debug = take((size_t)kDebugIdx * 4);
+    lo->labels = take((size_t)n * B * 4);
+    const size_t samples = (size_t)n * B;
+    lo->act[0] = take(samples * lay[0].in_size * 4);
+    lo->del[0] = 0;
+    for (int l = 0; l < L; ++l) {
+        lo->act[l + 1] = take(samples * lay[l].out_size * 4);
+        lo->del[l + 1] = take(samples * lay[l].out_size * 4);
+        lo->amax[l] = lay[l].type == AET_POOL ? take(samples * lay[l].out_size) : 0;
+    }
+    lo->total = off;
+    return true;
+}
+
+}  // namespace
+
+struct aet_ctx {
+    LayerGeom lay[AET_MAX_LAYERS];
+    int L = 0, B = 0, n = 0, inflight = 0, max_rounds = 0;
+    int64_t P = 0, Ps = 0;
+    uint64_t seed = 0;
+    hipStream_t stream = nullptr;
+    char *ws = nullptr;
+    Layout lo{};
+    LayerScratch sc{};
+    std::vector<aet_shard> shards;
+    std::vector<uint64_t> key;
+    std::vector<int64_t> i_c, t_c, q_c, free_at, H;
+    std::vector<std::vector<RoundRec>> recs;
+    std::vector<Msg> queue;
+    std::vector<int> free_slots;
+    int64_t tick = 0;
+    RoundParams *h_params[kRing] = {};
+    Arrival *h_arr[kRing] = {};
+    hipEvent_t ev_params[kRing] = {}, ev_arr[kRing] = {};
+    int ring_p = 0, ring_a = 0;
+    bool dead = false;
+    std::string err;
+
+    float *Wg() const { return reinterpret_cast<float *>(ws + lo.Wg); }
+    float *Wc(int c) const { return reinterpret_cast<float *>(ws + lo.W) + (int64_t)c * Ps; }
+    float *Uslot(int s) const { return reinterpret_cast<float *>(ws + lo.U) + (int64_t)s * Ps; }
+    float *loss_at(int c, int k) const {
+        return reinterpret_cast<float *>(ws + lo.loss) + (int64_t)c * max_rounds + k;
+    }
+};
+
+namespace {
+
+aet_status fail(aet_ctx *ctx, aet_status st, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf; else g_init_error = buf;
+    return st;
+}
+
+aet_status hip_fail(aet_ctx *ctx, hipError_t e, const char *what) {
+    if (ctx) ctx->dead = true;
+    return fail(ctx, AET_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define AET_HIP(ctx, call)                                   \
+    do {                                                     \
+        hipError_t e_ = (call);                              \
+        if (e_ != hipSuccess) return hip_fail(ctx, e_, #call); \
+    } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int64_t aet_n_params(const aet_model_desc *model) {
+    LayerGeom lay[AET_MAX_LAYERS];
+    int64_t P;
+    std::string why;
+    return resolve(model, lay, &P, &why) ? P : -1;
+}
+
+size_t aet_workspace_bytes(const aet_model_desc *model, int32_t n_clients, int32_t max_inflight,
+                           int32_t max_rounds) {
+    LayerGeom lay[AET_MAX_LAYERS];
+    int64_t P;
+    std::string why;
+    Layout lo;
+    if (!resolve(model, lay, &P, &why)) return 0;
+    if (!make_layout(lay, model->n_layers, P, model->batch, n_clients, max_inflight, max_rounds, &lo))
+        return 0;
+    return lo.total;
+}
+
+aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_clients,
+                    const aet_shard *shards, const float *w0, uint64_t seed, void *workspace,
+                    size_t workspace_bytes, int32_t max_inflight, int32_t max_rounds,
+                    void *hip_stream) {
+    if (!out) return fail(nullptr, AET_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!model || !shards || !w0 || !workspace) return fail(nullptr, AET_EINVAL, "NULL argument");
+    if (n_clients < 1 || n_clients > 65535) return fail(nullptr, AET_EINVAL, "n_clients must be 1..65535");
+    if (max_inflight < 1 || max_rounds < 1) return fail(nullptr, AET_EINVAL, "max_inflight and max_rounds must be >= 1");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(nullptr, AET_EINVAL, "workspace must be 256-byte aligned");
+    aet_ctx *ctx = new (std::nothrow) aet_ctx();
+    if (!ctx) return fail(nullptr, AET_ENOMEM, "host allocation failed");
+    std::string why;
+    if (!resolve(model, ctx->lay, &ctx->P, &why)) {
+        delete ctx;
+        return fail(nullptr, AET_EINVAL, "unsupported model: %s", why.c_str());
+    }
+    ctx->L = model->n_layers; ctx->B = model->batch; ctx->n = n_clients;
+    ctx->inflight = max_inflight; ctx->max_rounds = max_rounds;
+    ctx->Ps = (ctx->P + 63) / 64 * 64;
+    ctx->seed = seed;
+    ctx->stream = reinterpret_cast<hipStream_t>(hip_stream);
+    ctx->ws = static_cast<char *>(workspace);
+    make_layout(ctx->lay, ctx->L, ctx->P, ctx->B, ctx->n, max_inflight, max_rounds, &ctx->lo);
+    if (workspace_bytes < ctx->lo.total) {
+        const size_t need = ctx->lo.total;
+        delete ctx;
+        return fail(nullptr, AET_ENOMEM, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    }
+    for (int c = 0; c < n_clients; ++c) {
+        if (!shards[c].X || !shards[c].y || shards[c].n_samples < 1 || shards[c].n_samples > 2147483647LL) {
+            delete ctx;
+            return fail(nullptr, AET_EINVAL, "shard %d: NULL pointer or n_samples outside 1..2^31-1", c);
+        }
+    }
+    ctx->shards.assign(shards, shards + n_clients);
+    ctx->key.resize(n_clients);
+    const uint64_t sample_key = splitmix_at(seed, kTagSample);
+    for (int c = 0; c < n_clients; ++c) ctx->key[c] = splitmix_at(sample_key, (uint64_t)c);
+    ctx->i_c.assign(n_clients, 0); ctx->t_c.assign(n_clients, 0); ctx->q_c.assign(n_clients, 0);
+    ctx->free_at.assign(n_clients, 0); ctx->H.assign(n_clients, 0);
+    ctx->recs.resize(n_clients);
+    for (int s = n_clients * max_inflight - 1; s >= 0; --s) ctx->free_slots.push_back(s);
+    for (int l = 0; l <= ctx->L; ++l) {
+        ctx->sc.act[l] = reinterpret_cast<float *>(ctx->ws + ctx->lo.act[l]);
+        ctx->sc.del[l] = l ? reinterpret_cast<float *>(ctx->ws + ctx->lo.del[l]) : nullptr;
+    }
+    for (int l = 0; l < ctx->L; ++l)
+        ctx->sc.amax[l] = ctx->lay[l].type == AET_POOL ? reinterpret_cast<uint8_t *>(ctx->ws + ctx->lo.amax[l]) : nullptr;
+    ctx->sc.labels = reinterpret_cast<int32_t *>(ctx->ws + ctx->lo.labels);
+
+    hipError_t e = hipSuccess;
+    for (int r = 0; r < kRing && e == hipSuccess; ++r) {
+        e = hipHostMalloc(reinterpret_cast<void **>(&ctx->h_params[r]), (size_t)n_clients * sizeof(RoundParams), hipHostMallocDefault);
+        if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&ctx->h_arr[r]), (size_t)n_clients * max_inflight * sizeof(Arrival), hipHostMallocDefault);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_params[r], hipEventDisableTiming);
+        if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_arr[r], hipEventDisableTiming);
+    }
+    // global model and every replica start as w0
+    if (e == hipSuccess) e = hipMemcpyAsync(ctx->Wg(), w0, (size_t)ctx->P * 4, hipMemcpyHostToDevice, ctx->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // w0 is the caller's; do not keep reading it
+    for (int c = 0; c < n_clients && e == hipSuccess; ++c)
+        e = hipMemcpyAsync(ctx->Wc(c), ctx->Wg(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e != hipSuccess) {
+        const aet_status st = fail(nullptr, AET_EHIP, "aet_init: %s", hipGetErrorString(e));
+        aet_destroy(ctx);
+        return st;
+    }
+    *out = ctx;
+    return AET_OK;
+}
+
+aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *eta,
+                         const aet_delay *delay, int32_t *n_finished, int32_t *finished_client,
+                         int32_t *finished_round) {
+    if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
+    if (!thr || !eta) return fail(ctx, AET_EINVAL, "NULL argument");
+    if (thr->a < 0 || thr->b < 0 || thr->rounds < 0) return fail(ctx, AET_EINVAL, "threshold parameters must be non-negative");
+    if (thr->rounds > ctx->max_rounds) return fail(ctx, AET_EINVAL, "rounds exceeds max_rounds given to aet_init");
+    if (!(eta->eta0 > 0) || eta->beta < 0 || !std::isfinite(eta->eta0) || !std::isfinite(eta->beta) || !std::isfinite(eta->power))
+        return fail(ctx, AET_EINVAL, "bad step size parameters");
+    const int32_t dmin = delay ? delay->delay_min : 0, dmax = delay ? delay->delay_max : 0;
+    if (dmin < 0 || dmax < dmin || dmax >= ctx->inflight)
+        return fail(ctx, AET_EINVAL, "need 0 <= delay_min <= delay_max < max_inflight");
+    const int32_t *cf = delay ? delay->compute_factor : nullptr;
+    const uint8_t *st = delay ? delay->is_straggler : nullptr;
+    const int32_t d_gate = delay ? delay->d_max : -1;
+
+    // which clients run a round this tick (ascending), and with what
+    std::vector<int> act;
+    std::vector<RoundRec> rec;
+    int64_t max_m = 0;
+    for (int c = 0; c < ctx->n; ++c) {
+        if (ctx->free_at[c] > ctx->tick || ctx->i_c[c] >= thr->rounds) continue;
+        if (d_gate >= 0) {  // Synchronize: d_c = max over the other nodes of (i - H_e)
+            int64_t dc = 0;
+            for (int e = 0; e < ctx->n; ++e)
+                if (e != c) dc = std::max(dc, ctx->i_c[c] - ctx->H[e]);
+            if (dc > d_gate) continue;
+        }
+        if (cf && cf[c] < 1) return fail(ctx, AET_EINVAL, "compute_factor[%d] < 1", c);
+        const int64_t i = ctx->i_c[c];
+        const int64_t s = thr->a * i + thr->b;
+        if (s % ctx->B) return fail(ctx, AET_EINVAL, "round length s_%lld = %lld of client %d is not a multiple of batch %d", (long long)i, (long long)s, c, ctx->B);
+        const int64_t m = s / ctx->B;
+        if (m > 2147483647LL) return fail(ctx, AET_EINVAL, "round too long");
+        RoundRec r;
+        r.s = s; r.m = m; r.q0 = ctx->q_c[c]; r.t0 = ctx->t_c[c]; r.start = ctx->tick;
+        r.eta = (float)(eta->eta0 / (1.0 + eta->beta * std::pow((double)ctx->t_c[c], eta->power)));
+        const int64_t f = cf ? cf[c] : 1;
+        int64_t delta = 0;
+        if (st && st[c]) {
+            const uint64_t h = splitmix_at(splitmix_at(splitmix_at(delay->seed, kTagNet), (uint64_t)c), (uint64_t)i);
+            delta = dmin + (int64_t)(((h >> 32) * (uint64_t)(dmax - dmin + 1)) >> 32);
+        }
+        r.arrival = ctx->tick + f - 1 + delta;
+        act.push_back(c);
+        rec.push_back(r);
+        max_m = std::max(max_m, m);
+    }
+    const int nact = (int)act.size();
+    if ((int)ctx->free_slots.size() < nact)
+        return fail(ctx, AET_ENOMEM, "no free U slot: more than max_inflight messages of a client in flight");
+
+    if (nact > 0) {
+        const int ring = ctx->ring_p;
+        ctx->ring_p = (ring + 1) % kRing;
+        AET_HIP(ctx, hipEventSynchronize(ctx->ev_params[ring]));
+        RoundParams *hp = ctx->h_params[ring];
+        std::vector<int> slots(nact);
+        for (int a = 0; a < nact; ++a) {
+            const int c = act[a];
+            slots[a] = ctx->free_slots.back();
+            ctx->free_slots.pop_back();
+            RoundParams &p = hp[a];
+            p.X = ctx->shards[c].X; p.y = ctx->shards[c].y;
+            p.W = ctx->Wc(c); p.U = ctx->Uslot(slots[a]);
+            p.loss = ctx->loss_at(c, (int)ctx->i_c[c]);
+            p.key = ctx->key[c]; p.q0 = rec[a].q0; p.n_samples = (uint32_t)ctx->shards[c].n_samples;
+            p.m = (int32_t)rec[a].m; p.eta = rec[a].eta; p.client = c;
+        }
+        RoundParams *dp = reinterpret_cast<RoundParams *>(ctx->ws + ctx->lo.params);
+        AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
+        AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
+        AET_HIP(ctx, launch_begin_round(ctx->stream, dp, nact, ctx->Wg(), ctx->P));
+        for (int64_t u = 0; u < max_m; ++u)
+            AET_HIP(ctx, launch_layer_step(ctx->stream, dp, nact, (int)u, ctx->lay, ctx->L, ctx->B, ctx->sc));
+        for (int a = 0; a < nact; ++a) {
+            const int c = act[a];
+            Msg msg;
+            msg.c = c; msg.k = (int32_t)ctx->i_c[c]; msg.eta = rec[a].eta; msg.arrival = rec[a].arrival;
+            msg.slot = slots[a];
+            ctx->queue.push_back(msg);
+            ctx->recs[c].push_back(rec[a]);
+            ctx->t_c[c] += rec[a].m; ctx->q_c[c] += rec[a].s; ctx->i_c[c] += 1;
+            ctx->free_at[c] = ctx->tick + (cf ? cf[c] : 1);
+            if (finished_client) finished_client[a] = c;
+            if (finished_round) finished_round[a] = msg.k;
+        }
+    }
+    if (n_finished) *n_finished = nact;
+    return AET_OK;
+}
+
+aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applied,
+                                int32_t *applied_client, int32_t *applied_round) {
+    if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
+    if (!std::isfinite(agg_scale)) return fail(ctx, AET_EINVAL, "agg_scale is not finite");
+    std::vector<Msg> arr;
+    for (const Msg &m : ctx->queue)
+        if (m.arrival == ctx->tick) arr.push_back(m);
+    std::sort(arr.begin(), arr.end(), [](const Msg &x, const Msg &y) { return x.k != y.k ? x.k < y.k : x.c < y.c; });
+    const int na = (int)arr.size();
+    if (na > 0) {
+        const int ring = ctx->ring_a;
+        ctx->ring_a = (ring + 1) % kRing;
+        AET_HIP(ctx, hipEventSynchronize(ctx->ev_arr[ring]));
+        Arrival *ha = ctx->h_arr[ring];
+        for (int j = 0; j < na; ++j) {
+            ha[j].U = ctx->Uslot(arr[j].slot);
+            ha[j].scale = (float)((double)agg_scale * (double)arr[j].eta);
+            ha[j].pad_ = 0;
+        }
+        Arrival *da = reinterpret_cast<Arrival *>(ctx->ws + ctx->lo.arrivals);
+        AET_HIP(ctx, hipMemcpyAsync(da, ha, (size_t)na * sizeof(Arrival), hipMemcpyHostToDevice, ctx->stream));
+        AET_HIP(ctx, hipEventRecord(ctx->ev_arr[ring], ctx->stream));
+        AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->Wg(), da, na, ctx->P,
+                                          reinterpret_cast<float *>(ctx->ws + ctx->lo.partial), ctx->lo.max_chunks));
+        for (int j = 0; j < na; ++j) {
+            ctx->H[arr[j].c] += 1;
+            ctx->free_slots.push_back(arr[j].slot);
+            if (applied_client) applied_client[j] = arr[j].c;
+            if (applied_round) applied_round[j] = arr[j].k;
+        }
+        const int64_t now = ctx->tick;
+        ctx->queue.erase(std::remove_if(ctx->queue.begin(), ctx->queue.end(), [now](const Msg &m) { return m.arrival == now; }), ctx->queue.end());
+    }
+    if (n_applied) *n_applied = na;
+    ctx->tick += 1;
+    return AET_OK;
+}
+
+static aet_status copy_out(aet_ctx *ctx, const float *src, float *dst, int32_t on_host) {
+    if (on_host) {
+        AET_HIP(ctx, hipMemcpyAsync(dst, src, (size_t)ctx->P * 4, hipMemcpyDeviceToHost, ctx->stream));
+        AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    } else {
+        AET_HIP(ctx, hipMemcpyAsync(dst, src, (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    }
+    return AET_OK;
+}
+
+aet_status aet_get_U(aet_ctx *ctx, int32_t client, int32_t round, float *dst, int32_t on_host) {
+    if (!ctx) return AET_EINVAL;
+    if (!dst) return fail(ctx, AET_EINVAL, "dst is NULL");
+    for (const Msg &m : ctx->queue)
+        if (m.c == client && m.k == round) return copy_out(ctx, ctx->Uslot(m.slot), dst, on_host);
+    return fail(ctx, AET_ESTATE, "message (client %d, round %d) is not in flight", client, round);
+}
+
+aet_status aet_get_weights(aet_ctx *ctx, int32_t client, float *dst, int32_t on_host) {
+    if (!ctx) return AET_EINVAL;
+    if (!dst) return fail(ctx, AET_EINVAL, "dst is NULL");
+    if (client >= ctx->n) return fail(ctx, AET_EINVAL, "client out of range");
+    return copy_out(ctx, client < 0 ? ctx->Wg() : ctx->Wc(client), dst, on_host);
+}
+
+aet_status aet_get_round_info(aet_ctx *ctx, int32_t client, int32_t round, int64_t *ints,
+                              double *dbls) {
+    if (!ctx) return AET_EINVAL;
+    if (client < 0 || client >= ctx->n || round < 0 || round >= (int)ctx->recs[client].size())
+        return fail(ctx, AET_ESTATE, "client %d has not run round %d", client, round);
+    const RoundRec &r = ctx->recs[client][round];
+    if (ints) { ints[0] = r.s; ints[1] = r.m; ints[2] = r.q0; ints[3] = r.t0; ints[4] = r.start; ints[5] = r.arrival; }
+    if (dbls) {
+        float loss = 0.f;
+        AET_HIP(ctx, hipMemcpyAsync(&loss, ctx->loss_at(client, round), 4, hipMemcpyDeviceToHost, ctx->stream));
+        AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        dbls[0] = (double)r.eta;
+        dbls[1] = r.m > 0 ? (double)loss / (double)r.m : 0.0;
+    }
+    return AET_OK;
+}
+
+aet_status aet_debug_sample_indices(aet_ctx *ctx, int32_t client, int64_t q0, int32_t count,
+                                    int32_t *dst) {
+    if (!ctx) return AET_EINVAL;
+    if (client < 0 || client >= ctx->n || q0 < 0 || count < 0 || count > kDebugIdx || !dst)
+        return fail(ctx, AET_EINVAL, "bad argument");
+    if (count == 0) return AET_OK;
+    int32_t *d = reinterpret_cast<int32_t *>(ctx->ws + ctx->lo.debug);
+    AET_HIP(ctx, launch_debug_indices(ctx->stream, ctx->key[client], q0, count, (uint32_t)ctx->shards[client].n_samples, d));
+    AET_HIP(ctx, hipMemcpyAsync(dst, d, (size_t)count * 4, hipMemcpyDeviceToHost, ctx->stream));
+    AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return AET_OK;
+}
+
+int32_t aet_all_done(const aet_ctx *ctx, int32_t rounds) {
+    if (!ctx || !ctx->queue.empty()) return 0;
+    for (int c = 0; c < ctx->n; ++c)
+        if (ctx->i_c[c] < rounds) return 0;
+    return 1;
+}
+
+int64_t aet_tick(const aet_ctx *ctx) { return ctx ? ctx->tick : -1; }
+int64_t aet_history(const aet_ctx *ctx, int32_t client) {
+    return (ctx && client >= 0 && client < ctx->n) ? ctx->H[client] : -1;
+}
+int64_t aet_inflight(const aet_ctx *ctx) { return ctx ? (int64_t)ctx->queue.size() : -1; }
+
+aet_status aet_synchronize(aet_ctx *ctx) {
+    if (!ctx) return AET_EINVAL;
+    AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return AET_OK;
+}
+
+const char *aet_last_error(const aet_ctx *ctx) { return ctx ? ctx->err.c_str() : g_init_error.c_str(); }
+
+void aet_destroy(aet_ctx *ctx) {
+    if (!ctx) return;
+    (void)hipStreamSynchronize(ctx->stream);
+    for (int r = 0; r < kRing; ++r) {
+        if (ctx->h_params[r]) (void)hipHostFree(ctx->h_params[r]);
+        if (ctx->h_arr[r]) (void)hipHostFree(ctx->h_arr[r]);
+        if (ctx->ev_params[r]) (void)hipEventDestroy(ctx->ev_params[r]);
+        if (ctx->ev_arr[r]) (void)hipEventDestroy(ctx->ev_arr[r]);
+    }
+    delete ctx;
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Internal declarations shared by the host scheduler and the kernel launchers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace aet {
+
+// Resolved geometry of one layer (activations are C,H,W per sample).
+struct LayerGeom {
+    int type, relu, k, pad;
+    int ic, ih, iw, oc, oh, ow;
+    int64_t w_off, b_off;       // offsets into the flat parameter vector
+    int64_t in_size, out_size;  // floats per sample
+};
+
+// Everything a kernel needs to know about one client's round of this tick.
+// One record per ACTIVE client; the array lives in device memory.
+struct RoundParams {
+    const float *X;      // shard rows
+    const int32_t *y;    // shard labels
+    float *W;            // the client's replica w_c (P floats)
+    float *U;            // the slot that receives this round's gradient sum
+    float *loss;         // accumulates the per-recursion mean loss
+    uint64_t key;        // SplitMix64 stream key of (seed, client)
+    int64_t q0;          // sample counter at the start of the round
+    uint32_t n_samples;  // rows in the shard
+    int32_t m;           // recursions in this round
+    float eta;           // round step size
+    int32_t client;
+};
+
+// One arriving message for the server step: Wg -= scale * U.
+struct Arrival {
+    const float *U;
+    float scale;
+    int32_t pad_;
+};
+
+// Device scratch of the layer-by-layer engine; all sized for n_clients * batch samples.
+struct LayerScratch {
+    float *act[17];     // act[0] = gathered inputs, act[l+1] = output of layer l
+    float *del[17];     // d loss / d act[l] (l >= 1)
+    uint8_t *amax[16];  // pool layers: which of the 4 window elements was the maximum
+    int32_t *labels;    // [n_clients][batch]
+};
+
+// ---- launchers (each returns the launch status) --------------------------------------
+hipError_t launch_begin_round(hipStream_t s, const RoundParams *dp, int nact, const float *Wg,
+                              int64_t P);
+hipError_t launch_layer_step(hipStream_t s, const RoundParams *dp, int nact, int u,
+                             const LayerGeom *lay, int L, int B, const LayerScratch &sc);
+hipError_t launch_server_reduce(hipStream_t s, float *Wg, const Arrival *darr, int n_arr,
+                                int64_t P, float *partial, int max_chunks);
+hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
+                                uint32_t n_samples, int32_t *dst);
+// chunks of arrivals the two-stage server reduce uses for n_arr arrivals
+int server_reduce_chunks(int n_arr, int64_t P);
+
+}  // namespace aet

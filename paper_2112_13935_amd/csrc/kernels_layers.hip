@@ -1,0 +1,425 @@
+// Layer-by-layer engine: one SGD recursion of every active client as a short sequence of
+// kernels, each batched over the clients (blockIdx.z) and the mini-batch.  It runs any
+// model the ABI can describe; the fused persistent kernels for single-dense and
+// dense-ReLU-dense models take over for those shapes.
+//
+// One recursion (Algorithm 2, MainComputeNode, body of the while loop), for client c:
+//   draw B sample indices and gather the rows      -> k_gather
+//   forward pass, layer by layer                   -> k_conv_fwd / k_pool_fwd / k_dense_fwd
+//   softmax cross-entropy, d loss / d logits       -> k_softmax_ce
+//   backward pass; each parameter layer first hands the gradient to the layer below
+//   (k_*_bwd_data, which reads the not-yet-updated weights) and then forms its own
+//   gradient g and applies  w <- w - eta g,  U <- U + g  in the same kernel
+//   (k_*_bwd_weight), so g never goes to memory.
+// Clients whose round has fewer recursions than the step counter simply exit.
+#include "aet_device.h"
+#include "aet_internal.h"
+
+namespace aet {
+
+#define AET_RETURN_IF(e)                 \
+    do {                                 \
+        hipError_t e__ = (e);            \
+        if (e__ != hipSuccess) return e__; \
+    } while (0)
+
+__global__ void k_begin_round(const RoundParams *__restrict__ rp, const float *__restrict__ Wg,
+                              int64_t P) {
+    const RoundParams p = rp[blockIdx.y];
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < P) {
+        p.W[i] = Wg[i];  // adopt the broadcast global model
+        p.U[i] = 0.f;
+    }
+    if (i == 0) *p.loss = 0.f;
+}
+
+// act0[a][b][:] = X_c[row(q0 + u*B + b)][:]
+__global__ void k_gather(const RoundParams *__restrict__ rp, int u, int B, int D,
+                         float *__restrict__ act0, int32_t *__restrict__ labels) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int b = blockIdx.y;
+    const uint32_t row = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)u * B + b), p.n_samples);
+    const int d = blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t o = ((int64_t)blockIdx.z * B + b);
+    if (d < D) act0[o * D + d] = p.X[(int64_t)row * D + d];
+    if (d == 0) labels[o] = p.y[row];
+}
+
+// out[a][b][o] = relu?(bias[o] + sum_k W[o][k] in[a][b][k]); one wave per output feature
+__global__ void __launch_bounds__(256)
+k_dense_fwd(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
+            int64_t b_off, int relu, const float *__restrict__ in, float *__restrict__ out) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int o = blockIdx.x * 4 + wave;
+    if (o >= O) return;
+    const float *w = p.W + w_off + (int64_t)o * K;
+    const float bias = p.W[b_off + o];
+    const float *inb = in + (int64_t)blockIdx.z * B * K;
+    float *outb = out + (int64_t)blockIdx.z * B * O;
+    for (int b = 0; b < B; ++b) {
+        float s = 0.f;
+        for (int k = lane; k < K; k += 64) s += w[k] * inb[(int64_t)b * K + k];
+        s = wave_sum(s) + bias;
+        if (relu && !(s > 0.f)) s = 0.f;
+        if (lane == 0) outb[(int64_t)b * O + o] = s;
+    }
+}
+
+// din[a][b][k] = sum_o W[o][k] dout[a][b][o], masked by the ReLU of the layer below
+__global__ void __launch_bounds__(256)
+k_dense_bwd_data(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
+                 const float *__restrict__ dout, float *__restrict__ din,
+                 const float *__restrict__ mask_src) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    const int b = blockIdx.y;
+    const float *w = p.W + w_off;
+    const float *d = dout + ((int64_t)blockIdx.z * B + b) * O;
+    float s = 0.f;
+    for (int o = 0; o < O; ++o) s += w[(int64_t)o * K + k] * d[o];
+    const int64_t i = ((int64_t)blockIdx.z * B + b) * K + k;
+    if (mask_src && !(mask_src[i] > 0.f)) s = 0.f;
+    din[i] = s;
+}
+
+// g[o][k] = (1/B) sum_b dout[b][o] in[b][k];  W -= eta g;  U += g   (and the bias)
+__global__ void __launch_bounds__(256)
+k_dense_bwd_weight(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
+                   int64_t b_off, const float *__restrict__ in, const float *__restrict__ dout) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= K) return;
+    const int o = blockIdx.y;
+    const float *inb = in + (int64_t)blockIdx.z * B * K;
+    const float *d = dout + (int64_t)blockIdx.z * B * O;
+    const float invB = 1.0f / (float)B;
+    float g = 0.f, gb = 0.f;
+    for (int b = 0; b < B; ++b) {
+        const float dv = d[(int64_t)b * O + o];
+        g += dv * inb[(int64_t)b * K + k];
+        gb += dv;
+    }
+    g *= invB;
+    const int64_t wi = w_off + (int64_t)o * K + k;
+    p.W[wi] -= p.eta * g;
+    p.U[wi] += g;
+    if (k == 0) {
+        gb *= invB;
+        p.W[b_off + o] -= p.eta * gb;
+        p.U[b_off + o] += gb;
+    }
+}
+
+template <int KS>
+__global__ void __launch_bounds__(256)
+k_conv_fwd(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
+           const float *__restrict__ in, float *__restrict__ out) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= g.oc * g.oh * g.ow) return;
+    const int ox = idx % g.ow, oy = (idx / g.ow) % g.oh, co = idx / (g.ow * g.oh);
+    const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
+    const float *x = in + sample * g.in_size;
+    const float *w = p.W + g.w_off + (int64_t)co * g.ic * KS * KS;
+    float s = p.W[g.b_off + co];
+    for (int ci = 0; ci < g.ic; ++ci) {
+#pragma unroll
+        for (int ky = 0; ky < KS; ++ky) {
+            const int iy = oy + ky - g.pad;
+            if (iy < 0 || iy >= g.ih) continue;
+#pragma unroll
+            for (int kx = 0; kx < KS; ++kx) {
+                const int ix = ox + kx - g.pad;
+                if (ix < 0 || ix >= g.iw) continue;
+                s += w[(ci * KS + ky) * KS + kx] * x[((int64_t)ci * g.ih + iy) * g.iw + ix];
+            }
+        }
+    }
+    if (g.relu && !(s > 0.f)) s = 0.f;
+    out[sample * g.out_size + idx] = s;
+}
+
+// din[ci][iy][ix] = sum_{co,ky,kx} W[co][ci][ky][kx] dout[co][iy-ky+pad][ix-kx+pad]
+template <int KS>
+__global__ void __launch_bounds__(256)
+k_conv_bwd_data(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
+                const float *__restrict__ dout, float *__restrict__ din,
+                const float *__restrict__ mask_src) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= g.ic * g.ih * g.iw) return;
+    const int ix = idx % g.iw, iy = (idx / g.iw) % g.ih, ci = idx / (g.iw * g.ih);
+    const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
+    const float *d = dout + sample * g.out_size;
+    const float *w = p.W + g.w_off;
+    float s = 0.f;
+    for (int co = 0; co < g.oc; ++co) {
+#pragma unroll
+        for (int ky = 0; ky < KS; ++ky) {
+            const int oy = iy - ky + g.pad;
+            if (oy < 0 || oy >= g.oh) continue;
+#pragma unroll
+            for (int kx = 0; kx < KS; ++kx) {
+                const int ox = ix - kx + g.pad;
+                if (ox < 0 || ox >= g.ow) continue;
+                s += w[(((int64_t)co * g.ic + ci) * KS + ky) * KS + kx] *
+                     d[((int64_t)co * g.oh + oy) * g.ow + ox];
+            }
+        }
+    }
+    const int64_t i = sample * g.in_size + idx;
+    if (mask_src && !(mask_src[i] > 0.f)) s = 0.f;
+    din[i] = s;
+}
+
+// One block per (cin, cout) filter plane: g[ky][kx] = (1/B) sum_{b,oy,ox} dout * in, then
+// the fused update.  The cin == 0 block also does the bias of its output channel.
+template <int KS>
+__global__ void __launch_bounds__(256)
+k_conv_bwd_weight(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
+                  const float *__restrict__ in, const float *__restrict__ dout) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int ci = blockIdx.x, co = blockIdx.y;
+    constexpr int NA = KS * KS + 1;
+    float acc[NA];
+#pragma unroll
+    for (int j = 0; j < NA; ++j) acc[j] = 0.f;
+    const int plane = g.oh * g.ow;
+    const int total = B * plane;
+    const float *inb = in + (int64_t)blockIdx.z * B * g.in_size + (int64_t)ci * g.ih * g.iw;
+    const float *db = dout + (int64_t)blockIdx.z * B * g.out_size + (int64_t)co * plane;
+    for (int t = threadIdx.x; t < total; t += blockDim.x) {
+        const int b = t / plane, r = t - b * plane;
+        const int oy = r / g.ow, ox = r - oy * g.ow;
+        const float d = db[(int64_t)b * g.out_size + r];
+        const float *x = inb + (int64_t)b * g.in_size;
+        acc[KS * KS] += d;
+#pragma unroll
+        for (int ky = 0; ky < KS; ++ky) {
+            const int iy = oy + ky - g.pad;
+            if (iy < 0 || iy >= g.ih) continue;
+#pragma unroll
+            for (int kx = 0; kx < KS; ++kx) {
+                const int ix = ox + kx - g.pad;
+                if (ix < 0 || ix >= g.iw) continue;
+                acc[ky * KS + kx] += d * x[iy * g.iw + ix];
+            }
+        }
+    }
+    __shared__ float red[4][NA];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int j = 0; j < NA; ++j) {
+        const float v = wave_sum(acc[j]);
+        if (lane == 0) red[wave][j] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x < NA) {
+        const int j = threadIdx.x;
+        const float gsum = (red[0][j] + red[1][j] + red[2][j] + red[3][j]) * (1.0f / (float)B);
+        if (j < KS * KS) {
+            const int64_t wi = g.w_off + ((int64_t)co * g.ic + ci) * KS * KS + j;
+            p.W[wi] -= p.eta * gsum;
+            p.U[wi] += gsum;
+        } else if (ci == 0) {
+            p.W[g.b_off + co] -= p.eta * gsum;
+            p.U[g.b_off + co] += gsum;
+        }
+    }
+}
+
+// 2x2 / stride 2 max pooling; the first maximum in row-major window order wins
+__global__ void __launch_bounds__(256)
+k_pool_fwd(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
+           const float *__restrict__ in, float *__restrict__ out, uint8_t *__restrict__ amax) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= g.oc * g.oh * g.ow) return;
+    const int ox = idx % g.ow, oy = (idx / g.ow) % g.oh, c = idx / (g.ow * g.oh);
+    const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
+    const float *x = in + sample * g.in_size + ((int64_t)c * g.ih + 2 * oy) * g.iw + 2 * ox;
+    float best = x[0];
+    int which = 0;
+    if (x[1] > best) { best = x[1]; which = 1; }
+    if (x[g.iw] > best) { best = x[g.iw]; which = 2; }
+    if (x[g.iw + 1] > best) { best = x[g.iw + 1]; which = 3; }
+    out[sample * g.out_size + idx] = best;
+    amax[sample * g.out_size + idx] = (uint8_t)which;
+}
+
+__global__ void __launch_bounds__(256)
+k_pool_bwd(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
+           const float *__restrict__ dout, const uint8_t *__restrict__ amax,
+           float *__restrict__ din, const float *__restrict__ mask_src) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= g.oc * g.oh * g.ow) return;
+    const int ox = idx % g.ow, oy = (idx / g.ow) % g.oh, c = idx / (g.ow * g.oh);
+    const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
+    const float d = dout[sample * g.out_size + idx];
+    const int which = amax[sample * g.out_size + idx];
+    const int64_t base = sample * g.in_size + ((int64_t)c * g.ih + 2 * oy) * g.iw + 2 * ox;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int64_t i = base + (j >> 1) * g.iw + (j & 1);
+        float v = (j == which) ? d : 0.f;
+        if (mask_src && !(mask_src[i] > 0.f)) v = 0.f;
+        din[i] = v;
+    }
+}
+
+// loss and d loss / d logits of the mini-batch; one block per client
+__global__ void __launch_bounds__(256)
+k_softmax_ce(const RoundParams *__restrict__ rp, int u, int B, int C,
+             const float *__restrict__ logits, const int32_t *__restrict__ labels,
+             float *__restrict__ dz) {
+    const RoundParams p = rp[blockIdx.x];
+    if (u >= p.m) return;
+    __shared__ float sl[256];
+    const int b = threadIdx.x;
+    float loss = 0.f;
+    if (b < B) {
+        const float *z = logits + ((int64_t)blockIdx.x * B + b) * C;
+        float *d = dz + ((int64_t)blockIdx.x * B + b) * C;
+        const int lab = labels[(int64_t)blockIdx.x * B + b];
+        float zmax = z[0];
+        for (int j = 1; j < C; ++j) zmax = fmaxf(zmax, z[j]);
+        float sum = 0.f;
+        for (int j = 0; j < C; ++j) sum += expf(z[j] - zmax);
+        const float lse = zmax + logf(sum);
+        loss = lse - z[lab];
+        for (int j = 0; j < C; ++j) d[j] = expf(z[j] - lse) - (j == lab ? 1.f : 0.f);
+    }
+    sl[b] = loss;
+    __syncthreads();
+    if (b == 0) {
+        float s = 0.f;
+        for (int j = 0; j < B; ++j) s += sl[j];
+        *p.loss += s / (float)B;
+    }
+}
+
+hipError_t launch_begin_round(hipStream_t s, const RoundParams *dp, int nact, const float *Wg,
+                              int64_t P) {
+    if (nact <= 0) return hipSuccess;
+    dim3 grid((unsigned)((P + 255) / 256), (unsigned)nact);
+    k_begin_round<<<grid, 256, 0, s>>>(dp, Wg, P);
+    return hipGetLastError();
+}
+
+template <int KS>
+static hipError_t conv_step(hipStream_t s, const RoundParams *dp, int nact, int u, int B,
+                            const LayerGeom &g, int which, const float *a, const float *b,
+                            float *c, const float *mask) {
+    if (which == 0) {
+        dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
+        k_conv_fwd<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, c);
+    } else if (which == 1) {
+        dim3 grid((unsigned)((g.in_size + 255) / 256), B, nact);
+        k_conv_bwd_data<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, c, mask);
+    } else {
+        dim3 grid(g.ic, g.oc, nact);
+        k_conv_bwd_weight<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, b);
+    }
+    return hipGetLastError();
+}
+
+static hipError_t conv_dispatch(int ks, hipStream_t s, const RoundParams *dp, int nact, int u,
+                                int B, const LayerGeom &g, int which, const float *a,
+                                const float *b, float *c, const float *mask) {
+    switch (ks) {
+        case 1: return conv_step<1>(s, dp, nact, u, B, g, which, a, b, c, mask);
+        case 2: return conv_step<2>(s, dp, nact, u, B, g, which, a, b, c, mask);
+        case 3: return conv_step<3>(s, dp, nact, u, B, g, which, a, b, c, mask);
+        case 5: return conv_step<5>(s, dp, nact, u, B, g, which, a, b, c, mask);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_layer_step(hipStream_t s, const RoundParams *dp, int nact, int u,
+                             const LayerGeom *lay, int L, int B, const LayerScratch &sc) {
+    if (nact <= 0) return hipSuccess;
+    {
+        const int D = (int)lay[0].in_size;
+        dim3 grid((D + 255) / 256, B, nact);
+        k_gather<<<grid, 256, 0, s>>>(dp, u, B, D, sc.act[0], sc.labels);
+        AET_RETURN_IF(hipGetLastError());
+    }
+    for (int l = 0; l < L; ++l) {
+        const LayerGeom &g = lay[l];
+        if (g.type == 0) {
+            AET_RETURN_IF(conv_dispatch(g.k, s, dp, nact, u, B, g, 0, sc.act[l], nullptr,
+                                        sc.act[l + 1], nullptr));
+        } else if (g.type == 1) {
+            dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
+            k_pool_fwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.act[l], sc.act[l + 1], sc.amax[l]);
+            AET_RETURN_IF(hipGetLastError());
+        } else {
+            dim3 grid((g.oc + 3) / 4, 1, nact);
+            k_dense_fwd<<<grid, 256, 0, s>>>(dp, u, B, (int)g.in_size, g.oc, g.w_off, g.b_off,
+                                             g.relu, sc.act[l], sc.act[l + 1]);
+            AET_RETURN_IF(hipGetLastError());
+        }
+    }
+    k_softmax_ce<<<nact, 256, 0, s>>>(dp, u, B, lay[L - 1].oc, sc.act[L], sc.labels, sc.del[L]);
+    AET_RETURN_IF(hipGetLastError());
+    for (int l = L - 1; l >= 0; --l) {
+        const LayerGeom &g = lay[l];
+        // the gradient handed to act[l] is masked by the ReLU of the layer that produced it
+        const float *mask = (l > 0 && lay[l - 1].relu) ? sc.act[l] : nullptr;
+        if (g.type == 0) {
+            if (l > 0)
+                AET_RETURN_IF(conv_dispatch(g.k, s, dp, nact, u, B, g, 1, sc.del[l + 1], nullptr,
+                                            sc.del[l], mask));
+            AET_RETURN_IF(conv_dispatch(g.k, s, dp, nact, u, B, g, 2, sc.act[l], sc.del[l + 1],
+                                        nullptr, nullptr));
+        } else if (g.type == 1) {
+            if (l > 0) {
+                dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
+                k_pool_bwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.del[l + 1], sc.amax[l], sc.del[l],
+                                                mask);
+                AET_RETURN_IF(hipGetLastError());
+            }
+        } else {
+            const int K = (int)g.in_size;
+            if (l > 0) {
+                dim3 grid((K + 255) / 256, B, nact);
+                k_dense_bwd_data<<<grid, 256, 0, s>>>(dp, u, B, K, g.oc, g.w_off, sc.del[l + 1],
+                                                      sc.del[l], mask);
+                AET_RETURN_IF(hipGetLastError());
+            }
+            dim3 grid((K + 255) / 256, g.oc, nact);
+            k_dense_bwd_weight<<<grid, 256, 0, s>>>(dp, u, B, K, g.oc, g.w_off, g.b_off, sc.act[l],
+                                                    sc.del[l + 1]);
+            AET_RETURN_IF(hipGetLastError());
+        }
+    }
+    return hipSuccess;
+}
+
+__global__ void k_debug_indices(uint64_t key, int64_t q0, int count, uint32_t n_samples,
+                                int32_t *__restrict__ dst) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) dst[i] = (int32_t)sample_row(key, (uint64_t)(q0 + i), n_samples);
+}
+
+hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
+                                uint32_t n_samples, int32_t *dst) {
+    if (count <= 0) return hipSuccess;
+    k_debug_indices<<<(count + 255) / 256, 256, 0, s>>>(key, q0, count, n_samples, dst);
+    return hipGetLastError();
+}
+
+}  // namespace aet

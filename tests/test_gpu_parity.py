@@ -1,0 +1,191 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Run with  -m gpu  on an MI355X."""
+import numpy as np
+import pytest
+
+import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the parity tests need the HIP path")
+    from paper_2112_13935_amd import load_library
+    load_library()
+    from paper_2112_13935_amd.runner import Run
+    return Run
+
+
+def _both(gpu, wl, **kw):
+    from oracle import Oracle
+    return gpu(wl, **kw), Oracle(wl, "f64")
+
+
+def report(name, worst):
+    print(f"\n[parity] {name}: " + ", ".join(f"{k} {v:.2e}" for k, v in worst.items()), flush=True)
+
+
+def test_sample_indices_bit_exact(gpu, oracle_libs):
+    lib = oracle_libs.load("f64")
+    wl = W.config1(n_clients=5, n_per=1000, d=16, rounds=2)
+    sizes = [1, 2, 500, 999, 1000]
+    for c, N in enumerate(sizes):
+        wl.X[c] = wl.X[c][:N].copy()
+        wl.y[c] = wl.y[c][:N].copy()
+    run = gpu(wl)
+    for c, N in enumerate(sizes):
+        for q0, count in ((0, 4096), (123456789012, 1000), (2**40 + 5, 257), (7, 1)):
+            got = run.lib.aet_debug_sample_indices(c, q0, count)
+            want = np.array([lib.orc_sample_index(wl.seed, c, q0 + j, N) for j in range(count)],
+                            dtype=np.int32)
+            assert np.array_equal(got, want), (c, N, q0)
+    run.close()
+
+
+def small_cases():
+    cases = {}
+    wl = W.config1(n_clients=5, n_per=60, d=37, rounds=6, a=3, b=2)
+    wl.compute_factor = np.array([1, 2, 1, 3, 1], dtype=np.int32)
+    wl.is_straggler = np.array([0, 0, 1, 0, 1], dtype=np.uint8)
+    wl.delay_min, wl.delay_max, wl.delay_seed = 1, 3, 77
+    cases["softmax_ragged_delays"] = wl
+    wl = W.config2(n_clients=5, n_total=5 * 70, d=50, hidden=24, batch=4, rounds=6, a=4, b=8)
+    wl.is_straggler = np.array([1, 0, 0, 1, 0], dtype=np.uint8)
+    wl.delay_min, wl.delay_max, wl.delay_seed = 0, 2, 78
+    cases["mlp_ragged_stragglers"] = wl
+    wl = W.config3(n_clients=6, n_per=40, hw=16, batch=4, rounds=4, a=4, b=8)
+    wl.compute_factor = np.array([1, 1, 2, 1, 4, 1], dtype=np.int32)
+    cases["lenet16_factors_stragglers"] = wl
+    wl = W.config4(n_clients=3, n_per=40, hw=8, width=8, fc=32, batch=4, rounds=3, a=4, b=8)
+    cases["cnn8_factors"] = wl
+    wl = W.config1(n_clients=3, n_per=30, d=20, rounds=4, a=5, b=0)
+    cases["softmax_empty_first_round"] = wl
+    wl = W.config2(n_clients=4, n_total=200, d=30, hidden=10, batch=2, rounds=5, a=2, b=2)
+    wl.compute_factor = np.array([1, 3, 1, 2], dtype=np.int32)
+    wl.d_max = 1
+    cases["mlp_delay_checkpoint_d1"] = wl
+    wl = W.config1(n_clients=1, n_per=50, d=10, rounds=5, a=2, b=3)
+    wl.agg_scale = 1.0
+    cases["one_client_plain_sgd"] = wl
+    return cases
+
+
+@pytest.mark.parametrize("name", list(small_cases()))
+def test_small_cases_every_tick(gpu, oracle_libs, name):
+    """Sizes the oracle finishes at once, ragged in every dimension (feature counts that
+    are no multiple of the wavefront, odd client counts), with delays, compute factors,
+    stragglers, an empty round, the delay checkpoint and the one-client case; U, w_c, the
+    losses and the global model are compared after every tick."""
+    from parity import lockstep
+    wl = small_cases()[name]
+    run, orc = _both(gpu, wl)
+    worst = lockstep(wl, run, orc)
+    report(name, worst)
+    run.close()
+
+
+def test_U_invariant_on_gpu(gpu):
+    """w_start - w_end = eta_i U_i holds for the GPU's own numbers (fp32 rounding)."""
+    wl = small_cases()["mlp_ragged_stragglers"]
+    run = gpu(wl)
+    while not run.lib.aet_all_done(wl.rounds):
+        w_start = run.lib.aet_get_weights(-1).astype(np.float64)
+        for c, k in run.run_round():
+            info = run.lib.aet_get_round_info(c, k)
+            U = run.lib.aet_get_U(c, k).astype(np.float64)
+            w_end = run.lib.aet_get_weights(c).astype(np.float64)
+            err = np.abs((w_start - w_end) / info["eta"] - U).max()
+            assert err <= 1e-4 * max(1.0, np.abs(U).max())
+        run.server_aggregate()
+    run.close()
+
+
+def test_deterministic_rerun(gpu):
+    """Two runs of the same workload give bit-identical results."""
+    wl = small_cases()["lenet16_factors_stragglers"]
+    out = []
+    for _ in range(2):
+        run = gpu(wl)
+        run.run_all()
+        out.append(run.lib.aet_get_weights(-1))
+        run.close()
+    assert np.array_equal(out[0], out[1])
+
+
+def test_config1_full(gpu, oracle_libs):
+    from parity import lockstep
+    wl = W.config1()
+    run, orc = _both(gpu, wl)
+    report("config 1 (4 clients, 20 rounds)", lockstep(wl, run, orc))
+    run.close()
+
+
+def test_config2_full_clients_20_rounds(gpu, oracle_libs):
+    from parity import lockstep
+    wl = W.config2()
+    run, orc = _both(gpu, wl)
+    report("config 2 (16 clients, 20 rounds)", lockstep(wl, run, orc, rounds=20, check_every_tick=False))
+    run.close()
+
+
+def test_config3_full_clients_20_rounds(gpu, oracle_libs):
+    from parity import lockstep
+    wl = W.config3()
+    run, orc = _both(gpu, wl)
+    report("config 3 (64 clients, 20 rounds)", lockstep(wl, run, orc, rounds=20, check_every_tick=False))
+    run.close()
+
+
+def test_config4_full_layer_shapes(gpu, oracle_libs):
+    """The full 32x32x3 network and mini-batch 64, at 3 clients and 2 rounds (the oracle
+    needs 0.1 s per sample for this model)."""
+    from parity import lockstep
+    wl = W.config4(n_clients=3, n_per=200, rounds=2)
+    wl.compute_factor = np.array([1, 2, 1], dtype=np.int32)
+    run, orc = _both(gpu, wl)
+    report("config 4 shapes (3 clients, 2 rounds)", lockstep(wl, run, orc))
+    run.close()
+
+
+def test_config4_reduced_20_rounds(gpu, oracle_libs):
+    """Same architecture at 16x16 images and half width, 8 clients with compute factors,
+    20 rounds."""
+    from parity import lockstep
+    wl = W.config4(n_clients=8, n_per=300, hw=16, width=16, fc=64, batch=16, rounds=20, a=16, b=32)
+    run, orc = _both(gpu, wl)
+    report("config 4 reduced (8 clients, 20 rounds)", lockstep(wl, run, orc, check_every_tick=False))
+    run.close()
+
+
+def test_config5_full_clients_8_rounds(gpu, oracle_libs):
+    """All 1,024 clients and 3,072 features; 8 rounds (stragglers with delays up to 5
+    ticks are in flight throughout)."""
+    from parity import lockstep
+    wl = W.config5(rounds=8)
+    run, orc = _both(gpu, wl)
+    report("config 5 (1024 clients, 8 rounds)",
+           lockstep(wl, run, orc, check_every_tick=False, check_clients=set(range(0, 1024, 37))))
+    run.close()
+
+
+def test_error_paths(gpu):
+    """Bad arguments come back as status codes and leave the context usable."""
+    from paper_2112_13935_amd import AetError
+    wl = small_cases()["mlp_ragged_stragglers"]
+    run = gpu(wl)
+    with pytest.raises(AetError) as e:
+        run.lib.aet_run_round(4, 6, wl.rounds, wl.eta0, wl.beta, wl.power)   # 6 % batch(4) != 0
+    assert e.value.status == -1
+    with pytest.raises(AetError):
+        run.lib.aet_run_round(4, 8, wl.rounds, -1.0, 0.0, 1.0)
+    with pytest.raises(AetError):
+        run.lib.aet_run_round(4, 8, wl.rounds, 0.01, 0.0, 1.0, delay_min=2, delay_max=1)
+    with pytest.raises(AetError) as e:
+        run.lib.aet_get_U(0, 0)
+    assert e.value.status == -4
+    assert run.lib.aet_tick() == 0
+    assert run.run_round() == [(c, 0) for c in range(5)]
+    run.close()
