@@ -1,0 +1,178 @@
+#!/usr/bin/env python3
+"""Benchmark of the AET-SGD hot path on one MI355X.
+
+A "step" is one whole job of the workload: every client's local rounds (threshold
+s_i = a*i + b, all rounds), every server aggregation under the delay schedule, until the
+message queue has drained.  Inputs (shards, initial model) are resident in HBM before the
+timed region; the timed region holds K jobs, each restarted with aet_reset.
+
+Prints ONE JSON line with the throughput in client-samples/s, the roofline record of the
+dominant kernel (its launches are timed live with HIP events on the library's stream),
+and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0           # MI355X published HBM3E bandwidth
+FP32_MFMA_PEAK_TFLOPS = 157.3   # MI355X published dense fp32 matrix rate
+
+
+def per_step_bytes(model, fam_name):
+    """Algorithmic bytes one client moves in one SGD recursion inside the kernels of one
+    family (replicas and U live in HBM and are touched every recursion)."""
+    import workloads as W
+    B = model.batch
+    shp = model.shapes()
+    D = model.in_size()
+    P = model.n_params()
+    total = 0
+    if fam_name in ("k_softmax_round", "k_mlp_round"):
+        # read+write W, read+write U, the mini-batch rows and labels
+        return 16 * P + B * (4 * D + 4)
+    if fam_name == "k_gather":
+        return B * (8 * D + 8)
+    if fam_name == "k_softmax_ce":
+        return B * (8 * model.n_classes() + 4)
+    for L, sl, (c, h, w), (oc, oh, ow) in zip(model.layers, model.param_slices(), shp[:-1], shp[1:]):
+        n_in, n_out = c * h * w, oc * oh * ow
+        if L.type == W.DENSE:
+            nw = sl[1] + sl[3]
+            if fam_name == "k_dense_fwd":
+                total += 4 * nw + 4 * B * (n_in + n_out)
+            elif fam_name == "k_dense_bwd_data":
+                total += 4 * sl[1] + 4 * B * (n_in + n_out)
+            elif fam_name == "k_dense_bwd_weight":
+                total += 16 * nw + 4 * B * (n_in + n_out)
+        elif L.type == W.CONV:
+            nw = sl[1] + sl[3]
+            if fam_name == "k_conv_fwd":
+                total += 4 * nw + 4 * B * (n_in + n_out)
+            elif fam_name == "k_conv_bwd_data":
+                total += 4 * sl[1] + 4 * B * (n_in + n_out)
+            elif fam_name == "k_conv_bwd_weight":
+                total += 16 * nw + 4 * B * (n_in + n_out)
+        else:
+            if fam_name == "k_pool_fwd":
+                total += B * (4 * n_in + 5 * n_out)
+            elif fam_name == "k_pool_bwd":
+                total += B * (4 * n_in + 5 * n_out)
+    return total
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """The fp64 oracle as it stands, on the host cores, for about budget_s seconds of the
+    same workload from its start (whole ticks); client-samples per second."""
+    from oracle import Oracle
+    orc = Oracle(wl, "f64")
+    threads = min(wl.n_clients, int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1)))
+    done = 0
+    ticks = 0
+    t0 = time.perf_counter()
+    while not orc.all_done() and time.perf_counter() - t0 < budget_s:
+        for c, k in orc.run_round():
+            done += orc.round_info(c, k)["s"]
+        orc.server_aggregate()
+        ticks += 1
+    dt = time.perf_counter() - t0
+    orc.close()
+    return dict(value=done / dt, unit="client-samples/s", cores=threads, kind="oracle",
+                sample=f"first {ticks} ticks of the same workload ({done} client-samples, "
+                       f"{dt:.1f} s, fp64, one thread per client)")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=3)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the MLP)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import workloads as W
+    from paper_2112_13935_amd.runner import Run
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+
+    wl = W.CONFIGS[args.config]()
+    run = Run(wl)
+    names = run.lib.profile_family_names()
+    total_samples = wl.total_client_samples()
+    total_steps = wl.n_clients * sum((wl.a * i + wl.b) // wl.model.batch for i in range(wl.rounds))
+
+    def job():
+        run.lib.aet_reset()
+        return run.run_all()
+
+    for _ in range(max(args.warmup, 0)):
+        job()
+    run.lib.aet_synchronize()
+
+    # which kernel family dominates: one untimed job with every family's launches timed
+    run.lib.aet_profile_enable(-1, True)
+    job()
+    fam_ms = [run.lib.aet_profile_read(f) for f in range(len(names))]
+    run.lib.aet_profile_enable(-1, False)
+    dom = int(np.argmax([ms for _, ms in fam_ms]))
+    share = fam_ms[dom][1] / max(sum(ms for _, ms in fam_ms), 1e-12)
+
+    run.lib.aet_profile_enable(dom, True)
+    run.lib.aet_synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ticks = 0
+    for _ in range(args.steps):
+        ticks = job()
+    run.lib.aet_synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    launches, kernel_ms = run.lib.aet_profile_read(dom)
+    run.lib.aet_profile_enable(dom, False)
+
+    ms_per_step = dt * 1e3 / args.steps
+    value = total_samples * args.steps / dt
+    fam = names[dom]
+    bytes_per_job = per_step_bytes(wl.model, fam) * total_steps
+    launches_per_job = launches / args.steps
+    avg_launch_ms = kernel_ms / max(launches, 1)
+    achieved = (bytes_per_job / launches_per_job) / (avg_launch_ms * 1e-3) / 1e9
+    out = {
+        "metric": "client SGD samples/sec (all clients, 1 GPU)",
+        "value": value, "unit": "client-samples/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": wl.name, "n_clients": wl.n_clients, "rounds": wl.rounds,
+                   "batch": wl.model.batch, "threshold": f"s_i = {wl.a}*i + {wl.b}",
+                   "client_samples_per_step": total_samples, "ticks_per_step": ticks,
+                   "params": wl.model.n_params(), "agg_scale": wl.agg_scale},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": fam,
+                     "avg_launch_us": avg_launch_ms * 1e3, "launches_per_step": launches_per_job,
+                     "algorithmic_bytes_per_launch": bytes_per_job / launches_per_job,
+                     "share_of_kernel_time": share},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    run.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -197,6 +197,24 @@ int64_t aet_inflight(const aet_ctx *ctx);
 /* Block until everything enqueued so far has finished. */
 aet_status aet_synchronize(aet_ctx *ctx);
 
+/* Restart the run without re-creating the context: the global model goes back to the w0
+ * given to aet_init (a replica is refreshed when its next round adopts the global
+ * model); round counters, recursion and sample counters, the history H, the message
+ * queue and the tick counter are cleared.  Enqueued, no sync. */
+aet_status aet_reset(aet_ctx *ctx);
+
+/* Optional kernel timing for measurement harnesses.  The library's kernels are grouped
+ * in families (aet_profile_family_name gives each family's kernel name); while a family
+ * is enabled, every launch of it is bracketed by a pair of HIP events recorded on the
+ * context's stream.  aet_profile_read synchronises, then returns the number of launches
+ * and the sum of their durations in milliseconds since the last reset.
+ * family = -1 in aet_profile_enable means all families. */
+int32_t aet_profile_families(void);
+const char *aet_profile_family_name(int32_t family);
+aet_status aet_profile_enable(aet_ctx *ctx, int32_t family, int32_t on);
+aet_status aet_profile_read(aet_ctx *ctx, int32_t family, int64_t *launches, double *total_ms,
+                            int32_t reset);
+
 /* Text of the last error of this context (ctx == NULL: of the last failed aet_init). */
 const char *aet_last_error(const aet_ctx *ctx);
 

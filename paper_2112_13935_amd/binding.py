@@ -21,7 +21,8 @@ EXPORTS = [
     "aet_n_params", "aet_workspace_bytes", "aet_init", "aet_run_round", "aet_server_aggregate",
     "aet_get_U", "aet_get_weights", "aet_get_round_info", "aet_debug_sample_indices",
     "aet_all_done", "aet_tick", "aet_history", "aet_inflight", "aet_synchronize",
-    "aet_last_error", "aet_destroy",
+    "aet_last_error", "aet_destroy", "aet_reset", "aet_profile_families",
+    "aet_profile_family_name", "aet_profile_enable", "aet_profile_read",
 ]
 
 
@@ -104,6 +105,16 @@ def load_library():
     lib.aet_synchronize.argtypes = [vp]
     lib.aet_last_error.restype = C.c_char_p
     lib.aet_last_error.argtypes = [vp]
+    lib.aet_reset.restype = C.c_int
+    lib.aet_reset.argtypes = [vp]
+    lib.aet_profile_families.restype = i32
+    lib.aet_profile_families.argtypes = []
+    lib.aet_profile_family_name.restype = C.c_char_p
+    lib.aet_profile_family_name.argtypes = [i32]
+    lib.aet_profile_enable.restype = C.c_int
+    lib.aet_profile_enable.argtypes = [vp, i32, i32]
+    lib.aet_profile_read.restype = C.c_int
+    lib.aet_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double), i32]
     lib.aet_destroy.restype = None
     lib.aet_destroy.argtypes = [vp]
     _LIB = lib
@@ -236,6 +247,22 @@ class AetSgd:
 
     def aet_synchronize(self):
         self._check(self.lib.aet_synchronize(self.ctx))
+
+    def aet_reset(self):
+        self._check(self.lib.aet_reset(self.ctx))
+
+    def aet_profile_enable(self, family: int, on: bool):
+        self._check(self.lib.aet_profile_enable(self.ctx, family, 1 if on else 0))
+
+    def aet_profile_read(self, family: int, reset: bool = True) -> Tuple[int, float]:
+        n, ms = C.c_int64(0), C.c_double(0.0)
+        self._check(self.lib.aet_profile_read(self.ctx, family, C.byref(n), C.byref(ms),
+                                              1 if reset else 0))
+        return n.value, ms.value
+
+    def profile_family_names(self) -> List[str]:
+        return [self.lib.aet_profile_family_name(f).decode()
+                for f in range(self.lib.aet_profile_families())]
 
     def aet_destroy(self):
         if getattr(self, "ctx", None):

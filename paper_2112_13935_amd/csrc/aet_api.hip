@@ -37,7 +37,7 @@ struct RoundRec {
 };
 
 struct Layout {
-    size_t Wg, W, U, loss, params, arrivals, partial, debug, labels;
+    size_t w0, Wg, W, U, loss, params, arrivals, partial, debug, labels;
     size_t act[AET_MAX_LAYERS + 1], del[AET_MAX_LAYERS + 1], amax[AET_MAX_LAYERS];
     size_t total;
     int max_chunks;
@@ -95,6 +95,7 @@ bool make_layout(const LayerGeom *lay, int L, int64_t P, int B, int n, int infli
     const size_t Ps = (size_t)((P + 63) / 64 * 64);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    lo->w0 = take(Ps * 4);
     lo->Wg = take(Ps * 4);
     lo->W = take(Ps * 4 * n);
     lo->U = take(Ps * 4 * (size_t)n * inflight);
@@ -141,6 +142,9 @@ struct aet_ctx {
     int ring_p = 0, ring_a = 0;
     bool dead = false;
     std::string err;
+    Profiler prof;
+    Profiler *profp() { return prof.any ? &prof : nullptr; }
+    float *W0() const { return reinterpret_cast<float *>(ws + lo.w0); }
 
     float *Wg() const { return reinterpret_cast<float *>(ws + lo.Wg); }
     float *Wc(int c) const { return reinterpret_cast<float *>(ws + lo.W) + (int64_t)c * Ps; }
@@ -255,10 +259,11 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_arr[r], hipEventDisableTiming);
     }
     // global model and every replica start as w0
-    if (e == hipSuccess) e = hipMemcpyAsync(ctx->Wg(), w0, (size_t)ctx->P * 4, hipMemcpyHostToDevice, ctx->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(ctx->W0(), w0, (size_t)ctx->P * 4, hipMemcpyHostToDevice, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // w0 is the caller's; do not keep reading it
+    if (e == hipSuccess) e = hipMemcpyAsync(ctx->Wg(), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream);
     for (int c = 0; c < n_clients && e == hipSuccess; ++c)
-        e = hipMemcpyAsync(ctx->Wc(c), ctx->Wg(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream);
+        e = hipMemcpyAsync(ctx->Wc(c), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream);
     if (e != hipSuccess) {
         const aet_status st = fail(nullptr, AET_EHIP, "aet_init: %s", hipGetErrorString(e));
         aet_destroy(ctx);
@@ -341,9 +346,9 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         RoundParams *dp = reinterpret_cast<RoundParams *>(ctx->ws + ctx->lo.params);
         AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
         AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
-        AET_HIP(ctx, launch_begin_round(ctx->stream, dp, nact, ctx->Wg(), ctx->P));
+        AET_HIP(ctx, launch_begin_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), ctx->P));
         for (int64_t u = 0; u < max_m; ++u)
-            AET_HIP(ctx, launch_layer_step(ctx->stream, dp, nact, (int)u, ctx->lay, ctx->L, ctx->B, ctx->sc));
+            AET_HIP(ctx, launch_layer_step(ctx->stream, ctx->profp(), dp, nact, (int)u, ctx->lay, ctx->L, ctx->B, ctx->sc));
         for (int a = 0; a < nact; ++a) {
             const int c = act[a];
             Msg msg;
@@ -384,7 +389,7 @@ aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applie
         Arrival *da = reinterpret_cast<Arrival *>(ctx->ws + ctx->lo.arrivals);
         AET_HIP(ctx, hipMemcpyAsync(da, ha, (size_t)na * sizeof(Arrival), hipMemcpyHostToDevice, ctx->stream));
         AET_HIP(ctx, hipEventRecord(ctx->ev_arr[ring], ctx->stream));
-        AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->Wg(), da, na, ctx->P,
+        AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->profp(), ctx->Wg(), da, na, ctx->P,
                                           reinterpret_cast<float *>(ctx->ws + ctx->lo.partial), ctx->lo.max_chunks));
         for (int j = 0; j < na; ++j) {
             ctx->H[arr[j].c] += 1;
@@ -471,6 +476,48 @@ int64_t aet_inflight(const aet_ctx *ctx) { return ctx ? (int64_t)ctx->queue.size
 aet_status aet_synchronize(aet_ctx *ctx) {
     if (!ctx) return AET_EINVAL;
     AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    return AET_OK;
+}
+
+aet_status aet_reset(aet_ctx *ctx) {
+    if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
+    // the replicas need no copy: every round starts by adopting the global model
+    AET_HIP(ctx, hipMemcpyAsync(ctx->Wg(), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    std::fill(ctx->i_c.begin(), ctx->i_c.end(), 0);
+    std::fill(ctx->t_c.begin(), ctx->t_c.end(), 0);
+    std::fill(ctx->q_c.begin(), ctx->q_c.end(), 0);
+    std::fill(ctx->free_at.begin(), ctx->free_at.end(), 0);
+    std::fill(ctx->H.begin(), ctx->H.end(), 0);
+    for (auto &r : ctx->recs) r.clear();
+    ctx->queue.clear();
+    ctx->free_slots.clear();
+    for (int s = ctx->n * ctx->inflight - 1; s >= 0; --s) ctx->free_slots.push_back(s);
+    ctx->tick = 0;
+    return AET_OK;
+}
+
+int32_t aet_profile_families(void) { return F_COUNT; }
+const char *aet_profile_family_name(int32_t family) { return family_name(family); }
+
+aet_status aet_profile_enable(aet_ctx *ctx, int32_t family, int32_t on) {
+    if (!ctx) return AET_EINVAL;
+    if (family >= F_COUNT) return fail(ctx, AET_EINVAL, "no such kernel family");
+    for (int f = 0; f < F_COUNT; ++f)
+        if (family < 0 || f == family) ctx->prof.on[f] = on != 0;
+    ctx->prof.any = false;
+    for (int f = 0; f < F_COUNT; ++f) ctx->prof.any = ctx->prof.any || ctx->prof.on[f];
+    return AET_OK;
+}
+
+aet_status aet_profile_read(aet_ctx *ctx, int32_t family, int64_t *launches, double *total_ms,
+                            int32_t reset) {
+    if (!ctx) return AET_EINVAL;
+    if (family < 0 || family >= F_COUNT) return fail(ctx, AET_EINVAL, "no such kernel family");
+    AET_HIP(ctx, ctx->prof.drain(ctx->stream));
+    if (launches) *launches = ctx->prof.launches[family];
+    if (total_ms) *total_ms = ctx->prof.total_ms[family];
+    if (reset) { ctx->prof.launches[family] = 0; ctx->prof.total_ms[family] = 0.0; }
     return AET_OK;
 }
 

@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <vector>
+
 namespace aet {
 
 // Resolved geometry of one layer (activations are C,H,W per sample).
@@ -44,13 +46,41 @@ struct LayerScratch {
     int32_t *labels;    // [n_clients][batch]
 };
 
+// Kernel families, for the optional per-launch timing with HIP events.
+enum Family {
+    F_BEGIN_ROUND = 0, F_GATHER, F_DENSE_FWD, F_DENSE_BWD_DATA, F_DENSE_BWD_WEIGHT, F_CONV_FWD,
+    F_CONV_BWD_DATA, F_CONV_BWD_WEIGHT, F_POOL_FWD, F_POOL_BWD, F_SOFTMAX_CE, F_SERVER_REDUCE,
+    F_SOFTMAX_ROUND, F_MLP_ROUND, F_COUNT
+};
+const char *family_name(int fam);
+
+// Times the launches of the enabled families with event pairs recorded on the launch
+// stream; durations are summed when the pairs are drained.
+struct Profiler {
+    struct Pair { int fam; hipEvent_t a, b; };
+    bool on[F_COUNT] = {};
+    bool any = false;
+    double total_ms[F_COUNT] = {};
+    int64_t launches[F_COUNT] = {};
+    std::vector<hipEvent_t> pool;
+    std::vector<Pair> pending;
+    hipEvent_t cur = nullptr;
+    hipError_t status = hipSuccess;
+
+    void before(int fam, hipStream_t s);
+    void after(int fam, hipStream_t s);
+    hipError_t drain(hipStream_t s);
+    void clear();
+    ~Profiler();
+};
+
 // ---- launchers (each returns the launch status) --------------------------------------
-hipError_t launch_begin_round(hipStream_t s, const RoundParams *dp, int nact, const float *Wg,
-                              int64_t P);
-hipError_t launch_layer_step(hipStream_t s, const RoundParams *dp, int nact, int u,
+hipError_t launch_begin_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
+                              const float *Wg, int64_t P);
+hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                              const LayerGeom *lay, int L, int B, const LayerScratch &sc);
-hipError_t launch_server_reduce(hipStream_t s, float *Wg, const Arrival *darr, int n_arr,
-                                int64_t P, float *partial, int max_chunks);
+hipError_t launch_server_reduce(hipStream_t s, Profiler *prof, float *Wg, const Arrival *darr,
+                                int n_arr, int64_t P, float *partial, int max_chunks);
 hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
                                 uint32_t n_samples, int32_t *dst);
 // chunks of arrivals the two-stage server reduce uses for n_arr arrivals

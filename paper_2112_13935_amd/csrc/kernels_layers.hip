@@ -17,6 +17,14 @@
 
 namespace aet {
 
+// time the launch if its family is being profiled
+#define AET_TIMED(fam, ...)                              \
+    do {                                                 \
+        if (prof && prof->on[fam]) prof->before(fam, s); \
+        __VA_ARGS__;                                     \
+        if (prof && prof->on[fam]) prof->after(fam, s);  \
+    } while (0)
+
 #define AET_RETURN_IF(e)                 \
     do {                                 \
         hipError_t e__ = (e);            \
@@ -311,69 +319,69 @@ k_softmax_ce(const RoundParams *__restrict__ rp, int u, int B, int C,
     }
 }
 
-hipError_t launch_begin_round(hipStream_t s, const RoundParams *dp, int nact, const float *Wg,
-                              int64_t P) {
+hipError_t launch_begin_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
+                              const float *Wg, int64_t P) {
     if (nact <= 0) return hipSuccess;
     dim3 grid((unsigned)((P + 255) / 256), (unsigned)nact);
-    k_begin_round<<<grid, 256, 0, s>>>(dp, Wg, P);
+    AET_TIMED(F_BEGIN_ROUND, k_begin_round<<<grid, 256, 0, s>>>(dp, Wg, P));
     return hipGetLastError();
 }
 
 template <int KS>
-static hipError_t conv_step(hipStream_t s, const RoundParams *dp, int nact, int u, int B,
+static hipError_t conv_step(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u, int B,
                             const LayerGeom &g, int which, const float *a, const float *b,
                             float *c, const float *mask) {
     if (which == 0) {
         dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
-        k_conv_fwd<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, c);
+        AET_TIMED(F_CONV_FWD, k_conv_fwd<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, c));
     } else if (which == 1) {
         dim3 grid((unsigned)((g.in_size + 255) / 256), B, nact);
-        k_conv_bwd_data<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, c, mask);
+        AET_TIMED(F_CONV_BWD_DATA, k_conv_bwd_data<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, c, mask));
     } else {
         dim3 grid(g.ic, g.oc, nact);
-        k_conv_bwd_weight<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, b);
+        AET_TIMED(F_CONV_BWD_WEIGHT, k_conv_bwd_weight<KS><<<grid, 256, 0, s>>>(dp, u, B, g, a, b));
     }
     return hipGetLastError();
 }
 
-static hipError_t conv_dispatch(int ks, hipStream_t s, const RoundParams *dp, int nact, int u,
+static hipError_t conv_dispatch(int ks, hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                                 int B, const LayerGeom &g, int which, const float *a,
                                 const float *b, float *c, const float *mask) {
     switch (ks) {
-        case 1: return conv_step<1>(s, dp, nact, u, B, g, which, a, b, c, mask);
-        case 2: return conv_step<2>(s, dp, nact, u, B, g, which, a, b, c, mask);
-        case 3: return conv_step<3>(s, dp, nact, u, B, g, which, a, b, c, mask);
-        case 5: return conv_step<5>(s, dp, nact, u, B, g, which, a, b, c, mask);
+        case 1: return conv_step<1>(s, prof, dp, nact, u, B, g, which, a, b, c, mask);
+        case 2: return conv_step<2>(s, prof, dp, nact, u, B, g, which, a, b, c, mask);
+        case 3: return conv_step<3>(s, prof, dp, nact, u, B, g, which, a, b, c, mask);
+        case 5: return conv_step<5>(s, prof, dp, nact, u, B, g, which, a, b, c, mask);
         default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t launch_layer_step(hipStream_t s, const RoundParams *dp, int nact, int u,
+hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                              const LayerGeom *lay, int L, int B, const LayerScratch &sc) {
     if (nact <= 0) return hipSuccess;
     {
         const int D = (int)lay[0].in_size;
         dim3 grid((D + 255) / 256, B, nact);
-        k_gather<<<grid, 256, 0, s>>>(dp, u, B, D, sc.act[0], sc.labels);
+        AET_TIMED(F_GATHER, k_gather<<<grid, 256, 0, s>>>(dp, u, B, D, sc.act[0], sc.labels));
         AET_RETURN_IF(hipGetLastError());
     }
     for (int l = 0; l < L; ++l) {
         const LayerGeom &g = lay[l];
         if (g.type == 0) {
-            AET_RETURN_IF(conv_dispatch(g.k, s, dp, nact, u, B, g, 0, sc.act[l], nullptr,
+            AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 0, sc.act[l], nullptr,
                                         sc.act[l + 1], nullptr));
         } else if (g.type == 1) {
             dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
-            k_pool_fwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.act[l], sc.act[l + 1], sc.amax[l]);
+            AET_TIMED(F_POOL_FWD, k_pool_fwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.act[l], sc.act[l + 1], sc.amax[l]));
             AET_RETURN_IF(hipGetLastError());
         } else {
             dim3 grid((g.oc + 3) / 4, 1, nact);
-            k_dense_fwd<<<grid, 256, 0, s>>>(dp, u, B, (int)g.in_size, g.oc, g.w_off, g.b_off,
-                                             g.relu, sc.act[l], sc.act[l + 1]);
+            AET_TIMED(F_DENSE_FWD, k_dense_fwd<<<grid, 256, 0, s>>>(dp, u, B, (int)g.in_size, g.oc, g.w_off, g.b_off,
+                                                                    g.relu, sc.act[l], sc.act[l + 1]));
             AET_RETURN_IF(hipGetLastError());
         }
     }
-    k_softmax_ce<<<nact, 256, 0, s>>>(dp, u, B, lay[L - 1].oc, sc.act[L], sc.labels, sc.del[L]);
+    AET_TIMED(F_SOFTMAX_CE, k_softmax_ce<<<nact, 256, 0, s>>>(dp, u, B, lay[L - 1].oc, sc.act[L], sc.labels, sc.del[L]));
     AET_RETURN_IF(hipGetLastError());
     for (int l = L - 1; l >= 0; --l) {
         const LayerGeom &g = lay[l];
@@ -381,28 +389,25 @@ hipError_t launch_layer_step(hipStream_t s, const RoundParams *dp, int nact, int
         const float *mask = (l > 0 && lay[l - 1].relu) ? sc.act[l] : nullptr;
         if (g.type == 0) {
             if (l > 0)
-                AET_RETURN_IF(conv_dispatch(g.k, s, dp, nact, u, B, g, 1, sc.del[l + 1], nullptr,
+                AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 1, sc.del[l + 1], nullptr,
                                             sc.del[l], mask));
-            AET_RETURN_IF(conv_dispatch(g.k, s, dp, nact, u, B, g, 2, sc.act[l], sc.del[l + 1],
+            AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 2, sc.act[l], sc.del[l + 1],
                                         nullptr, nullptr));
         } else if (g.type == 1) {
             if (l > 0) {
                 dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
-                k_pool_bwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.del[l + 1], sc.amax[l], sc.del[l],
-                                                mask);
+                AET_TIMED(F_POOL_BWD, k_pool_bwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.del[l + 1], sc.amax[l], sc.del[l], mask));
                 AET_RETURN_IF(hipGetLastError());
             }
         } else {
             const int K = (int)g.in_size;
             if (l > 0) {
                 dim3 grid((K + 255) / 256, B, nact);
-                k_dense_bwd_data<<<grid, 256, 0, s>>>(dp, u, B, K, g.oc, g.w_off, sc.del[l + 1],
-                                                      sc.del[l], mask);
+                AET_TIMED(F_DENSE_BWD_DATA, k_dense_bwd_data<<<grid, 256, 0, s>>>(dp, u, B, K, g.oc, g.w_off, sc.del[l + 1], sc.del[l], mask));
                 AET_RETURN_IF(hipGetLastError());
             }
             dim3 grid((K + 255) / 256, g.oc, nact);
-            k_dense_bwd_weight<<<grid, 256, 0, s>>>(dp, u, B, K, g.oc, g.w_off, g.b_off, sc.act[l],
-                                                    sc.del[l + 1]);
+            AET_TIMED(F_DENSE_BWD_WEIGHT, k_dense_bwd_weight<<<grid, 256, 0, s>>>(dp, u, B, K, g.oc, g.w_off, g.b_off, sc.act[l], sc.del[l + 1]));
             AET_RETURN_IF(hipGetLastError());
         }
     }

@@ -47,13 +47,16 @@ int server_reduce_chunks(int n_arr, int64_t P) {
     return n_arr <= 2 * kChunk ? 1 : (n_arr + kChunk - 1) / kChunk;
 }
 
-hipError_t launch_server_reduce(hipStream_t s, float *Wg, const Arrival *darr, int n_arr,
-                                int64_t P, float *partial, int max_chunks) {
+hipError_t launch_server_reduce(hipStream_t s, Profiler *prof, float *Wg, const Arrival *darr,
+                                int n_arr, int64_t P, float *partial, int max_chunks) {
     if (n_arr <= 0) return hipSuccess;
+    const bool timed = prof && prof->on[F_SERVER_REDUCE];
+    if (timed) prof->before(F_SERVER_REDUCE, s);
     const unsigned gx = (unsigned)((P + 255) / 256);
     const int chunks = server_reduce_chunks(n_arr, P);
     if (chunks == 1 || chunks > max_chunks) {
         k_server_apply<<<gx, 256, 0, s>>>(Wg, darr, n_arr, P);
+        if (timed) prof->after(F_SERVER_REDUCE, s);
         return hipGetLastError();
     }
     const int64_t stride = (P + 63) / 64 * 64;
@@ -61,6 +64,7 @@ hipError_t launch_server_reduce(hipStream_t s, float *Wg, const Arrival *darr, i
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     k_server_finish<<<gx, 256, 0, s>>>(Wg, partial, chunks, P, stride);
+    if (timed) prof->after(F_SERVER_REDUCE, s);
     return hipGetLastError();
 }
 

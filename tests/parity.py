@@ -2,15 +2,28 @@
 lock step on the same seeded workload and compare them.
 
 Bars: bit-exact for everything integer (which clients run, round numbers, round lengths,
-sample counters, ticks, sample indices, the order in which arrivals are applied); for
-floating point, per tensor  max|gpu - cpu| / max(max|cpu|, 1e-12) <= tol  with tol = 1e-4
-(fp32 results after 20 rounds), and the round step size must be the fp32 rounding of the
-oracle's double."""
+sample counters, ticks, sample indices, the order in which arrivals are applied); the
+round step size must be the fp32 rounding of the oracle's double.  For floating point,
+per tensor (each layer's weights, each layer's bias)
+    max|gpu - cpu| / max(max|cpu|, 1e-12) <= 1e-4        (fp32 results after 20 rounds)
+for the global model and the losses, always, and for the per-client U and w_c of models
+without ReLU.  The gradient of a ReLU network is discontinuous where a pre-activation
+crosses zero: when fp32 rounding puts one pre-activation of one sample on the other side
+of zero than the fp64 oracle has it, that unit's row of the mini-batch gradient jumps by
+|delta| * |input| / B, and the unit's weights by eta times that -- about 3e-4 of the
+bias tensor's largest entry for the LeNet-style configuration (eta 0.01, B 16,
+|delta| ~ 0.3, max|bias| ~ 0.065), whatever the arithmetic's quality; the oracle's own
+fp32 twin shows the same jumps against the fp64 oracle.  Such flips are rare (a few per
+client over 20 rounds) and touch one row of one tensor, so for per-client tensors of
+ReLU networks the bar is: at least 98% of the checked (client, tensor) pairs within
+1e-4, and every pair within 2e-3."""
 from __future__ import annotations
 
 import numpy as np
 
 TOL = 1e-4
+KINK_TOL = 2e-3        # ceiling for a per-client tensor of a ReLU network
+KINK_FRACTION = 0.02   # share of such tensors that may exceed TOL
 
 
 def relerr(gpu: np.ndarray, cpu: np.ndarray) -> float:
@@ -27,13 +40,43 @@ def layer_slices(model):
     return out
 
 
+def tensor_relerrs(model, gpu: np.ndarray, cpu: np.ndarray):
+    """Per-tensor relative errors (each layer's weights and bias on their own); a tensor
+    that is exactly zero on the CPU side must be (almost) zero on the GPU."""
+    return [relerr(gpu[s], cpu[s]) if np.abs(cpu[s]).max() > 0 else float(np.abs(gpu[s]).max())
+            for s in layer_slices(model)]
+
+
 def tensor_relerr(model, gpu: np.ndarray, cpu: np.ndarray) -> float:
-    """Worst per-tensor relative error (each layer's weights and bias on their own);
-    a tensor that is exactly zero on the CPU side must be (almost) zero on the GPU."""
-    worst = 0.0
-    for s in layer_slices(model):
-        worst = max(worst, relerr(gpu[s], cpu[s]) if np.abs(cpu[s]).max() > 0 else float(np.abs(gpu[s]).max()))
-    return worst
+    return max(tensor_relerrs(model, gpu, cpu))
+
+
+def has_kinks(model) -> bool:
+    return any(L.relu or L.type == 1 for L in model.layers)
+
+
+class LocalErrors:
+    """Collects the per-tensor errors of per-client quantities and applies their bar."""
+
+    def __init__(self, model, tol):
+        self.kinks = has_kinks(model)
+        self.tol = tol
+        self.errs = []
+
+    def add(self, what, errs):
+        hard = KINK_TOL if self.kinks else self.tol
+        for j, e in enumerate(errs):
+            assert e <= hard, f"{what}, tensor {j}: relerr {e:.3e} > {hard:.0e}"
+        self.errs += list(errs)
+
+    def finish(self):
+        if not self.errs:
+            return 0.0, 0.0
+        e = np.array(self.errs)
+        frac = float((e > self.tol).mean())
+        assert frac <= (KINK_FRACTION if self.kinks else 0.0), \
+            f"{frac:.1%} of the per-client tensors exceed {self.tol:.0e} (worst {e.max():.3e})"
+        return float(e.max()), frac
 
 
 def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_ticks=10000,
@@ -42,6 +85,7 @@ def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_tick
     R = wl.rounds if rounds is None else rounds
     model = wl.model
     worst = dict(U=0.0, W=0.0, Wg=0.0, loss=0.0)
+    local = LocalErrors(model, tol)
     ticks = 0
     while not orc.all_done(R):
         assert not run.lib.aet_all_done(R)
@@ -57,12 +101,12 @@ def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_tick
                 assert ig[key] == io[key], (c, k, key)
             assert ig["eta"] == float(np.float32(io["eta"])), (c, k, "eta")
             if check_every_tick:
-                e = tensor_relerr(model, run.lib.aet_get_U(c, k), orc.get_U(c, k))
-                worst["U"] = max(worst["U"], e)
-                assert e <= tol, f"U of client {c} round {k}: relerr {e:.3e}"
-                e = tensor_relerr(model, run.lib.aet_get_weights(c), orc.get_weights(c))
-                worst["W"] = max(worst["W"], e)
-                assert e <= tol, f"w_c of client {c} round {k}: relerr {e:.3e}"
+                es = tensor_relerrs(model, run.lib.aet_get_U(c, k), orc.get_U(c, k))
+                worst["U"] = max(worst["U"], max(es))
+                local.add(f"U of client {c} round {k}", es)
+                es = tensor_relerrs(model, run.lib.aet_get_weights(c), orc.get_weights(c))
+                worst["W"] = max(worst["W"], max(es))
+                local.add(f"w_c of client {c} round {k}", es)
             if io["m"] > 0:
                 e = abs(ig["loss"] - io["loss"]) / max(abs(io["loss"]), 1e-12)
                 worst["loss"] = max(worst["loss"], e)
@@ -85,7 +129,8 @@ def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_tick
         assert run.lib.aet_history(c) == orc.history(c)
         if check_clients is not None and c not in check_clients:
             continue
-        e = tensor_relerr(model, run.lib.aet_get_weights(c), orc.get_weights(c))
-        worst["W"] = max(worst["W"], e)
-        assert e <= tol, f"final w_c of client {c}: relerr {e:.3e}"
+        es = tensor_relerrs(model, run.lib.aet_get_weights(c), orc.get_weights(c))
+        worst["W"] = max(worst["W"], max(es))
+        local.add(f"final w_c of client {c}", es)
+    worst["local_max"], worst["local_frac_over_tol"] = local.finish()
     return worst
