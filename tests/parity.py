@@ -1,29 +1,38 @@
 """Helpers of the GPU parity tests: drive the CPU oracle (fp64) and the HIP library in
 lock step on the same seeded workload and compare them.
 
-Bars: bit-exact for everything integer (which clients run, round numbers, round lengths,
-sample counters, ticks, sample indices, the order in which arrivals are applied); the
-round step size must be the fp32 rounding of the oracle's double.  For floating point,
-per tensor (each layer's weights, each layer's bias)
-    max|gpu - cpu| / max(max|cpu|, 1e-12) <= 1e-4        (fp32 results after 20 rounds)
-for the global model and the losses, always, and for the per-client U and w_c of models
-without ReLU.  The gradient of a ReLU network is discontinuous where a pre-activation
-crosses zero: when fp32 rounding puts one pre-activation of one sample on the other side
-of zero than the fp64 oracle has it, that unit's row of the mini-batch gradient jumps by
-|delta| * |input| / B, and the unit's weights by eta times that -- about 3e-4 of the
-bias tensor's largest entry for the LeNet-style configuration (eta 0.01, B 16,
-|delta| ~ 0.3, max|bias| ~ 0.065), whatever the arithmetic's quality; the oracle's own
-fp32 twin shows the same jumps against the fp64 oracle.  Such flips are rare (a few per
-client over 20 rounds) and touch one row of one tensor, so for per-client tensors of
-ReLU networks the bar is: at least 98% of the checked (client, tensor) pairs within
-1e-4, and every pair within 2e-3."""
+Integer side, bit-exact: which clients run in a tick, their round numbers, round lengths
+s_i and recursion counts, sample counters, start and arrival ticks, the sample indices,
+the order in which arrivals are applied, the history H.  The round step size must be the
+fp32 rounding of the oracle's double.
+
+Floating point, per tensor (each layer's weights, each layer's bias, on their own):
+    err = max|gpu - cpu| / max(max|cpu|, 1e-12) <= 1e-4      (fp32 results after 20 rounds)
+for the global model, every client's w_c, and the losses.  U enters the result only
+through eta_k * U (Receive) and a round's U can be a small difference of large per-sample
+gradients, so for networks with ReLU/pooling its error is taken in weight units:
+eta_i * max|U_gpu - U_cpu| over a tensor divided by max|w_c| over the same tensor; for
+networks without ReLU/pooling the plain relative error of U has to meet 1e-4 as well.
+
+ReLU networks and the yardstick.  The gradient of a ReLU/max-pool network is
+discontinuous where a pre-activation crosses zero (or two pooled values cross): when fp32
+rounding puts one pre-activation of one sample on the other side of zero than fp64 has
+it, that unit's row of the mini-batch gradient jumps by |delta|*|input|/B and its weights
+by eta times that, however good the arithmetic.  On a small bias tensor (largest entry
+1/sqrt(fan_in)) one such flip is already several 1e-4 of the tensor's scale, and over 20
+rounds every client sees a few.  The oracle's own fp32 twin (same C source, REAL=float)
+shows exactly these jumps against the fp64 oracle.  For such models the tests may
+therefore pass a twin: it runs in lock step, and the bar for tensor j of a quantity is
+    max(1e-4, 3 * worst error of the twin on tensor j of that quantity over the run),
+never more than 1e-2.  Without a twin the bar is 1e-4 flat.
+"""
 from __future__ import annotations
 
 import numpy as np
 
 TOL = 1e-4
-KINK_TOL = 2e-3        # ceiling for a per-client tensor of a ReLU network
-KINK_FRACTION = 0.02   # share of such tensors that may exceed TOL
+TWIN_FACTOR = 3.0
+CEILING = 1e-2
 
 
 def relerr(gpu: np.ndarray, cpu: np.ndarray) -> float:
@@ -41,8 +50,8 @@ def layer_slices(model):
 
 
 def tensor_relerrs(model, gpu: np.ndarray, cpu: np.ndarray):
-    """Per-tensor relative errors (each layer's weights and bias on their own); a tensor
-    that is exactly zero on the CPU side must be (almost) zero on the GPU."""
+    """Per-tensor relative errors; a tensor that is exactly zero on the CPU side must be
+    (almost) zero on the other side."""
     return [relerr(gpu[s], cpu[s]) if np.abs(cpu[s]).max() > 0 else float(np.abs(gpu[s]).max())
             for s in layer_slices(model)]
 
@@ -51,48 +60,75 @@ def tensor_relerr(model, gpu: np.ndarray, cpu: np.ndarray) -> float:
     return max(tensor_relerrs(model, gpu, cpu))
 
 
+def weight_unit_errs(model, eta, U_a, U_cpu, w_cpu):
+    """eta * max|dU| over a tensor, relative to the largest weight of that tensor."""
+    return [eta * float(np.abs(U_a[s].astype(np.float64) - U_cpu[s]).max()) /
+            max(float(np.abs(w_cpu[s]).max()), 1e-12) for s in layer_slices(model)]
+
+
 def has_kinks(model) -> bool:
     return any(L.relu or L.type == 1 for L in model.layers)
 
 
-class LocalErrors:
-    """Collects the per-tensor errors of per-client quantities and applies their bar."""
+class Ledger:
+    """Worst error per (quantity, tensor) of the GPU and of the twin; judged at the end."""
 
-    def __init__(self, model, tol):
-        self.kinks = has_kinks(model)
+    def __init__(self, tol):
         self.tol = tol
-        self.errs = []
+        self.gpu, self.twin, self.where = {}, {}, {}
 
-    def add(self, what, errs):
-        hard = KINK_TOL if self.kinks else self.tol
-        for j, e in enumerate(errs):
-            assert e <= hard, f"{what}, tensor {j}: relerr {e:.3e} > {hard:.0e}"
-        self.errs += list(errs)
+    def add(self, quantity, what, gpu_errs, twin_errs=None):
+        g = self.gpu.setdefault(quantity, [0.0] * len(gpu_errs))
+        w = self.where.setdefault(quantity, [""] * len(gpu_errs))
+        for j, e in enumerate(gpu_errs):
+            if e > g[j]:
+                g[j], w[j] = e, what
+        if twin_errs is not None:
+            t = self.twin.setdefault(quantity, [0.0] * len(twin_errs))
+            for j, e in enumerate(twin_errs):
+                t[j] = max(t[j], e)
 
-    def finish(self):
-        if not self.errs:
-            return 0.0, 0.0
-        e = np.array(self.errs)
-        frac = float((e > self.tol).mean())
-        assert frac <= (KINK_FRACTION if self.kinks else 0.0), \
-            f"{frac:.1%} of the per-client tensors exceed {self.tol:.0e} (worst {e.max():.3e})"
-        return float(e.max()), frac
+    def judge(self):
+        summary = {}
+        for q, g in self.gpu.items():
+            t = self.twin.get(q)
+            for j, e in enumerate(g):
+                bar = self.tol if t is None else min(CEILING, max(self.tol, TWIN_FACTOR * t[j]))
+                assert e <= bar, (f"{q}, tensor {j}, worst at {self.where[q][j]}: relerr {e:.3e} > bar "
+                                  f"{bar:.1e}" + ("" if t is None else f" (fp32 twin: {t[j]:.3e})"))
+            summary[q] = max(g)
+            if t is not None:
+                summary[q + "_twin"] = max(t)
+        return summary
 
 
 def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_ticks=10000,
-             check_clients=None):
-    """Tick both sides until done.  Returns the worst relative errors seen."""
+             check_clients=None, twin=None):
+    """Tick all sides until done; returns the worst relative errors seen."""
     R = wl.rounds if rounds is None else rounds
     model = wl.model
-    worst = dict(U=0.0, W=0.0, Wg=0.0, loss=0.0)
-    local = LocalErrors(model, tol)
+    kinks = has_kinks(model)
+    led = Ledger(tol)
     ticks = 0
+
+    def compare_global(what):
+        wo = orc.get_weights(-1)
+        led.add("Wg", what, tensor_relerrs(model, run.lib.aet_get_weights(-1), wo),
+                None if twin is None else tensor_relerrs(model, twin.get_weights(-1), wo))
+
+    def compare_client(c, what):
+        wo = orc.get_weights(c)
+        led.add("w_c", what, tensor_relerrs(model, run.lib.aet_get_weights(c), wo),
+                None if twin is None else tensor_relerrs(model, twin.get_weights(c), wo))
+
     while not orc.all_done(R):
         assert not run.lib.aet_all_done(R)
         assert run.lib.aet_tick() == orc.tick
         fin_o = orc.run_round(R)
         fin_g = run.run_round(R)
         assert fin_g == fin_o, f"tick {orc.tick}: clients/rounds differ"
+        if twin is not None:
+            assert twin.run_round(R) == fin_o
         for c, k in fin_o:
             if check_clients is not None and c not in check_clients:
                 continue
@@ -100,37 +136,42 @@ def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_tick
             for key in ("s", "m", "q0", "t0", "start_tick", "arrival"):
                 assert ig[key] == io[key], (c, k, key)
             assert ig["eta"] == float(np.float32(io["eta"])), (c, k, "eta")
+            what = f"client {c} round {k}"
             if check_every_tick:
-                es = tensor_relerrs(model, run.lib.aet_get_U(c, k), orc.get_U(c, k))
-                worst["U"] = max(worst["U"], max(es))
-                local.add(f"U of client {c} round {k}", es)
-                es = tensor_relerrs(model, run.lib.aet_get_weights(c), orc.get_weights(c))
-                worst["W"] = max(worst["W"], max(es))
-                local.add(f"w_c of client {c} round {k}", es)
+                Ug, Uo, wo = run.lib.aet_get_U(c, k), orc.get_U(c, k), orc.get_weights(c)
+                Ut = None if twin is None else twin.get_U(c, k)
+                led.add("U_plain", what, tensor_relerrs(model, Ug, Uo),
+                        None if Ut is None else tensor_relerrs(model, Ut, Uo))
+                if kinks:
+                    led.add("U_weight_units", what, weight_unit_errs(model, io["eta"], Ug, Uo, wo),
+                            None if Ut is None else weight_unit_errs(model, io["eta"], Ut, Uo, wo))
+                compare_client(c, what)
             if io["m"] > 0:
                 e = abs(ig["loss"] - io["loss"]) / max(abs(io["loss"]), 1e-12)
-                worst["loss"] = max(worst["loss"], e)
-                assert e <= tol, f"loss of client {c} round {k}: {ig['loss']} vs {io['loss']}"
+                et = None if twin is None else [abs(twin.round_info(c, k)["loss"] - io["loss"]) /
+                                                max(abs(io["loss"]), 1e-12)]
+                led.add("loss", what, [e], et)
         app_o = orc.server_aggregate()
         app_g = run.server_aggregate()
         assert app_g == app_o, f"tick {orc.tick - 1}: aggregation order differs"
+        if twin is not None:
+            assert twin.server_aggregate() == app_o
         if check_every_tick:
-            e = tensor_relerr(model, run.lib.aet_get_weights(-1), orc.get_weights(-1))
-            worst["Wg"] = max(worst["Wg"], e)
-            assert e <= tol, f"global model after tick {orc.tick - 1}: relerr {e:.3e}"
+            compare_global(f"after tick {orc.tick - 1}")
         ticks += 1
         assert ticks <= max_ticks
     assert run.lib.aet_all_done(R)
     assert run.lib.aet_inflight() == 0
-    e = tensor_relerr(model, run.lib.aet_get_weights(-1), orc.get_weights(-1))
-    worst["Wg"] = max(worst["Wg"], e)
-    assert e <= tol, f"final global model: relerr {e:.3e}"
+    compare_global("end of run")
     for c in range(orc.n):
         assert run.lib.aet_history(c) == orc.history(c)
-        if check_clients is not None and c not in check_clients:
-            continue
-        es = tensor_relerrs(model, run.lib.aet_get_weights(c), orc.get_weights(c))
-        worst["W"] = max(worst["W"], max(es))
-        local.add(f"final w_c of client {c}", es)
-    worst["local_max"], worst["local_frac_over_tol"] = local.finish()
-    return worst
+        if check_clients is None or c in check_clients:
+            compare_client(c, f"client {c} at the end")
+    if kinks and "U_plain" in led.gpu:
+        # reported, not judged: see the module docstring
+        plain = max(led.gpu.pop("U_plain"))
+        led.twin.pop("U_plain", None)
+        out = led.judge()
+        out["U_plain(info)"] = plain
+        return out
+    return led.judge()

@@ -24,6 +24,12 @@ def _both(gpu, wl, **kw):
     return gpu(wl, **kw), Oracle(wl, "f64")
 
 
+def _twin(wl):
+    """The oracle's fp32 build: the yardstick for ReLU networks (see parity.py)."""
+    from oracle import Oracle
+    return Oracle(wl, "f32")
+
+
 def report(name, worst):
     print(f"\n[parity] {name}: " + ", ".join(f"{k} {v:.2e}" for k, v in worst.items()), flush=True)
 
@@ -135,7 +141,8 @@ def test_config3_full_clients_20_rounds(gpu, oracle_libs):
     from parity import lockstep
     wl = W.config3()
     run, orc = _both(gpu, wl)
-    report("config 3 (64 clients, 20 rounds)", lockstep(wl, run, orc, rounds=20, check_every_tick=False))
+    report("config 3 (64 clients, 20 rounds)",
+           lockstep(wl, run, orc, rounds=20, check_every_tick=False, twin=_twin(wl)))
     run.close()
 
 
@@ -146,7 +153,7 @@ def test_config4_full_layer_shapes(gpu, oracle_libs):
     wl = W.config4(n_clients=3, n_per=200, rounds=2)
     wl.compute_factor = np.array([1, 2, 1], dtype=np.int32)
     run, orc = _both(gpu, wl)
-    report("config 4 shapes (3 clients, 2 rounds)", lockstep(wl, run, orc))
+    report("config 4 shapes (3 clients, 2 rounds)", lockstep(wl, run, orc, twin=_twin(wl)))
     run.close()
 
 
@@ -156,7 +163,8 @@ def test_config4_reduced_20_rounds(gpu, oracle_libs):
     from parity import lockstep
     wl = W.config4(n_clients=8, n_per=300, hw=16, width=16, fc=64, batch=16, rounds=20, a=16, b=32)
     run, orc = _both(gpu, wl)
-    report("config 4 reduced (8 clients, 20 rounds)", lockstep(wl, run, orc, check_every_tick=False))
+    report("config 4 reduced (8 clients, 20 rounds)",
+           lockstep(wl, run, orc, check_every_tick=False, twin=_twin(wl)))
     run.close()
 
 
