@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -37,7 +38,7 @@ struct RoundRec {
 };
 
 struct Layout {
-    size_t w0, Wg, W, U, loss, params, arrivals, partial, debug, labels;
+    size_t w0, Wg, W, U, loss, params, arrivals, partial, debug, labels, fused;
     size_t act[AET_MAX_LAYERS + 1], del[AET_MAX_LAYERS + 1], amax[AET_MAX_LAYERS];
     size_t total;
     int max_chunks;
@@ -89,6 +90,18 @@ bool resolve(const aet_model_desc *m, LayerGeom *lay, int64_t *P, std::string *w
     return true;
 }
 
+// which engine runs the local rounds of this model
+enum Engine { ENGINE_LAYERS = 0, ENGINE_MLP = 1 };
+
+Engine pick_engine(const LayerGeom *lay, int L, int B) {
+    const char *force = std::getenv("AET_FORCE_LAYER_ENGINE");
+    if (force && force[0] == '1') return ENGINE_LAYERS;
+    if (L == 2 && lay[0].type == AET_DENSE && lay[1].type == AET_DENSE && lay[0].relu &&
+        mlp_round_supported((int)lay[0].in_size, lay[0].oc, lay[1].oc, B))
+        return ENGINE_MLP;
+    return ENGINE_LAYERS;
+}
+
 bool make_layout(const LayerGeom *lay, int L, int64_t P, int B, int n, int inflight, int rounds,
                  Layout *lo) {
     if (n < 1 || inflight < 1 || rounds < 1) return false;
@@ -106,6 +119,7 @@ bool make_layout(const LayerGeom *lay, int L, int64_t P, int B, int n, int infli
     lo->partial = take(Ps * 4 * (size_t)lo->max_chunks);
     lo->debug = take((size_t)kDebugIdx * 4);
     lo->labels = take((size_t)n * B * 4);
+    lo->fused = take(mlp_round_scratch_bytes(n, B));
     const size_t samples = (size_t)n * B;
     lo->act[0] = take(samples * lay[0].in_size * 4);
     lo->del[0] = 0;
@@ -141,6 +155,7 @@ struct aet_ctx {
     hipEvent_t ev_params[kRing] = {}, ev_arr[kRing] = {};
     int ring_p = 0, ring_a = 0;
     bool dead = false;
+    int engine = 0;
     std::string err;
     Profiler prof;
     Profiler *profp() { return prof.any ? &prof : nullptr; }
@@ -250,6 +265,7 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
     for (int l = 0; l < ctx->L; ++l)
         ctx->sc.amax[l] = ctx->lay[l].type == AET_POOL ? reinterpret_cast<uint8_t *>(ctx->ws + ctx->lo.amax[l]) : nullptr;
     ctx->sc.labels = reinterpret_cast<int32_t *>(ctx->ws + ctx->lo.labels);
+    ctx->engine = pick_engine(ctx->lay, ctx->L, ctx->B);
 
     hipError_t e = hipSuccess;
     for (int r = 0; r < kRing && e == hipSuccess; ++r) {
@@ -258,6 +274,7 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_params[r], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_arr[r], hipEventDisableTiming);
     }
+    if (e == hipSuccess) e = mlp_clear_error_flag(ctx->stream, ctx->ws + ctx->lo.fused, n_clients, ctx->B);
     // global model and every replica start as w0
     if (e == hipSuccess) e = hipMemcpyAsync(ctx->W0(), w0, (size_t)ctx->P * 4, hipMemcpyHostToDevice, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // w0 is the caller's; do not keep reading it
@@ -346,9 +363,14 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         RoundParams *dp = reinterpret_cast<RoundParams *>(ctx->ws + ctx->lo.params);
         AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
         AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
-        AET_HIP(ctx, launch_begin_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), ctx->P));
-        for (int64_t u = 0; u < max_m; ++u)
-            AET_HIP(ctx, launch_layer_step(ctx->stream, ctx->profp(), dp, nact, (int)u, ctx->lay, ctx->L, ctx->B, ctx->sc));
+        if (ctx->engine == ENGINE_MLP) {
+            AET_HIP(ctx, launch_mlp_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), (int)ctx->lay[0].in_size,
+                                          ctx->lay[0].oc, ctx->lay[1].oc, ctx->B, ctx->ws + ctx->lo.fused, ctx->n));
+        } else {
+            AET_HIP(ctx, launch_begin_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), ctx->P));
+            for (int64_t u = 0; u < max_m; ++u)
+                AET_HIP(ctx, launch_layer_step(ctx->stream, ctx->profp(), dp, nact, (int)u, ctx->lay, ctx->L, ctx->B, ctx->sc));
+        }
         for (int a = 0; a < nact; ++a) {
             const int c = act[a];
             Msg msg;
@@ -405,10 +427,24 @@ aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applie
     return AET_OK;
 }
 
+// After a synchronisation: did a fused kernel give up waiting for its cluster peers?
+static aet_status check_device_flag(aet_ctx *ctx) {
+    if (ctx->engine == ENGINE_LAYERS) return AET_OK;
+    int flag = 0;
+    AET_HIP(ctx, hipMemcpyAsync(&flag, mlp_error_flag_ptr(ctx->ws + ctx->lo.fused, ctx->n, ctx->B), 4, hipMemcpyDeviceToHost, ctx->stream));
+    AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (flag) {
+        ctx->dead = true;
+        return fail(ctx, AET_EHIP, "a fused round kernel timed out in its cluster barrier; results are invalid");
+    }
+    return AET_OK;
+}
+
 static aet_status copy_out(aet_ctx *ctx, const float *src, float *dst, int32_t on_host) {
     if (on_host) {
         AET_HIP(ctx, hipMemcpyAsync(dst, src, (size_t)ctx->P * 4, hipMemcpyDeviceToHost, ctx->stream));
         AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        return check_device_flag(ctx);
     } else {
         AET_HIP(ctx, hipMemcpyAsync(dst, src, (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream));
     }
@@ -476,7 +512,7 @@ int64_t aet_inflight(const aet_ctx *ctx) { return ctx ? (int64_t)ctx->queue.size
 aet_status aet_synchronize(aet_ctx *ctx) {
     if (!ctx) return AET_EINVAL;
     AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    return AET_OK;
+    return check_device_flag(ctx);
 }
 
 aet_status aet_reset(aet_ctx *ctx) {

@@ -83,6 +83,14 @@ hipError_t launch_server_reduce(hipStream_t s, Profiler *prof, float *Wg, const 
                                 int n_arr, int64_t P, float *partial, int max_chunks);
 hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
                                 uint32_t n_samples, int32_t *dst);
+// fused round of dense-ReLU-dense models (kernels_mlp.hip)
+bool mlp_round_supported(int D, int H, int C, int B);
+size_t mlp_round_scratch_bytes(int n_clients, int B);
+hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
+                            const float *Wg, int D, int H, int C, int B, void *scratch,
+                            int n_clients);
+hipError_t mlp_clear_error_flag(hipStream_t s, void *scratch, int n_clients, int B);
+const int *mlp_error_flag_ptr(void *scratch, int n_clients, int B);
 // chunks of arrivals the two-stage server reduce uses for n_arr arrivals
 int server_reduce_chunks(int n_arr, int64_t P);
 

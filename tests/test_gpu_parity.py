@@ -76,6 +76,17 @@ def small_cases():
     wl = W.config1(n_clients=1, n_per=50, d=10, rounds=5, a=2, b=3)
     wl.agg_scale = 1.0
     cases["one_client_plain_sgd"] = wl
+    # shapes the fused dense-ReLU-dense kernel takes (hidden a multiple of 16, batch 16/32)
+    wl = W.config2(n_clients=5, n_total=5 * 70, d=50, hidden=32, batch=16, rounds=5, a=16, b=32)
+    wl.is_straggler = np.array([1, 0, 0, 1, 0], dtype=np.uint8)
+    wl.delay_min, wl.delay_max, wl.delay_seed = 0, 2, 78
+    wl.compute_factor = np.array([1, 2, 1, 1, 3], dtype=np.int32)
+    cases["mlp_fused_b16_ragged_d"] = wl
+    wl = W.config2(n_clients=11, n_total=11 * 90, d=100, hidden=48, batch=32, rounds=4, a=32, b=64)
+    cases["mlp_fused_b32_11_clients"] = wl
+    wl = W.config2(n_clients=3, n_total=3 * 200, d=784, hidden=128, batch=32, rounds=3, a=32, b=32)
+    wl.compute_factor = np.array([1, 2, 1], dtype=np.int32)
+    cases["mlp_fused_full_width"] = wl
     return cases
 
 
@@ -93,9 +104,20 @@ def test_small_cases_every_tick(gpu, oracle_libs, name):
     run.close()
 
 
+def test_layer_engine_on_fused_shapes(gpu, oracle_libs, monkeypatch):
+    """The layer-by-layer engine on a shape the fused kernel would take: both code paths
+    have to match the oracle."""
+    from parity import lockstep
+    monkeypatch.setenv("AET_FORCE_LAYER_ENGINE", "1")
+    wl = small_cases()["mlp_fused_b16_ragged_d"]
+    run, orc = _both(gpu, wl)
+    report("layer engine on mlp_fused_b16_ragged_d", lockstep(wl, run, orc))
+    run.close()
+
+
 def test_U_invariant_on_gpu(gpu):
     """w_start - w_end = eta_i U_i holds for the GPU's own numbers (fp32 rounding)."""
-    wl = small_cases()["mlp_ragged_stragglers"]
+    wl = small_cases()["mlp_fused_b16_ragged_d"]
     run = gpu(wl)
     while not run.lib.aet_all_done(wl.rounds):
         w_start = run.lib.aet_get_weights(-1).astype(np.float64)
