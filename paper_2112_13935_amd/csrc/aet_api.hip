@@ -156,6 +156,7 @@ struct aet_ctx {
     int ring_p = 0, ring_a = 0;
     bool dead = false;
     int engine = 0;
+    uint32_t epoch = 0;  // step-tag base of the fused kernels' exchange records
     std::string err;
     Profiler prof;
     Profiler *profp() { return prof.any ? &prof : nullptr; }
@@ -364,8 +365,8 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
         AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
         if (ctx->engine == ENGINE_MLP) {
-            AET_HIP(ctx, launch_mlp_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), (int)ctx->lay[0].in_size,
-                                          ctx->lay[0].oc, ctx->lay[1].oc, ctx->B, ctx->ws + ctx->lo.fused, ctx->n));
+            AET_HIP(ctx, launch_mlp_round(ctx->stream, ctx->profp(), dp, nact, (int)max_m, ctx->Wg(), (int)ctx->lay[0].in_size,
+                                          ctx->lay[0].oc, ctx->lay[1].oc, ctx->B, ctx->ws + ctx->lo.fused, ctx->n, &ctx->epoch));
         } else {
             AET_HIP(ctx, launch_begin_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), ctx->P));
             for (int64_t u = 0; u < max_m; ++u)

@@ -23,6 +23,17 @@ __host__ __device__ __forceinline__ uint32_t sample_row(uint64_t key, uint64_t q
     return (uint32_t)(((h >> 32) * (uint64_t)n_samples) >> 32);
 }
 
+// Pointers that kernels read out of a parameter record in memory are "flat" to the
+// compiler; these casts tell it they point to global memory, so that it emits global_*
+// instead of flat_* accesses (flat accesses also count against the LDS wait counter and
+// serialise with LDS traffic).
+typedef const float __attribute__((address_space(1))) *gcf_ptr;
+typedef float __attribute__((address_space(1))) *gf_ptr;
+typedef const int32_t __attribute__((address_space(1))) *gci_ptr;
+__device__ __forceinline__ gcf_ptr as_global(const float *p) { return (gcf_ptr)p; }
+__device__ __forceinline__ gf_ptr as_global(float *p) { return (gf_ptr)p; }
+__device__ __forceinline__ gci_ptr as_global(const int32_t *p) { return (gci_ptr)p; }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);

@@ -87,8 +87,8 @@ hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int cou
 bool mlp_round_supported(int D, int H, int C, int B);
 size_t mlp_round_scratch_bytes(int n_clients, int B);
 hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
-                            const float *Wg, int D, int H, int C, int B, void *scratch,
-                            int n_clients);
+                            int max_m, const float *Wg, int D, int H, int C, int B, void *scratch,
+                            int n_clients, uint32_t *epoch);
 hipError_t mlp_clear_error_flag(hipStream_t s, void *scratch, int n_clients, int B);
 const int *mlp_error_flag_ptr(void *scratch, int n_clients, int B);
 // chunks of arrivals the two-stage server reduce uses for n_arr arrivals

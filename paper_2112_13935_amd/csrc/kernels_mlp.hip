@@ -5,21 +5,30 @@
 // g owns hidden units 16g..16g+15: its slice of the first layer (16 x D weights, 16
 // biases) and of the second layer (C x 16 weights), together with the matching slices of
 // U, stay in registers / LDS for the whole round, so the per-recursion traffic is the
-// mini-batch rows plus one small exchange:
+// mini-batch rows plus one small exchange.
 //
-//   per recursion: gather the B rows into LDS; z1 = X W1^T on the matrix cores (fp32 MFMA
-//   16x16x4; the K range is split over the 4 waves and summed through LDS); h = relu(z1 +
-//   b1); partial logits of the 16 own units -> a 16-float-per-sample record in global
-//   memory; cluster barrier; every workgroup sums the G records, softmax, d logits;
-//   dh = (W2^T d logits) * 1[h > 0]; dW1^T = X^T dh again on the matrix cores, whose
-//   accumulator tile has exactly the register layout the forward pass needs as its B
-//   operand, so  w <- w - eta g  and  U <- U + g  are applied to registers in place.
+// Per recursion:
+//   - each of the 4 waves owns a contiguous quarter of the input columns: it has
+//     prefetched its part of the B sampled rows into registers during the previous
+//     recursion and now drops them into LDS (no workgroup barrier: nobody else touches
+//     those columns);
+//   - z1 = X W1^T on the matrix cores (fp32 MFMA 16x16x4), partial over the wave's columns,
+//     summed over the waves through LDS; h = relu(z1 + b1);
+//   - the partial logits of the 16 own units are written to the client's exchange record
+//     as 64-bit {step tag, value} words; every workgroup polls the G records until all
+//     tags show the current step, which gives the logits without a separate barrier or
+//     fence (each word validates itself; two records alternate so a fast workgroup never
+//     overwrites what a slow one still has to read);
+//   - softmax / d logits with 16 lanes per sample; dh = (d logits W2) * 1[h > 0] and
+//     dW2 = d logits^T h as small MFMA products;
+//   - dW1^T = X^T dh on the matrix cores: the accumulator tile has exactly the register
+//     layout the forward pass uses as its B operand, so  w <- w - eta g  and  U <- U + g
+//     are applied to the register-resident slice in place (g never exists in memory).
 //
-// The cluster barrier is a counter in global memory (release/acquire at agent scope) and
-// needs all G workgroups of a client resident at once: the launcher never launches more
-// workgroups than the device can hold (1 per compute unit with this LDS footprint).  The
-// wait is bounded: on expiry an error flag is raised and every workgroup still runs to
-// the end, so the grid always drains.
+// All G workgroups of a client must be resident together: the launcher never has more
+// working workgroups in flight than the device holds (1 per compute unit with this LDS
+// footprint).  The poll is bounded: on expiry an error flag is raised and every workgroup
+// still runs to the end, so the grid always drains.
 #include "aet_device.h"
 #include "aet_internal.h"
 
@@ -29,63 +38,58 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 
 constexpr int kMlpTPW = 13;          // K tiles (of 16) per wave  => D <= 16*4*13 = 832
 constexpr int kMlpMaxG = 16;         // workgroups per client
-constexpr int kSpinLimit = 1 << 22;  // bounded wait of the cluster barrier
+constexpr int kMlpRec = 512;         // 64-bit words per exchange record (B*C <= 512)
+constexpr int kSpinLimit = 1 << 22;  // bounded wait of the exchange poll
 
-__device__ __forceinline__ void store_agent(float *p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+__device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
-__device__ __forceinline__ float load_agent(const float *p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// sum / max over the 16 lanes of one sample (lanes 16k .. 16k+15 of the wave)
+__device__ __forceinline__ float row16_sum(float v) {
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 16);
+    return v;
 }
-
-// All threads of the workgroup call this.  Returns after every workgroup of the cluster
-// has arrived `target` times in total (or the wait expired and the error flag is set).
-__device__ __forceinline__ void cluster_barrier(int *counter, int target, int *errflag) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        int spins = 0;
-        while (__hip_atomic_load(counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            __builtin_amdgcn_s_sleep(1);
-            if ((++spins & 1023) == 0) {
-                if (spins >= kSpinLimit ||
-                    __hip_atomic_load(errflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                    __hip_atomic_store(errflag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    break;
-                }
-            }
-        }
-    }
-    __syncthreads();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+__device__ __forceinline__ float row16_max(float v) {
+#pragma unroll
+    for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 16));
+    return v;
 }
 
 template <int NBT>
 __global__ void __launch_bounds__(256, 1)
 k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *__restrict__ Wg,
-            int D, int H, int C, int G, float *__restrict__ xbuf, int *__restrict__ counters,
+            int D, int H, int C, int G, unsigned long long *__restrict__ xrec, uint32_t tag0,
             int *__restrict__ errflag) {
     constexpr int B = 16 * NBT;
     // workgroup -> (client, unit group): consecutive workgroup ids go round the 8 XCDs, so
-    // the G workgroups of one client are given ids that land on the same XCD and share
-    // its L2 for the mini-batch rows.
+    // the G workgroups of one client get ids that land on the same XCD and share its L2
+    // for the mini-batch rows.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int a = a0 + xcd + 8 * (slot / G);
     const int g = slot % G;
     if (a >= nact) return;
     const RoundParams p = rp[a];
+    const gcf_ptr Xg = as_global(p.X);
+    const gci_ptr yg = as_global(p.y);
+    const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
     const int KT = (D + 15) >> 4;
     const int ld = KT * 16 + 4;
+    // contiguous K tiles of this wave
+    const int nt = KT / 4 + (wave < (KT & 3) ? 1 : 0);
+    const int t0 = wave * (KT / 4) + min(wave, KT & 3);
+    const int col0 = 16 * t0;                 // first column of the wave
+    const bool vec_ok = (D & 3) == 0;         // rows are 16-byte aligned
+    const bool my_vec = lane < 4 * nt;        // this lane moves one float4 per row
 
     extern __shared__ float smem[];
     float *Xs = smem;                 // [B][ld]
     float *red = Xs + B * ld;         // [4][B][16]
     float *hs = red + 4 * B * 16;     // [B][16]
     float *dhs = hs + B * 16;         // [B][16]
-    float *zs = dhs + B * 16;         // [B][16]  logits, then d logits
+    float *zs = dhs + B * 16;         // [B][16]  logits, then d logits (columns >= C stay 0)
     float *W2s = zs + B * 16;         // [16][16] (o, j)
     float *U2s = W2s + 256;
     float *b1s = U2s + 256;           // [16]
@@ -93,23 +97,38 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
     float *b2s = Ub1s + 16;
     float *Ub2s = b2s + 16;
     float *lossb = Ub2s + 16;         // [B]
-    int *rows = reinterpret_cast<int *>(lossb + B);
-    int *labs = rows + B;
+    int *labs = reinterpret_cast<int *>(lossb + B);
 
     const int64_t b1_off = (int64_t)H * D, w2_off = b1_off + H, b2_off = w2_off + (int64_t)C * H;
     const float invB = 1.0f / (float)B;
+
+    // one row of the wave's columns: global -> registers
+    auto load_row = [&](uint32_t row) -> f4 {
+        f4 x = {0.f, 0.f, 0.f, 0.f};
+        if (my_vec) {
+            const int col = col0 + 4 * lane;
+            const gcf_ptr src = Xg + (int64_t)row * D + col;
+            if (vec_ok && col + 3 < D) {
+                x = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(src);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    if (col + r < D) x[r] = src[r];
+            }
+        }
+        return x;
+    };
 
     // ---- adopt the global model: own slice into registers / LDS; U = 0 -----------------
     f4 W1r[kMlpTPW], U1r[kMlpTPW];
 #pragma unroll
     for (int tt = 0; tt < kMlpTPW; ++tt) {
-        const int t = tt * 4 + wave;
         f4 w = {0.f, 0.f, 0.f, 0.f};
-        if (t < KT) {
+        if (tt < nt) {
             const float *src = Wg + (int64_t)(16 * g + li) * D;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int k = 16 * t + 4 * lg + r;
+                const int k = 16 * (t0 + tt) + 4 * lg + r;
                 if (k < D) w[r] = src[k];
             }
         }
@@ -120,6 +139,7 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
         const int o = tid >> 4, j = tid & 15;  // 256 threads = 16 x 16
         W2s[tid] = (o < C) ? Wg[w2_off + (int64_t)o * H + 16 * g + j] : 0.f;
         U2s[tid] = 0.f;
+        for (int i = tid; i < B * 16; i += 256) zs[i] = 0.f;
         if (tid < 16) {
             b1s[tid] = Wg[b1_off + 16 * g + tid];
             Ub1s[tid] = 0.f;
@@ -127,35 +147,38 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
             Ub2s[tid] = 0.f;
         }
     }
+    // rows and labels of recursion 0 go straight to LDS
+    if (p.m > 0) {
+        uint32_t rowv = 0;
+        if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + lane), p.n_samples);
+        if (wave == 0 && lane < B) labs[lane] = yg[rowv];
+#pragma unroll
+        for (int rr = 0; rr < B; ++rr) {
+            const uint32_t row = __builtin_amdgcn_readlane(rowv, rr);
+            const f4 x = load_row(row);
+            if (my_vec) *reinterpret_cast<f4 *>(Xs + rr * ld + col0 + 4 * lane) = x;
+        }
+    }
     float loss_acc = 0.f;
-    int *counter = counters + a;
+    f4 dW2acc = {0.f, 0.f, 0.f, 0.f};
+    unsigned long long *rec_base = xrec + (int64_t)a * 2 * kMlpMaxG * kMlpRec;
+    bool dead = false;  // the poll expired: keep going, the host will see the flag
     __syncthreads();
 
     for (int u = 0; u < p.m; ++u) {
-        // ---- sample indices of the mini-batch (Algorithm 2: sample xi from D_c) ---------
-        if (tid < B) {
-            const uint32_t row = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)u * B + tid), p.n_samples);
-            rows[tid] = (int)row;
-            labs[tid] = p.y[row];
-        }
-        __syncthreads();
-        // ---- gather the rows into LDS (pad columns to a multiple of 16 with zeros) ------
-        {
-            const int vec_per_row = KT * 4;  // float4 per padded row
-            for (int i = tid; i < B * vec_per_row; i += 256) {
-                const int b = i / vec_per_row, v = i - b * vec_per_row;
-                const float *src = p.X + (int64_t)rows[b] * D + 4 * v;
-                f4 x;
-                if (4 * v + 3 < D && (D & 3) == 0) {
-                    x = *reinterpret_cast<const f4 *>(src);
-                } else {
+        // ---- prefetch the rows of the NEXT recursion into registers ----------------------
+        // (Algorithm 2: "sample xi from D_c"; the indices are a counter hash, so they are
+        // known ahead of time)
+        f4 xpre[B];
+        int labn = 0;
+        const bool more = u + 1 < p.m;
+        if (more) {
+            uint32_t rowv = 0;
+            if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)(u + 1) * B + lane), p.n_samples);
+            if (wave == 0 && lane < B) labn = yg[rowv];
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) x[r] = (4 * v + r < D) ? src[r] : 0.f;
-                }
-                *reinterpret_cast<f4 *>(Xs + b * ld + 4 * v) = x;
-            }
+            for (int rr = 0; rr < B; ++rr) xpre[rr] = load_row(__builtin_amdgcn_readlane(rowv, rr));
         }
-        __syncthreads();
         // ---- z1 partial sums on the matrix cores ----------------------------------------
         {
             f4 acc[NBT];
@@ -163,14 +186,12 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
             for (int bt = 0; bt < NBT; ++bt) acc[bt] = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int tt = 0; tt < kMlpTPW; ++tt) {
-                const int t = tt * 4 + wave;
-                if (t < KT) {
+                if (tt < nt) {
 #pragma unroll
                     for (int bt = 0; bt < NBT; ++bt) {
-                        const f4 x = *reinterpret_cast<const f4 *>(Xs + (16 * bt + li) * ld + 16 * t + 4 * lg);
+                        const f4 x = *reinterpret_cast<const f4 *>(Xs + (16 * bt + li) * ld + 16 * (t0 + tt) + 4 * lg);
 #pragma unroll
-                        for (int r = 0; r < 4; ++r)
-                            acc[bt] = __builtin_amdgcn_mfma_f32_16x16x4f32(x[r], W1r[tt][r], acc[bt], 0, 0, 0);
+                        for (int r = 0; r < 4; ++r) acc[bt] = mfma16(x[r], W1r[tt][r], acc[bt]);
                     }
                 }
             }
@@ -183,78 +204,118 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
         __syncthreads();
         // ---- h = relu(z1 + b1) ----------------------------------------------------------
         for (int i = tid; i < B * 16; i += 256) {
-            float s = b1s[i & 15] + red[i] + red[B * 16 + i] + red[2 * B * 16 + i] + red[3 * B * 16 + i];
+            const float s = b1s[i & 15] + red[i] + red[B * 16 + i] + red[2 * B * 16 + i] + red[3 * B * 16 + i];
             hs[i] = s > 0.f ? s : 0.f;
         }
         __syncthreads();
-        // ---- partial logits of the own 16 units -> exchange record ----------------------
-        float *rec = xbuf + ((int64_t)(a * 2 + (u & 1)) * kMlpMaxG) * (B * 16);
+        // ---- partial logits of the own 16 units -> tagged exchange record ---------------
+        const uint32_t tag = tag0 + (uint32_t)u;
+        unsigned long long *rec = rec_base + (int64_t)(u & 1) * kMlpMaxG * kMlpRec;
+        if (wave < NBT) {
+            const int bt = wave;
+            f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4; ++s)
+                acc = mfma16(hs[(16 * bt + li) * 16 + 4 * s + lg], W2s[li * 16 + 4 * s + lg], acc);
+            if (li < C) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int b = 16 * bt + 4 * lg + r;
+                    const unsigned long long word = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(acc[r]);
+                    __hip_atomic_store(rec + (int64_t)g * kMlpRec + b * C + li, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        // ---- logits = b2 + sum over the G records (poll until every tag is current) -----
+        for (int e = tid; e < B * C; e += 256) {
+            const int b = e / C, o = e - b * C;
+            float s = 0.f;
+            int spins = 0;
+            for (;;) {
+                unsigned long long v[kMlpMaxG];
+#pragma unroll
+                for (int gg = 0; gg < kMlpMaxG; ++gg)
+                    if (gg < G) v[gg] = __hip_atomic_load(rec + (int64_t)gg * kMlpRec + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                bool ok = true;
+                s = b2s[o];
+#pragma unroll
+                for (int gg = 0; gg < kMlpMaxG; ++gg)
+                    if (gg < G) {
+                        ok = ok && (uint32_t)(v[gg] >> 32) == tag;
+                        s += __uint_as_float((uint32_t)v[gg]);
+                    }
+                if (ok || dead) break;
+                __builtin_amdgcn_s_sleep(1);
+                if ((++spins & 255) == 0) {
+                    if (spins >= kSpinLimit || __hip_atomic_load(errflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                        __hip_atomic_store(errflag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        dead = true;
+                    }
+                }
+            }
+            zs[b * 16 + o] = s;
+        }
+        __syncthreads();
+        // ---- softmax cross-entropy and d logits, 16 lanes per sample --------------------
         for (int i = tid; i < B * 16; i += 256) {
             const int b = i >> 4, o = i & 15;
-            float s = 0.f;
-            if (o < C) {
+            const float z = zs[i];
+            const float zmax = row16_max(o < C ? z : -3.0e38f);
+            const float ex = o < C ? expf(z - zmax) : 0.f;
+            const float lse = zmax + logf(row16_sum(ex));
+            const int lab = labs[b];
+            if (o == lab) lossb[b] = lse - z;
+            zs[i] = o < C ? expf(z - lse) - (o == lab ? 1.f : 0.f) : 0.f;
+        }
+        __syncthreads();
+        // ---- small products on the matrix cores -----------------------------------------
+        if (wave < NBT) {
+            // dh = (dz W2) * 1[h > 0] for samples 16*wave .. 16*wave+15
+            const int bt = wave;
+            f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int j = 0; j < 16; ++j) s += W2s[o * 16 + j] * hs[b * 16 + j];
+            for (int s = 0; s < 4; ++s)
+                acc = mfma16(zs[(16 * bt + li) * 16 + 4 * s + lg], W2s[(4 * s + lg) * 16 + li], acc);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = (16 * bt + 4 * lg + r) * 16 + li;
+                dhs[i] = hs[i] > 0.f ? acc[r] : 0.f;
             }
-            store_agent(rec + (int64_t)g * (B * 16) + i, s);
-        }
-        cluster_barrier(counter, G * (u + 1), errflag);
-        for (int i = tid; i < B * 16; i += 256) {
-            float s = b2s[i & 15];
-            for (int gg = 0; gg < G; ++gg) s += load_agent(rec + (int64_t)gg * (B * 16) + i);
-            zs[i] = s;
+        } else if (wave == 2) {
+            // dW2[o][j] = sum_b dz[b][o] h[b][j]; applied after the barrier (W2 is still read)
+            dW2acc = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int s = 0; s < 4 * NBT; ++s)
+                dW2acc = mfma16(zs[(4 * s + lg) * 16 + li], hs[(4 * s + lg) * 16 + li], dW2acc);
+        } else if (wave == 3) {
+            if (lane < C) {
+                float s = 0.f;
+                for (int b = 0; b < B; ++b) s += zs[b * 16 + lane];
+                s *= invB;
+                b2s[lane] -= p.eta * s;
+                Ub2s[lane] += s;
+            }
+            if (lane == 0) {
+                float s = 0.f;
+                for (int b = 0; b < B; ++b) s += lossb[b];
+                loss_acc += s * invB;
+            }
         }
         __syncthreads();
-        // ---- softmax cross-entropy, d logits --------------------------------------------
-        if (tid < B) {
-            float *z = zs + tid * 16;
-            const int lab = labs[tid];
-            float zmax = z[0];
-            for (int j = 1; j < C; ++j) zmax = fmaxf(zmax, z[j]);
-            float sum = 0.f;
-            for (int j = 0; j < C; ++j) sum += expf(z[j] - zmax);
-            const float lse = zmax + logf(sum);
-            lossb[tid] = lse - z[lab];
-            for (int j = 0; j < 16; ++j) z[j] = (j < C) ? expf(z[j] - lse) - (j == lab ? 1.f : 0.f) : 0.f;
-        }
-        __syncthreads();
-        if (g == 0 && tid == 0) {
+        if (wave == 2) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int i = (4 * lg + r) * 16 + li;  // (o, j)
+                const float gv = dW2acc[r] * invB;
+                W2s[i] -= p.eta * gv;
+                U2s[i] += gv;
+            }
+        } else if (wave == 3 && lane < 16) {
             float s = 0.f;
-            for (int b = 0; b < B; ++b) s += lossb[b];
-            loss_acc += s * invB;
-        }
-        // ---- dh = (W2^T dz) * 1[h > 0] --------------------------------------------------
-        for (int i = tid; i < B * 16; i += 256) {
-            const int b = i >> 4, j = i & 15;
-            float s = 0.f;
-            for (int o = 0; o < C; ++o) s += W2s[o * 16 + j] * zs[b * 16 + o];
-            dhs[i] = hs[i] > 0.f ? s : 0.f;
-        }
-        __syncthreads();
-        // ---- second layer and biases: g, then w -= eta g, U += g ------------------------
-        {
-            const int o = tid >> 4, j = tid & 15;
-            if (o < C) {
-                float s = 0.f;
-                for (int b = 0; b < B; ++b) s += zs[b * 16 + o] * hs[b * 16 + j];
-                s *= invB;
-                W2s[tid] -= p.eta * s;
-                U2s[tid] += s;
-            }
-            if (tid < 16) {
-                float s = 0.f;
-                for (int b = 0; b < B; ++b) s += dhs[b * 16 + tid];
-                s *= invB;
-                b1s[tid] -= p.eta * s;
-                Ub1s[tid] += s;
-            } else if (tid < 32 && tid - 16 < C) {
-                const int oo = tid - 16;
-                float s = 0.f;
-                for (int b = 0; b < B; ++b) s += zs[b * 16 + oo];
-                s *= invB;
-                b2s[oo] -= p.eta * s;
-                Ub2s[oo] += s;
-            }
+            for (int b = 0; b < B; ++b) s += dhs[b * 16 + lane];
+            s *= invB;
+            b1s[lane] -= p.eta * s;
+            Ub1s[lane] += s;
         }
         // ---- first layer: dW1^T = X^T dh on the matrix cores, update in registers -------
         {
@@ -264,12 +325,11 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
             const float eb = p.eta * invB;
 #pragma unroll
             for (int tt = 0; tt < kMlpTPW; ++tt) {
-                const int t = tt * 4 + wave;
-                if (t < KT) {
+                if (tt < nt) {
                     f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                     for (int s = 0; s < 4 * NBT; ++s)
-                        acc = __builtin_amdgcn_mfma_f32_16x16x4f32(Xs[(4 * s + lg) * ld + 16 * t + li], dhb[s], acc, 0, 0, 0);
+                        acc = mfma16(Xs[(4 * s + lg) * ld + 16 * (t0 + tt) + li], dhb[s], acc);
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         W1r[tt][r] -= eb * acc[r];
@@ -278,51 +338,58 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
                 }
             }
         }
-        __syncthreads();
+        // ---- the prefetched rows replace this wave's columns ----------------------------
+        if (more) {
+#pragma unroll
+            for (int rr = 0; rr < B; ++rr)
+                if (my_vec) *reinterpret_cast<f4 *>(Xs + rr * ld + col0 + 4 * lane) = xpre[rr];
+            if (wave == 0 && lane < B) labs[lane] = labn;
+        }
     }
 
     // ---- end of round: the replica and the message payload go to HBM ---------------------
 #pragma unroll
     for (int tt = 0; tt < kMlpTPW; ++tt) {
-        const int t = tt * 4 + wave;
-        if (t < KT) {
+        if (tt < nt) {
             const int64_t base = (int64_t)(16 * g + li) * D;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int k = 16 * t + 4 * lg + r;
+                const int k = 16 * (t0 + tt) + 4 * lg + r;
                 if (k < D) {
-                    p.W[base + k] = W1r[tt][r];
-                    p.U[base + k] = U1r[tt][r];
+                    Wc[base + k] = W1r[tt][r];
+                    Uc[base + k] = U1r[tt][r];
                 }
             }
         }
     }
+    __syncthreads();
     {
         const int o = tid >> 4, j = tid & 15;
         if (o < C) {
-            p.W[w2_off + (int64_t)o * H + 16 * g + j] = W2s[tid];
-            p.U[w2_off + (int64_t)o * H + 16 * g + j] = U2s[tid];
+            Wc[w2_off + (int64_t)o * H + 16 * g + j] = W2s[tid];
+            Uc[w2_off + (int64_t)o * H + 16 * g + j] = U2s[tid];
         }
         if (tid < 16) {
-            p.W[b1_off + 16 * g + tid] = b1s[tid];
-            p.U[b1_off + 16 * g + tid] = Ub1s[tid];
+            Wc[b1_off + 16 * g + tid] = b1s[tid];
+            Uc[b1_off + 16 * g + tid] = Ub1s[tid];
             if (g == 0 && tid < C) {
-                p.W[b2_off + tid] = b2s[tid];
-                p.U[b2_off + tid] = Ub2s[tid];
+                Wc[b2_off + tid] = b2s[tid];
+                Uc[b2_off + tid] = Ub2s[tid];
             }
         }
-        if (g == 0 && tid == 0) *p.loss = loss_acc;
     }
+    // the loss was accumulated by wave 3, lane 0 of unit group 0
+    if (g == 0 && wave == 3 && lane == 0) *as_global(p.loss) = loss_acc;
 }
 
-__global__ void k_zero_ints(int *p, int n) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
+__global__ void k_zero_words(unsigned long long *p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
 }
 
 static size_t mlp_lds_bytes(int D, int B) {
     const int KT = (D + 15) / 16, ld = KT * 16 + 4;
-    return sizeof(float) * ((size_t)B * ld + 4 * B * 16 + 3 * B * 16 + 512 + 64 + B) + sizeof(int) * 2 * B;
+    return sizeof(float) * ((size_t)B * ld + 4 * B * 16 + 3 * B * 16 + 512 + 64 + B) + sizeof(int) * B;
 }
 
 bool mlp_round_supported(int D, int H, int C, int B) {
@@ -332,9 +399,12 @@ bool mlp_round_supported(int D, int H, int C, int B) {
     return mlp_lds_bytes(D, B) <= 160 * 1024;
 }
 
+// exchange records [client][2][kMlpMaxG][kMlpRec] 64-bit words, then the error flag
+static size_t mlp_rec_words(int n_clients) { return (size_t)n_clients * 2 * kMlpMaxG * kMlpRec; }
+
 size_t mlp_round_scratch_bytes(int n_clients, int B) {
-    // exchange records [client][2][kMlpMaxG][B*16] floats, one counter per client, one flag
-    return (size_t)n_clients * 2 * kMlpMaxG * B * 16 * 4 + ((size_t)n_clients + 64) * 4;
+    (void)B;
+    return mlp_rec_words(n_clients) * 8 + 256;
 }
 
 static int g_mlp_capacity[2] = {0, 0};  // resident workgroups per device, per NBT
@@ -353,35 +423,43 @@ static hipError_t mlp_capacity(size_t lds, int *cap) {
     e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_mlp_round<NBT>, 256, lds);
     if (e != hipSuccess) return e;
     *cap = cus * per_cu;
+    g_mlp_capacity[NBT - 1] = *cap;
     return hipSuccess;
 }
 
 template <int NBT>
-static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, const float *Wg,
-                             int D, int H, int C, void *scratch, int n_clients) {
+static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int max_m,
+                             const float *Wg, int D, int H, int C, void *scratch, int n_clients,
+                             uint32_t *epoch) {
     constexpr int B = 16 * NBT;
     const int G = H / 16;
     const size_t lds = mlp_lds_bytes(D, B);
     int cap = 0;
     hipError_t e = mlp_capacity<NBT>(lds, &cap);
     if (e != hipSuccess) return e;
-    // Clusters per launch: every workgroup that waits in the cluster barrier must be
-    // resident together with its peers.  Workgroups of unused slots exit at once and free
-    // their compute unit, so only the working ones count.
+    // Clusters per launch: every workgroup that polls must be resident together with its
+    // peers.  Workgroups of unused slots exit at once and free their compute unit, so only
+    // the working ones count.
     const int per_launch = cap / G;
     if (per_launch < 1) return hipErrorLaunchOutOfResources;
-    float *xbuf = static_cast<float *>(scratch);
-    int *counters = reinterpret_cast<int *>(xbuf + (size_t)n_clients * 2 * kMlpMaxG * B * 16);
-    int *errflag = counters + n_clients;
-    k_zero_ints<<<(nact + 255) / 256, 256, 0, s>>>(counters, nact);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
+    unsigned long long *xrec = static_cast<unsigned long long *>(scratch);
+    int *errflag = reinterpret_cast<int *>(xrec + mlp_rec_words(n_clients));
+    // step tags of this launch: never 0 (the cleared state) and never a tag that an
+    // earlier launch may have left in the records
+    if (*epoch == 0 || *epoch > 0xFFFFFFFFu - (uint32_t)max_m - 2u) {
+        k_zero_words<<<(unsigned)((mlp_rec_words(n_clients) + 255) / 256), 256, 0, s>>>(xrec, mlp_rec_words(n_clients));
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        *epoch = 1;
+    }
+    const uint32_t tag0 = *epoch;
+    *epoch += (uint32_t)max_m + 1u;
     for (int a0 = 0; a0 < nact; a0 += per_launch) {
         const int here = (nact - a0 < per_launch) ? nact - a0 : per_launch;
         const int groups = (here + 7) / 8;  // clients per XCD in this launch
         const unsigned grid = (unsigned)(8 * groups * G);
         if (prof && prof->on[F_MLP_ROUND]) prof->before(F_MLP_ROUND, s);
-        k_mlp_round<NBT><<<grid, 256, lds, s>>>(dp, a0, (a0 + here), Wg, D, H, C, G, xbuf, counters, errflag);
+        k_mlp_round<NBT><<<grid, 256, lds, s>>>(dp, a0, a0 + here, Wg, D, H, C, G, xrec, tag0, errflag);
         if (prof && prof->on[F_MLP_ROUND]) prof->after(F_MLP_ROUND, s);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -389,25 +467,25 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *d
     return hipSuccess;
 }
 
-hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
+hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int max_m,
                             const float *Wg, int D, int H, int C, int B, void *scratch,
-                            int n_clients) {
+                            int n_clients, uint32_t *epoch) {
     if (nact <= 0) return hipSuccess;
-    return B == 16 ? mlp_launch<1>(s, prof, dp, nact, Wg, D, H, C, scratch, n_clients)
-                   : mlp_launch<2>(s, prof, dp, nact, Wg, D, H, C, scratch, n_clients);
+    return B == 16 ? mlp_launch<1>(s, prof, dp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch)
+                   : mlp_launch<2>(s, prof, dp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);
 }
 
 hipError_t mlp_clear_error_flag(hipStream_t s, void *scratch, int n_clients, int B) {
-    float *xbuf = static_cast<float *>(scratch);
-    int *counters = reinterpret_cast<int *>(xbuf + (size_t)n_clients * 2 * kMlpMaxG * B * 16);
-    k_zero_ints<<<1, 64, 0, s>>>(counters + n_clients, 1);
+    (void)B;
+    unsigned long long *xrec = static_cast<unsigned long long *>(scratch);
+    k_zero_words<<<1, 64, 0, s>>>(xrec + mlp_rec_words(n_clients), 1);
     return hipGetLastError();
 }
 
 const int *mlp_error_flag_ptr(void *scratch, int n_clients, int B) {
-    float *xbuf = static_cast<float *>(scratch);
-    int *counters = reinterpret_cast<int *>(xbuf + (size_t)n_clients * 2 * kMlpMaxG * B * 16);
-    return counters + n_clients;
+    (void)B;
+    unsigned long long *xrec = static_cast<unsigned long long *>(scratch);
+    return reinterpret_cast<const int *>(xrec + mlp_rec_words(n_clients));
 }
 
 }  // namespace aet
