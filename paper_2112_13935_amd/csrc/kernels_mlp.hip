@@ -8,7 +8,7 @@
 // mini-batch rows plus one small exchange.
 //
 // Per recursion:
-//   - each of the 4 waves owns a contiguous quarter of the input columns: it has
+//   - each of the 8 waves owns a contiguous eighth of the input columns: it has
 //     prefetched its part of the B sampled rows into registers during the previous
 //     recursion and now drops them into LDS (no workgroup barrier: nobody else touches
 //     those columns);
@@ -36,10 +36,19 @@ namespace aet {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-constexpr int kMlpTPW = 13;          // K tiles (of 16) per wave  => D <= 16*4*13 = 832
+constexpr int kMlpWaves = 8;         // waves per workgroup (2 per SIMD)
+constexpr int kMlpThreads = 64 * kMlpWaves;
+constexpr int kMlpMaxTPW = 7;        // K tiles (of 16) per wave  => D <= 16*8*7 = 896
 constexpr int kMlpMaxG = 16;         // workgroups per client
 constexpr int kMlpRec = 512;         // 64-bit words per exchange record (B*C <= 512)
 constexpr int kSpinLimit = 1 << 22;  // bounded wait of the exchange poll
+
+// Hides a value from the optimiser so that addresses derived from it are computed where
+// they are used instead of being kept in registers across the whole recursion loop.
+__device__ __forceinline__ int opaque(int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
 
 __device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
@@ -56,8 +65,12 @@ __device__ __forceinline__ float row16_max(float v) {
     return v;
 }
 
-template <int NBT>
-__global__ void __launch_bounds__(256, 1)
+// FAST: D is a multiple of 16, so every row piece is one aligned 16-byte load.
+// NBT: batch tiles of 16 samples; TPW: K tiles every wave steps through (waves that own
+// fewer real tiles run the remaining ones as no-ops on zero weights, so that the tile loops
+// are free of branches and the compiler can keep the matrix pipeline full).
+template <int NBT, int TPW, bool FAST>
+__global__ void __launch_bounds__(kMlpThreads, 1)
 k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *__restrict__ Wg,
             int D, int H, int C, int G, unsigned long long *__restrict__ xrec, uint32_t tag0,
             int *__restrict__ errflag) {
@@ -75,21 +88,26 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
     const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
-    const int KT = (D + 15) >> 4;
-    const int ld = KT * 16 + 4;
-    // contiguous K tiles of this wave
-    const int nt = KT / 4 + (wave < (KT & 3) ? 1 : 0);
-    const int t0 = wave * (KT / 4) + min(wave, KT & 3);
+    const int KT = (D + 15) >> 4;             // real K tiles (of 16 columns)
+    constexpr int ld = 16 * kMlpWaves * TPW + 4;  // LDS row stride: all tiles + 4 floats of skew
+    constexpr int LPR = 4 * TPW;              // lanes that move one row of the wave's columns
+    constexpr int RPI = 64 / LPR;             // rows moved by one load instruction
+    constexpr int NI = (B + RPI - 1) / RPI;   // load instructions per mini-batch
+    // wave w steps through tiles [TPW*w, TPW*w + TPW); the first nt of them are real, the
+    // rest lie in the zero-filled tail of the LDS rows and meet zero weights
+    const int t0 = TPW * wave;
+    const int nt = min(max(KT - t0, 0), TPW);
     const int col0 = 16 * t0;                 // first column of the wave
-    const bool vec_ok = (D & 3) == 0;         // rows are 16-byte aligned
-    const bool my_vec = lane < 4 * nt;        // this lane moves one float4 per row
+    const int sub = lane / LPR, cl = lane - sub * LPR;  // row slot and float4 slot of this lane
+    const bool my_vec = sub < RPI && cl < 4 * nt;       // this lane moves float4s of real columns
 
     extern __shared__ float smem[];
-    float *Xs = smem;                 // [B][ld]
-    float *red = Xs + B * ld;         // [4][B][16]
-    float *hs = red + 4 * B * 16;     // [B][16]
+    // the small arrays come first so that their addresses fit the 16-bit offset field of
+    // the LDS instructions; the big mini-batch tile follows
+    float *red = smem;                // [waves][B][16]
+    float *hs = red + kMlpWaves * B * 16;  // [B][16]
     float *dhs = hs + B * 16;         // [B][16]
-    float *zs = dhs + B * 16;         // [B][16]  logits, then d logits (columns >= C stay 0)
+    float *zs = dhs + B * 16;         // [B][16]  d logits (columns >= C stay 0)
     float *W2s = zs + B * 16;         // [16][16] (o, j)
     float *U2s = W2s + 256;
     float *b1s = U2s + 256;           // [16]
@@ -97,32 +115,34 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
     float *b2s = Ub1s + 16;
     float *Ub2s = b2s + 16;
     float *lossb = Ub2s + 16;         // [B]
-    int *labs = reinterpret_cast<int *>(lossb + B);
+    float *lossacc = lossb + B;       // [16], entry 0: the round's loss sum
+    int *labs = reinterpret_cast<int *>(lossacc + 16);  // [B]
+    float *Xs = reinterpret_cast<float *>(labs + B); // [B][ld]
 
     const int64_t b1_off = (int64_t)H * D, w2_off = b1_off + H, b2_off = w2_off + (int64_t)C * H;
     const float invB = 1.0f / (float)B;
 
-    // one row of the wave's columns: global -> registers
-    auto load_row = [&](uint32_t row) -> f4 {
+    // one row of the wave's columns: global -> registers.  `fast`: every lane's float4 is
+    // inside the row and 16-byte aligned (D a multiple of 16), so a row is one load.
+    constexpr bool fast = FAST;
+    const gcf_ptr lane_src = Xg + col0 + 4 * cl;
+    auto load_row_fast = [&](uint32_t row) -> f4 {
+        return *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(lane_src + (int64_t)row * D);
+    };
+    auto load_row_slow = [&](uint32_t row) -> f4 {
         f4 x = {0.f, 0.f, 0.f, 0.f};
-        if (my_vec) {
-            const int col = col0 + 4 * lane;
-            const gcf_ptr src = Xg + (int64_t)row * D + col;
-            if (vec_ok && col + 3 < D) {
-                x = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(src);
-            } else {
+        const int col = col0 + 4 * cl;
+        const gcf_ptr src = lane_src + (int64_t)row * D;
 #pragma unroll
-                for (int r = 0; r < 4; ++r)
-                    if (col + r < D) x[r] = src[r];
-            }
-        }
+        for (int r = 0; r < 4; ++r)
+            if (col + r < D) x[r] = src[r];
         return x;
     };
 
     // ---- adopt the global model: own slice into registers / LDS; U = 0 -----------------
-    f4 W1r[kMlpTPW], U1r[kMlpTPW];
+    f4 W1r[TPW], U1r[TPW];
 #pragma unroll
-    for (int tt = 0; tt < kMlpTPW; ++tt) {
+    for (int tt = 0; tt < TPW; ++tt) {
         f4 w = {0.f, 0.f, 0.f, 0.f};
         if (tt < nt) {
             const float *src = Wg + (int64_t)(16 * g + li) * D;
@@ -136,64 +156,68 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
         U1r[tt] = f4{0.f, 0.f, 0.f, 0.f};
     }
     {
-        const int o = tid >> 4, j = tid & 15;  // 256 threads = 16 x 16
-        W2s[tid] = (o < C) ? Wg[w2_off + (int64_t)o * H + 16 * g + j] : 0.f;
-        U2s[tid] = 0.f;
-        for (int i = tid; i < B * 16; i += 256) zs[i] = 0.f;
+        const int o = tid >> 4, j = tid & 15;  // threads 0..255 = 16 x 16
+        if (tid < 256) {
+            W2s[tid] = (o < C) ? Wg[w2_off + (int64_t)o * H + 16 * g + j] : 0.f;
+            U2s[tid] = 0.f;
+        }
+        for (int i = tid; i < B * 16; i += kMlpThreads) zs[i] = 0.f;
         if (tid < 16) {
             b1s[tid] = Wg[b1_off + 16 * g + tid];
             Ub1s[tid] = 0.f;
             b2s[tid] = (tid < C) ? Wg[b2_off + tid] : 0.f;
             Ub2s[tid] = 0.f;
+            lossacc[tid] = 0.f;
         }
     }
+    // the tail of every LDS row (columns the model does not have) stays zero for the round
+    for (int i = tid; i < B * ld; i += kMlpThreads) Xs[i] = 0.f;
+    __syncthreads();
     // rows and labels of recursion 0 go straight to LDS
     if (p.m > 0) {
         uint32_t rowv = 0;
         if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + lane), p.n_samples);
         if (wave == 0 && lane < B) labs[lane] = yg[rowv];
+        f4 x0[NI];
 #pragma unroll
-        for (int rr = 0; rr < B; ++rr) {
-            const uint32_t row = __builtin_amdgcn_readlane(rowv, rr);
-            const f4 x = load_row(row);
-            if (my_vec) *reinterpret_cast<f4 *>(Xs + rr * ld + col0 + 4 * lane) = x;
+        for (int i = 0; i < NI; ++i) {
+            const uint32_t row = __shfl(rowv, min(i * RPI + sub, B - 1));
+            x0[i] = f4{0.f, 0.f, 0.f, 0.f};
+            if (my_vec && i * RPI + sub < B) {
+                if constexpr (FAST) x0[i] = load_row_fast(row); else x0[i] = load_row_slow(row);
+            }
         }
+#pragma unroll
+        for (int i = 0; i < NI; ++i)
+            if (my_vec && i * RPI + sub < B) *reinterpret_cast<f4 *>(Xs + (i * RPI + sub) * ld + col0 + 4 * cl) = x0[i];
     }
-    float loss_acc = 0.f;
-    f4 dW2acc = {0.f, 0.f, 0.f, 0.f};
     unsigned long long *rec_base = xrec + (int64_t)a * 2 * kMlpMaxG * kMlpRec;
     bool dead = false;  // the poll expired: keep going, the host will see the flag
     __syncthreads();
 
     for (int u = 0; u < p.m; ++u) {
-        // ---- prefetch the rows of the NEXT recursion into registers ----------------------
-        // (Algorithm 2: "sample xi from D_c"; the indices are a counter hash, so they are
-        // known ahead of time)
-        f4 xpre[B];
-        int labn = 0;
-        const bool more = u + 1 < p.m;
-        if (more) {
-            uint32_t rowv = 0;
-            if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)(u + 1) * B + lane), p.n_samples);
-            if (wave == 0 && lane < B) labn = yg[rowv];
-#pragma unroll
-            for (int rr = 0; rr < B; ++rr) xpre[rr] = load_row(__builtin_amdgcn_readlane(rowv, rr));
-        }
         // ---- z1 partial sums on the matrix cores ----------------------------------------
         {
             f4 acc[NBT];
 #pragma unroll
             for (int bt = 0; bt < NBT; ++bt) acc[bt] = f4{0.f, 0.f, 0.f, 0.f};
+            // operands of the next tile are fetched from LDS while this tile multiplies
+            f4 xa[2][NBT];
 #pragma unroll
-            for (int tt = 0; tt < kMlpTPW; ++tt) {
-                if (tt < nt) {
+            for (int bt = 0; bt < NBT; ++bt)
+                xa[0][bt] = *reinterpret_cast<const f4 *>(Xs + (16 * bt + li) * ld + col0 + 4 * lg);
 #pragma unroll
-                    for (int bt = 0; bt < NBT; ++bt) {
-                        const f4 x = *reinterpret_cast<const f4 *>(Xs + (16 * bt + li) * ld + 16 * (t0 + tt) + 4 * lg);
+            for (int tt = 0; tt < TPW; ++tt) {
+                if (tt + 1 < TPW) {
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) acc[bt] = mfma16(x[r], W1r[tt][r], acc[bt]);
-                    }
+                    for (int bt = 0; bt < NBT; ++bt)
+                        xa[(tt + 1) & 1][bt] = *reinterpret_cast<const f4 *>(Xs + (16 * bt + li) * ld + col0 + 16 * (tt + 1) + 4 * lg);
                 }
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int bt = 0; bt < NBT; ++bt) acc[bt] = mfma16(xa[tt & 1][bt][r], W1r[tt][r], acc[bt]);
+                __builtin_amdgcn_sched_barrier(0);
             }
 #pragma unroll
             for (int bt = 0; bt < NBT; ++bt)
@@ -203,8 +227,10 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
         }
         __syncthreads();
         // ---- h = relu(z1 + b1) ----------------------------------------------------------
-        for (int i = tid; i < B * 16; i += 256) {
-            const float s = b1s[i & 15] + red[i] + red[B * 16 + i] + red[2 * B * 16 + i] + red[3 * B * 16 + i];
+        for (int i = tid; i < B * 16; i += kMlpThreads) {
+            float s = b1s[i & 15];
+#pragma unroll
+            for (int w = 0; w < kMlpWaves; ++w) s += red[w * B * 16 + i];
             hs[i] = s > 0.f ? s : 0.f;
         }
         __syncthreads();
@@ -226,49 +252,99 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
                 }
             }
         }
-        // ---- logits = b2 + sum over the G records (poll until every tag is current) -----
-        for (int e = tid; e < B * C; e += 256) {
-            const int b = e / C, o = e - b * C;
-            float s = 0.f;
+        // ---- prefetch the rows of the NEXT recursion into registers ----------------------
+        // (Algorithm 2: "sample xi from D_c"; the indices are a counter hash, so they are
+        // known ahead of time).  Loads of one wave return in order, so the waves that poll
+        // the exchange records issue their prefetch only after the poll; the other waves
+        // have nothing to poll and issue theirs at once.
+        f4 xpre[NI];
+        int labn = 0;
+        const bool more = u + 1 < p.m;
+        auto prefetch = [&]() {
+            if (!more) return;
+            uint32_t rowv = 0;
+            if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)(u + 1) * B + lane), p.n_samples);
+            if (wave == 0 && lane < B) labn = yg[rowv];
+            const int subo = opaque(sub);
+#pragma unroll
+            for (int i = 0; i < NI; ++i) {
+                const uint32_t row = __shfl(rowv, min(i * RPI + subo, B - 1));
+                xpre[i] = f4{0.f, 0.f, 0.f, 0.f};
+                if (my_vec && i * RPI + sub < B) {
+                    if constexpr (FAST) xpre[i] = load_row_fast(row); else xpre[i] = load_row_slow(row);
+                }
+            }
+        };
+        // ---- logits, softmax, d logits: thread (b, o) = (tid / 16, tid % 16) ------------
+        // Every thread with o < C fetches its own logit: the G tagged words of element
+        // (b, o).  To keep the memory system quiet while the peers are still computing,
+        // a wave first watches one word per record and batch tile (the last one its owner
+        // stores) and fetches the elements only when those show the current tag; the
+        // element tags are still checked, and the fetch repeated if one is stale.
+        {
+            const int b = tid >> 4, o = tid & 15;
+            const bool mine = b < B && o < C;
+            float z = 0.f;
             int spins = 0;
-            for (;;) {
-                unsigned long long v[kMlpMaxG];
-#pragma unroll
-                for (int gg = 0; gg < kMlpMaxG; ++gg)
-                    if (gg < G) v[gg] = __hip_atomic_load(rec + (int64_t)gg * kMlpRec + e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                bool ok = true;
-                s = b2s[o];
-#pragma unroll
-                for (int gg = 0; gg < kMlpMaxG; ++gg)
-                    if (gg < G) {
-                        ok = ok && (uint32_t)(v[gg] >> 32) == tag;
-                        s += __uint_as_float((uint32_t)v[gg]);
-                    }
-                if (ok || dead) break;
-                __builtin_amdgcn_s_sleep(1);
-                if ((++spins & 255) == 0) {
-                    if (spins >= kSpinLimit || __hip_atomic_load(errflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
-                        __hip_atomic_store(errflag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        dead = true;
+            {
+                // lane -> (record, batch tile); the word of sample 16*bt+15, class C-1
+                const int gg = lane % G, bt = lane / G;
+                const bool watch = bt < NBT;
+                const unsigned long long *w = rec + (int64_t)gg * kMlpRec + (16 * min(bt, NBT - 1) + 15) * C + (C - 1);
+                for (;;) {
+                    bool ok = true;
+                    if (watch) ok = (uint32_t)(__hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >> 32) == tag;
+                    if (__all(ok) || dead) break;
+                    __builtin_amdgcn_s_sleep(2);
+                    if ((++spins & 255) == 0) {
+                        if (spins >= kSpinLimit || __hip_atomic_load(errflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                            __hip_atomic_store(errflag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            dead = true;
+                        }
                     }
                 }
             }
-            zs[b * 16 + o] = s;
-        }
-        __syncthreads();
-        // ---- softmax cross-entropy and d logits, 16 lanes per sample --------------------
-        for (int i = tid; i < B * 16; i += 256) {
-            const int b = i >> 4, o = i & 15;
-            const float z = zs[i];
-            const float zmax = row16_max(o < C ? z : -3.0e38f);
-            const float ex = o < C ? expf(z - zmax) : 0.f;
-            const float lse = zmax + logf(row16_sum(ex));
-            const int lab = labs[b];
-            if (o == lab) lossb[b] = lse - z;
-            zs[i] = o < C ? expf(z - lse) - (o == lab ? 1.f : 0.f) : 0.f;
+            if (mine) {
+                const unsigned long long *src = rec + b * C + o;
+                constexpr int GC = 8;  // records fetched per batch of loads
+                for (;;) {
+                    bool ok = true;
+                    z = b2s[o];
+                    for (int g0 = 0; g0 < G; g0 += GC) {
+                        unsigned long long v[GC];
+#pragma unroll
+                        for (int gg = 0; gg < GC; ++gg)
+                            if (g0 + gg < G) v[gg] = __hip_atomic_load(src + (g0 + gg) * kMlpRec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                        for (int gg = 0; gg < GC; ++gg)
+                            if (g0 + gg < G) {
+                                ok = ok && (uint32_t)(v[gg] >> 32) == tag;
+                                z += __uint_as_float((uint32_t)v[gg]);
+                            }
+                    }
+                    if (ok || dead) break;
+                    __builtin_amdgcn_s_sleep(2);
+                    if ((++spins & 255) == 0) {
+                        if (spins >= kSpinLimit || __hip_atomic_load(errflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                            __hip_atomic_store(errflag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            dead = true;
+                        }
+                    }
+                }
+            }
+            if (b < B) {
+                const float zmax = row16_max(o < C ? z : -3.0e38f);
+                const float ex = o < C ? expf(z - zmax) : 0.f;
+                const float lse = zmax + logf(row16_sum(ex));
+                const int lab = labs[b];
+                if (o == lab) lossb[b] = lse - z;
+                zs[b * 16 + o] = o < C ? expf(z - lse) - (o == lab ? 1.f : 0.f) : 0.f;
+            }
         }
         __syncthreads();
         // ---- small products on the matrix cores -----------------------------------------
+        if (wave >= NBT) prefetch();
+        f4 dW2acc = {0.f, 0.f, 0.f, 0.f};
         if (wave < NBT) {
             // dh = (dz W2) * 1[h > 0] for samples 16*wave .. 16*wave+15
             const int bt = wave;
@@ -281,9 +357,9 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
                 const int i = (16 * bt + 4 * lg + r) * 16 + li;
                 dhs[i] = hs[i] > 0.f ? acc[r] : 0.f;
             }
+            prefetch();
         } else if (wave == 2) {
             // dW2[o][j] = sum_b dz[b][o] h[b][j]; applied after the barrier (W2 is still read)
-            dW2acc = f4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < 4 * NBT; ++s)
                 dW2acc = mfma16(zs[(4 * s + lg) * 16 + li], hs[(4 * s + lg) * 16 + li], dW2acc);
@@ -294,14 +370,14 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
                 s *= invB;
                 b2s[lane] -= p.eta * s;
                 Ub2s[lane] += s;
-            }
-            if (lane == 0) {
+            } else if (lane == 32) {
                 float s = 0.f;
                 for (int b = 0; b < B; ++b) s += lossb[b];
-                loss_acc += s * invB;
+                lossacc[0] += s * invB;
             }
         }
         __syncthreads();
+        // ---- second layer and first-layer bias: w <- w - eta g, U <- U + g ---------------
         if (wave == 2) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -322,34 +398,49 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
             float dhb[4 * NBT];
 #pragma unroll
             for (int s = 0; s < 4 * NBT; ++s) dhb[s] = dhs[(4 * s + lg) * 16 + li];
+            float xb[2][4 * NBT];
+            const float *xcol = Xs + opaque(lg * ld + col0 + li);
+#pragma unroll
+            for (int s = 0; s < 4 * NBT; ++s) xb[0][s] = xcol[4 * s * ld];
             const float eb = p.eta * invB;
 #pragma unroll
-            for (int tt = 0; tt < kMlpTPW; ++tt) {
-                if (tt < nt) {
-                    f4 acc = {0.f, 0.f, 0.f, 0.f};
+            for (int tt = 0; tt < TPW; ++tt) {
+                if (tt + 1 < TPW) {
 #pragma unroll
-                    for (int s = 0; s < 4 * NBT; ++s)
-                        acc = mfma16(Xs[(4 * s + lg) * ld + 16 * (t0 + tt) + li], dhb[s], acc);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        W1r[tt][r] -= eb * acc[r];
-                        U1r[tt][r] += invB * acc[r];
-                    }
+                    for (int s = 0; s < 4 * NBT; ++s) xb[(tt + 1) & 1][s] = xcol[4 * s * ld + 16 * (tt + 1)];
                 }
+                // two independent accumulation chains per tile
+                f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = 0; s < 4 * NBT; s += 2) {
+                    acc0 = mfma16(xb[tt & 1][s], dhb[s], acc0);
+                    acc1 = mfma16(xb[tt & 1][s + 1], dhb[s + 1], acc1);
+                }
+                const bool real = tt < nt;  // pad tiles keep their zero weights
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float gsum = real ? acc0[r] + acc1[r] : 0.f;
+                    W1r[tt][r] -= eb * gsum;
+                    U1r[tt][r] += invB * gsum;
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         // ---- the prefetched rows replace this wave's columns ----------------------------
         if (more) {
+            int dst = opaque(sub * ld + col0 + 4 * cl);
 #pragma unroll
-            for (int rr = 0; rr < B; ++rr)
-                if (my_vec) *reinterpret_cast<f4 *>(Xs + rr * ld + col0 + 4 * lane) = xpre[rr];
+            for (int i = 0; i < NI; ++i) {
+                if (my_vec && i * RPI + sub < B) *reinterpret_cast<f4 *>(Xs + dst) = xpre[i];
+                dst = opaque(dst + RPI * ld);
+            }
             if (wave == 0 && lane < B) labs[lane] = labn;
         }
     }
 
     // ---- end of round: the replica and the message payload go to HBM ---------------------
 #pragma unroll
-    for (int tt = 0; tt < kMlpTPW; ++tt) {
+    for (int tt = 0; tt < TPW; ++tt) {
         if (tt < nt) {
             const int64_t base = (int64_t)(16 * g + li) * D;
 #pragma unroll
@@ -365,7 +456,7 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
     __syncthreads();
     {
         const int o = tid >> 4, j = tid & 15;
-        if (o < C) {
+        if (tid < 256 && o < C) {
             Wc[w2_off + (int64_t)o * H + 16 * g + j] = W2s[tid];
             Uc[w2_off + (int64_t)o * H + 16 * g + j] = U2s[tid];
         }
@@ -378,8 +469,8 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
             }
         }
     }
-    // the loss was accumulated by wave 3, lane 0 of unit group 0
-    if (g == 0 && wave == 3 && lane == 0) *as_global(p.loss) = loss_acc;
+    // the loss was accumulated by wave 3, lane 32 of unit group 0
+    if (g == 0 && wave == 3 && lane == 32) *as_global(p.loss) = lossacc[0];
 }
 
 __global__ void k_zero_words(unsigned long long *p, size_t n) {
@@ -387,15 +478,17 @@ __global__ void k_zero_words(unsigned long long *p, size_t n) {
     if (i < n) p[i] = 0ull;
 }
 
+static int mlp_tpw(int D) { return (D + 15) / 16 <= 2 * kMlpWaves ? 2 : kMlpMaxTPW; }
+
 static size_t mlp_lds_bytes(int D, int B) {
-    const int KT = (D + 15) / 16, ld = KT * 16 + 4;
-    return sizeof(float) * ((size_t)B * ld + 4 * B * 16 + 3 * B * 16 + 512 + 64 + B) + sizeof(int) * B;
+    const int ld = 16 * kMlpWaves * mlp_tpw(D) + 4;
+    return sizeof(float) * ((size_t)B * ld + kMlpWaves * B * 16 + 3 * B * 16 + 512 + 64 + B + 16) + sizeof(int) * B;
 }
 
 bool mlp_round_supported(int D, int H, int C, int B) {
     if (!(B == 16 || B == 32)) return false;
     if (H % 16 || H / 16 > kMlpMaxG || C < 1 || C > 16) return false;
-    if (D < 1 || (D + 15) / 16 > 4 * kMlpTPW) return false;
+    if (D < 1 || (D + 15) / 16 > kMlpWaves * kMlpMaxTPW) return false;
     return mlp_lds_bytes(D, B) <= 160 * 1024;
 }
 
@@ -407,12 +500,13 @@ size_t mlp_round_scratch_bytes(int n_clients, int B) {
     return mlp_rec_words(n_clients) * 8 + 256;
 }
 
-static int g_mlp_capacity[2] = {0, 0};  // resident workgroups per device, per NBT
+static int g_mlp_capacity[2][2][2] = {};  // resident workgroups, per instantiation
 
-template <int NBT>
+template <int NBT, int TPW, bool FAST>
 static hipError_t mlp_capacity(size_t lds, int *cap) {
-    if (g_mlp_capacity[NBT - 1] > 0) { *cap = g_mlp_capacity[NBT - 1]; return hipSuccess; }
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mlp_round<NBT>),
+    int &cached = g_mlp_capacity[NBT - 1][TPW == kMlpMaxTPW ? 1 : 0][FAST ? 1 : 0];
+    if (cached > 0) { *cap = cached; return hipSuccess; }
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mlp_round<NBT, TPW, FAST>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     int dev = 0, cus = 0, per_cu = 0;
@@ -420,14 +514,14 @@ static hipError_t mlp_capacity(size_t lds, int *cap) {
     if (e != hipSuccess) return e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_mlp_round<NBT>, 256, lds);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_mlp_round<NBT, TPW, FAST>, kMlpThreads, lds);
     if (e != hipSuccess) return e;
     *cap = cus * per_cu;
-    g_mlp_capacity[NBT - 1] = *cap;
+    cached = *cap;
     return hipSuccess;
 }
 
-template <int NBT>
+template <int NBT, int TPW, bool FAST>
 static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int max_m,
                              const float *Wg, int D, int H, int C, void *scratch, int n_clients,
                              uint32_t *epoch) {
@@ -435,7 +529,7 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *d
     const int G = H / 16;
     const size_t lds = mlp_lds_bytes(D, B);
     int cap = 0;
-    hipError_t e = mlp_capacity<NBT>(lds, &cap);
+    hipError_t e = mlp_capacity<NBT, TPW, FAST>(lds, &cap);
     if (e != hipSuccess) return e;
     // Clusters per launch: every workgroup that polls must be resident together with its
     // peers.  Workgroups of unused slots exit at once and free their compute unit, so only
@@ -459,7 +553,7 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *d
         const int groups = (here + 7) / 8;  // clients per XCD in this launch
         const unsigned grid = (unsigned)(8 * groups * G);
         if (prof && prof->on[F_MLP_ROUND]) prof->before(F_MLP_ROUND, s);
-        k_mlp_round<NBT><<<grid, 256, lds, s>>>(dp, a0, a0 + here, Wg, D, H, C, G, xrec, tag0, errflag);
+        k_mlp_round<NBT, TPW, FAST><<<grid, kMlpThreads, lds, s>>>(dp, a0, a0 + here, Wg, D, H, C, G, xrec, tag0, errflag);
         if (prof && prof->on[F_MLP_ROUND]) prof->after(F_MLP_ROUND, s);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -471,8 +565,17 @@ hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *dp
                             const float *Wg, int D, int H, int C, int B, void *scratch,
                             int n_clients, uint32_t *epoch) {
     if (nact <= 0) return hipSuccess;
-    return B == 16 ? mlp_launch<1>(s, prof, dp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch)
-                   : mlp_launch<2>(s, prof, dp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);
+    const bool small = mlp_tpw(D) == 2;  // at most 2 K tiles per wave
+    const bool fast = (D & 15) == 0;
+#define AET_MLP_CASE(nbt, tpw, f) \
+    return mlp_launch<nbt, tpw, f>(s, prof, dp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch)
+    if (B == 16) {
+        if (small) { if (fast) AET_MLP_CASE(1, 2, true); else AET_MLP_CASE(1, 2, false); }
+        if (fast) AET_MLP_CASE(1, kMlpMaxTPW, true); else AET_MLP_CASE(1, kMlpMaxTPW, false);
+    }
+    if (small) { if (fast) AET_MLP_CASE(2, 2, true); else AET_MLP_CASE(2, 2, false); }
+    if (fast) AET_MLP_CASE(2, kMlpMaxTPW, true); else AET_MLP_CASE(2, kMlpMaxTPW, false);
+#undef AET_MLP_CASE
 }
 
 hipError_t mlp_clear_error_flag(hipStream_t s, void *scratch, int n_clients, int B) {
