@@ -119,7 +119,7 @@ def main():
 
     def job():
         run.lib.aet_reset()
-        return run.run_all()
+        return run.run_ticks()
 
     for _ in range(max(args.warmup, 0)):
         job()

@@ -165,6 +165,14 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
 aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applied,
                                 int32_t *applied_client, int32_t *applied_round);
 
+/* Driver loop: repeats { aet_run_round; aet_server_aggregate } with the same parameters
+ * until every client has completed thr->rounds local rounds and the message queue has
+ * drained, or max_ticks ticks have run.  *ticks_done (HOST, may be NULL) receives the
+ * number of ticks run; it is valid also when a tick fails. */
+aet_status aet_run_ticks(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *eta,
+                         const aet_delay *delay, float agg_scale, int32_t max_ticks,
+                         int32_t *ticks_done);
+
 /* U of the message (client, round) while it is in flight (posted, not yet applied).
  * dst: P floats, HOST if on_host != 0 (synchronises), else DEVICE (enqueued). */
 aet_status aet_get_U(aet_ctx *ctx, int32_t client, int32_t round, float *dst, int32_t on_host);

@@ -22,7 +22,7 @@ EXPORTS = [
     "aet_get_U", "aet_get_weights", "aet_get_round_info", "aet_debug_sample_indices",
     "aet_all_done", "aet_tick", "aet_history", "aet_inflight", "aet_synchronize",
     "aet_last_error", "aet_destroy", "aet_reset", "aet_profile_families",
-    "aet_profile_family_name", "aet_profile_enable", "aet_profile_read",
+    "aet_profile_family_name", "aet_profile_enable", "aet_profile_read", "aet_run_ticks",
 ]
 
 
@@ -84,6 +84,9 @@ def load_library():
     lib.aet_run_round.restype = C.c_int
     lib.aet_run_round.argtypes = [vp, C.POINTER(aet_threshold), C.POINTER(aet_eta),
                                   C.POINTER(aet_delay), C.POINTER(i32), vp, vp]
+    lib.aet_run_ticks.restype = C.c_int
+    lib.aet_run_ticks.argtypes = [vp, C.POINTER(aet_threshold), C.POINTER(aet_eta),
+                                  C.POINTER(aet_delay), C.c_float, i32, C.POINTER(i32)]
     lib.aet_server_aggregate.restype = C.c_int
     lib.aet_server_aggregate.argtypes = [vp, C.c_float, C.POINTER(i32), vp, vp]
     lib.aet_get_U.restype = C.c_int
@@ -198,6 +201,22 @@ class AetSgd:
         self._check(self.lib.aet_run_round(self.ctx, C.byref(thr), C.byref(eta), C.byref(dl),
                                            C.byref(nf), _hptr(self._fc), _hptr(self._fr)))
         return list(zip(self._fc[: nf.value].tolist(), self._fr[: nf.value].tolist()))
+
+    def aet_run_ticks(self, a: int, b: int, rounds: int, eta0: float, beta: float, power: float,
+                      agg_scale: float, compute_factor: Optional[np.ndarray] = None,
+                      is_straggler: Optional[np.ndarray] = None, delay_min: int = 0,
+                      delay_max: int = 0, delay_seed: int = 0, d_max: int = -1,
+                      max_ticks: int = 1 << 30) -> int:
+        thr = aet_threshold(a, b, rounds)
+        eta = aet_eta(eta0, beta, power)
+        cf = None if compute_factor is None else np.ascontiguousarray(compute_factor, dtype=np.int32)
+        st = None if is_straggler is None else np.ascontiguousarray(is_straggler, dtype=np.uint8)
+        dl = aet_delay(None if cf is None else cf.ctypes.data, None if st is None else st.ctypes.data,
+                       delay_min, delay_max, delay_seed, d_max)
+        done = C.c_int32(0)
+        self._check(self.lib.aet_run_ticks(self.ctx, C.byref(thr), C.byref(eta), C.byref(dl),
+                                           C.c_float(agg_scale), max_ticks, C.byref(done)))
+        return done.value
 
     def aet_server_aggregate(self, agg_scale: float) -> List[Tuple[int, int]]:
         na = C.c_int32(0)

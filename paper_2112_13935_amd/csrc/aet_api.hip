@@ -345,10 +345,14 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         return fail(ctx, AET_ENOMEM, "no free U slot: more than max_inflight messages of a client in flight");
 
     if (nact > 0) {
+        // staging: the layer engine copies the records to the device from a pinned ring;
+        // the fused engines take them in their kernel arguments from plain host memory
         const int ring = ctx->ring_p;
-        ctx->ring_p = (ring + 1) % kRing;
-        AET_HIP(ctx, hipEventSynchronize(ctx->ev_params[ring]));
         RoundParams *hp = ctx->h_params[ring];
+        if (ctx->engine == ENGINE_LAYERS) {
+            ctx->ring_p = (ring + 1) % kRing;
+            AET_HIP(ctx, hipEventSynchronize(ctx->ev_params[ring]));
+        }
         std::vector<int> slots(nact);
         for (int a = 0; a < nact; ++a) {
             const int c = act[a];
@@ -361,9 +365,12 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
             p.key = ctx->key[c]; p.q0 = rec[a].q0; p.n_samples = (uint32_t)ctx->shards[c].n_samples;
             p.m = (int32_t)rec[a].m; p.eta = rec[a].eta; p.client = c;
         }
-        RoundParams *dp = reinterpret_cast<RoundParams *>(ctx->ws + ctx->lo.params);
-        AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
-        AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
+        RoundParams *dp = hp;
+        if (ctx->engine == ENGINE_LAYERS) {
+            dp = reinterpret_cast<RoundParams *>(ctx->ws + ctx->lo.params);
+            AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
+            AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
+        }
         if (ctx->engine == ENGINE_MLP) {
             AET_HIP(ctx, launch_mlp_round(ctx->stream, ctx->profp(), dp, nact, (int)max_m, ctx->Wg(), (int)ctx->lay[0].in_size,
                                           ctx->lay[0].oc, ctx->lay[1].oc, ctx->B, ctx->ws + ctx->lo.fused, ctx->n, &ctx->epoch));
@@ -400,20 +407,31 @@ aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applie
     std::sort(arr.begin(), arr.end(), [](const Msg &x, const Msg &y) { return x.k != y.k ? x.k < y.k : x.c < y.c; });
     const int na = (int)arr.size();
     if (na > 0) {
-        const int ring = ctx->ring_a;
-        ctx->ring_a = (ring + 1) % kRing;
-        AET_HIP(ctx, hipEventSynchronize(ctx->ev_arr[ring]));
-        Arrival *ha = ctx->h_arr[ring];
-        for (int j = 0; j < na; ++j) {
-            ha[j].U = ctx->Uslot(arr[j].slot);
-            ha[j].scale = (float)((double)agg_scale * (double)arr[j].eta);
-            ha[j].pad_ = 0;
+        if (na <= kArrivalPack) {
+            // few arrivals: the list travels in the kernel arguments
+            ArrivalPack pack;
+            for (int j = 0; j < na; ++j) {
+                pack.a[j].U = ctx->Uslot(arr[j].slot);
+                pack.a[j].scale = (float)((double)agg_scale * (double)arr[j].eta);
+                pack.a[j].pad_ = 0;
+            }
+            AET_HIP(ctx, launch_server_apply_small(ctx->stream, ctx->profp(), ctx->Wg(), pack, na, ctx->P));
+        } else {
+            const int ring = ctx->ring_a;
+            ctx->ring_a = (ring + 1) % kRing;
+            AET_HIP(ctx, hipEventSynchronize(ctx->ev_arr[ring]));
+            Arrival *ha = ctx->h_arr[ring];
+            for (int j = 0; j < na; ++j) {
+                ha[j].U = ctx->Uslot(arr[j].slot);
+                ha[j].scale = (float)((double)agg_scale * (double)arr[j].eta);
+                ha[j].pad_ = 0;
+            }
+            Arrival *da = reinterpret_cast<Arrival *>(ctx->ws + ctx->lo.arrivals);
+            AET_HIP(ctx, hipMemcpyAsync(da, ha, (size_t)na * sizeof(Arrival), hipMemcpyHostToDevice, ctx->stream));
+            AET_HIP(ctx, hipEventRecord(ctx->ev_arr[ring], ctx->stream));
+            AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->profp(), ctx->Wg(), da, na, ctx->P,
+                                              reinterpret_cast<float *>(ctx->ws + ctx->lo.partial), ctx->lo.max_chunks));
         }
-        Arrival *da = reinterpret_cast<Arrival *>(ctx->ws + ctx->lo.arrivals);
-        AET_HIP(ctx, hipMemcpyAsync(da, ha, (size_t)na * sizeof(Arrival), hipMemcpyHostToDevice, ctx->stream));
-        AET_HIP(ctx, hipEventRecord(ctx->ev_arr[ring], ctx->stream));
-        AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->profp(), ctx->Wg(), da, na, ctx->P,
-                                          reinterpret_cast<float *>(ctx->ws + ctx->lo.partial), ctx->lo.max_chunks));
         for (int j = 0; j < na; ++j) {
             ctx->H[arr[j].c] += 1;
             ctx->free_slots.push_back(arr[j].slot);
@@ -437,6 +455,24 @@ static aet_status check_device_flag(aet_ctx *ctx) {
     if (flag) {
         ctx->dead = true;
         return fail(ctx, AET_EHIP, "a fused round kernel timed out in its cluster barrier; results are invalid");
+    }
+    return AET_OK;
+}
+
+aet_status aet_run_ticks(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *eta,
+                         const aet_delay *delay, float agg_scale, int32_t max_ticks,
+                         int32_t *ticks_done) {
+    if (!ctx) return AET_EINVAL;
+    if (!thr) return fail(ctx, AET_EINVAL, "NULL argument");
+    int32_t done = 0;
+    if (ticks_done) *ticks_done = 0;
+    while (done < max_ticks && !aet_all_done(ctx, thr->rounds)) {
+        aet_status st = aet_run_round(ctx, thr, eta, delay, nullptr, nullptr, nullptr);
+        if (st != AET_OK) return st;
+        st = aet_server_aggregate(ctx, agg_scale, nullptr, nullptr, nullptr);
+        if (st != AET_OK) return st;
+        ++done;
+        if (ticks_done) *ticks_done = done;
     }
     return AET_OK;
 }

@@ -38,6 +38,12 @@ struct Arrival {
     int32_t pad_;
 };
 
+// A short arrival list that is passed to the kernel by value.
+constexpr int kArrivalPack = 32;
+struct ArrivalPack {
+    Arrival a[kArrivalPack];
+};
+
 // Device scratch of the layer-by-layer engine; all sized for n_clients * batch samples.
 struct LayerScratch {
     float *act[17];     // act[0] = gathered inputs, act[l+1] = output of layer l
@@ -81,12 +87,15 @@ hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *d
                              const LayerGeom *lay, int L, int B, const LayerScratch &sc);
 hipError_t launch_server_reduce(hipStream_t s, Profiler *prof, float *Wg, const Arrival *darr,
                                 int n_arr, int64_t P, float *partial, int max_chunks);
+hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, const ArrivalPack &pack,
+                                     int n_arr, int64_t P);
 hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
                                 uint32_t n_samples, int32_t *dst);
 // fused round of dense-ReLU-dense models (kernels_mlp.hip)
 bool mlp_round_supported(int D, int H, int C, int B);
 size_t mlp_round_scratch_bytes(int n_clients, int B);
-hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
+// hp: HOST array of the tick's round records (they are passed on in kernel arguments)
+hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *hp, int nact,
                             int max_m, const float *Wg, int D, int H, int C, int B, void *scratch,
                             int n_clients, uint32_t *epoch);
 hipError_t mlp_clear_error_flag(hipStream_t s, void *scratch, int n_clients, int B);

@@ -69,9 +69,16 @@ __device__ __forceinline__ float row16_max(float v) {
 // NBT: batch tiles of 16 samples; TPW: K tiles every wave steps through (waves that own
 // fewer real tiles run the remaining ones as no-ops on zero weights, so that the tile loops
 // are free of branches and the compiler can keep the matrix pipeline full).
+// The round records of one launch travel in the kernel arguments: no staging copy, no
+// buffer whose reuse would have to be fenced with events.
+constexpr int kMlpPack = 48;
+struct MlpPack {
+    RoundParams p[kMlpPack];
+};
+
 template <int NBT, int TPW, bool FAST>
 __global__ void __launch_bounds__(kMlpThreads, 1)
-k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *__restrict__ Wg,
+k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *__restrict__ Wg,
             int D, int H, int C, int G, unsigned long long *__restrict__ xrec, uint32_t tag0,
             int *__restrict__ errflag) {
     constexpr int B = 16 * NBT;
@@ -79,10 +86,10 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
     // the G workgroups of one client get ids that land on the same XCD and share its L2
     // for the mini-batch rows.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int a = a0 + xcd + 8 * (slot / G);
+    const int a = xcd + 8 * (slot / G);  // index into this launch's records
     const int g = slot % G;
-    if (a >= nact) return;
-    const RoundParams p = rp[a];
+    if (a >= nhere) return;
+    const RoundParams p = pack.p[a];
     const gcf_ptr Xg = as_global(p.X);
     const gci_ptr yg = as_global(p.y);
     const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
@@ -191,7 +198,7 @@ k_mlp_round(const RoundParams *__restrict__ rp, int a0, int nact, const float *_
         for (int i = 0; i < NI; ++i)
             if (my_vec && i * RPI + sub < B) *reinterpret_cast<f4 *>(Xs + (i * RPI + sub) * ld + col0 + 4 * cl) = x0[i];
     }
-    unsigned long long *rec_base = xrec + (int64_t)a * 2 * kMlpMaxG * kMlpRec;
+    unsigned long long *rec_base = xrec + (int64_t)(rec0 + a) * 2 * kMlpMaxG * kMlpRec;
     bool dead = false;  // the poll expired: keep going, the host will see the flag
     __syncthreads();
 
@@ -522,7 +529,7 @@ static hipError_t mlp_capacity(size_t lds, int *cap) {
 }
 
 template <int NBT, int TPW, bool FAST>
-static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int max_m,
+static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *hp, int nact, int max_m,
                              const float *Wg, int D, int H, int C, void *scratch, int n_clients,
                              uint32_t *epoch) {
     constexpr int B = 16 * NBT;
@@ -534,7 +541,7 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *d
     // Clusters per launch: every workgroup that polls must be resident together with its
     // peers.  Workgroups of unused slots exit at once and free their compute unit, so only
     // the working ones count.
-    const int per_launch = cap / G;
+    const int per_launch = cap / G < kMlpPack ? cap / G : kMlpPack;
     if (per_launch < 1) return hipErrorLaunchOutOfResources;
     unsigned long long *xrec = static_cast<unsigned long long *>(scratch);
     int *errflag = reinterpret_cast<int *>(xrec + mlp_rec_words(n_clients));
@@ -552,8 +559,10 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *d
         const int here = (nact - a0 < per_launch) ? nact - a0 : per_launch;
         const int groups = (here + 7) / 8;  // clients per XCD in this launch
         const unsigned grid = (unsigned)(8 * groups * G);
+        MlpPack pack;
+        for (int j = 0; j < here; ++j) pack.p[j] = hp[a0 + j];
         if (prof && prof->on[F_MLP_ROUND]) prof->before(F_MLP_ROUND, s);
-        k_mlp_round<NBT, TPW, FAST><<<grid, kMlpThreads, lds, s>>>(dp, a0, a0 + here, Wg, D, H, C, G, xrec, tag0, errflag);
+        k_mlp_round<NBT, TPW, FAST><<<grid, kMlpThreads, lds, s>>>(pack, here, a0, Wg, D, H, C, G, xrec, tag0, errflag);
         if (prof && prof->on[F_MLP_ROUND]) prof->after(F_MLP_ROUND, s);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -561,14 +570,14 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *d
     return hipSuccess;
 }
 
-hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int max_m,
+hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *hp, int nact, int max_m,
                             const float *Wg, int D, int H, int C, int B, void *scratch,
                             int n_clients, uint32_t *epoch) {
     if (nact <= 0) return hipSuccess;
     const bool small = mlp_tpw(D) == 2;  // at most 2 K tiles per wave
     const bool fast = (D & 15) == 0;
 #define AET_MLP_CASE(nbt, tpw, f) \
-    return mlp_launch<nbt, tpw, f>(s, prof, dp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch)
+    return mlp_launch<nbt, tpw, f>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch)
     if (B == 16) {
         if (small) { if (fast) AET_MLP_CASE(1, 2, true); else AET_MLP_CASE(1, 2, false); }
         if (fast) AET_MLP_CASE(1, kMlpMaxTPW, true); else AET_MLP_CASE(1, kMlpMaxTPW, false);

@@ -20,6 +20,16 @@ k_server_apply(float *__restrict__ Wg, const Arrival *__restrict__ arr, int n_ar
     Wg[i] = w;
 }
 
+// the same with the arrival list in the kernel arguments (no staging copy)
+__global__ void __launch_bounds__(256)
+k_server_apply_small(float *__restrict__ Wg, ArrivalPack pack, int n_arr, int64_t P) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= P) return;
+    float w = Wg[i];
+    for (int j = 0; j < n_arr; ++j) w -= pack.a[j].scale * as_global(pack.a[j].U)[i];
+    Wg[i] = w;
+}
+
 __global__ void __launch_bounds__(256)
 k_server_partial(const Arrival *__restrict__ arr, int n_arr, int64_t P, int64_t stride,
                  float *__restrict__ partial) {
@@ -40,6 +50,16 @@ k_server_finish(float *__restrict__ Wg, const float *__restrict__ partial, int c
     float w = Wg[i];
     for (int c = 0; c < chunks; ++c) w -= partial[(int64_t)c * stride + i];
     Wg[i] = w;
+}
+
+hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, const ArrivalPack &pack,
+                                     int n_arr, int64_t P) {
+    if (n_arr <= 0) return hipSuccess;
+    const bool timed = prof && prof->on[F_SERVER_REDUCE];
+    if (timed) prof->before(F_SERVER_REDUCE, s);
+    k_server_apply_small<<<(unsigned)((P + 255) / 256), 256, 0, s>>>(Wg, pack, n_arr, P);
+    if (timed) prof->after(F_SERVER_REDUCE, s);
+    return hipGetLastError();
 }
 
 int server_reduce_chunks(int n_arr, int64_t P) {

@@ -48,5 +48,15 @@ class Run:
                 raise RuntimeError("run did not finish")
         return ticks
 
+    def run_ticks(self, rounds: Optional[int] = None, max_ticks: int = 1 << 30) -> int:
+        """The same loop inside the library (one call for the whole job)."""
+        wl = self.wl
+        return self.lib.aet_run_ticks(
+            wl.a, wl.b, wl.rounds if rounds is None else rounds, wl.eta0, wl.beta, wl.power,
+            wl.agg_scale,
+            None if wl.compute_factor is None else wl.compute_factor[: self.n],
+            None if wl.is_straggler is None else wl.is_straggler[: self.n],
+            wl.delay_min, wl.delay_max, wl.delay_seed, wl.d_max, max_ticks)
+
     def close(self):
         self.lib.aet_destroy()

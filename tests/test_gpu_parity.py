@@ -131,6 +131,24 @@ def test_U_invariant_on_gpu(gpu):
     run.close()
 
 
+def test_run_ticks_equals_tick_by_tick(gpu):
+    """aet_run_ticks is the same loop as calling the two entry points per tick."""
+    wl = small_cases()["mlp_fused_b16_ragged_d"]
+    a = gpu(wl)
+    ticks_a = a.run_all()
+    b = gpu(wl)
+    ticks_b = b.run_ticks()
+    assert ticks_a == ticks_b
+    assert np.array_equal(a.lib.aet_get_weights(-1), b.lib.aet_get_weights(-1))
+    assert b.lib.aet_all_done(wl.rounds)
+    # a second job after aet_reset gives the same bits again
+    b.lib.aet_reset()
+    assert b.run_ticks() == ticks_b
+    assert np.array_equal(a.lib.aet_get_weights(-1), b.lib.aet_get_weights(-1))
+    a.close()
+    b.close()
+
+
 def test_deterministic_rerun(gpu):
     """Two runs of the same workload give bit-identical results."""
     wl = small_cases()["lenet16_factors_stragglers"]
