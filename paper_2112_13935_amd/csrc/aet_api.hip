@@ -91,7 +91,7 @@ bool resolve(const aet_model_desc *m, LayerGeom *lay, int64_t *P, std::string *w
 }
 
 // which engine runs the local rounds of this model
-enum Engine { ENGINE_LAYERS = 0, ENGINE_MLP = 1 };
+enum Engine { ENGINE_LAYERS = 0, ENGINE_MLP = 1, ENGINE_SOFTMAX = 2 };
 
 Engine pick_engine(const LayerGeom *lay, int L, int B) {
     const char *force = std::getenv("AET_FORCE_LAYER_ENGINE");
@@ -99,6 +99,8 @@ Engine pick_engine(const LayerGeom *lay, int L, int B) {
     if (L == 2 && lay[0].type == AET_DENSE && lay[1].type == AET_DENSE && lay[0].relu &&
         mlp_round_supported((int)lay[0].in_size, lay[0].oc, lay[1].oc, B))
         return ENGINE_MLP;
+    if (L == 1 && lay[0].type == AET_DENSE && softmax_round_supported((int)lay[0].in_size, lay[0].oc, B))
+        return ENGINE_SOFTMAX;
     return ENGINE_LAYERS;
 }
 
@@ -346,10 +348,10 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
 
     if (nact > 0) {
         // staging: the layer engine copies the records to the device from a pinned ring;
-        // the fused engines take them in their kernel arguments from plain host memory
+        // the dense-ReLU-dense engine takes them in its kernel arguments from plain host memory
         const int ring = ctx->ring_p;
         RoundParams *hp = ctx->h_params[ring];
-        if (ctx->engine == ENGINE_LAYERS) {
+        if (ctx->engine != ENGINE_MLP) {
             ctx->ring_p = (ring + 1) % kRing;
             AET_HIP(ctx, hipEventSynchronize(ctx->ev_params[ring]));
         }
@@ -366,7 +368,7 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
             p.m = (int32_t)rec[a].m; p.eta = rec[a].eta; p.client = c;
         }
         RoundParams *dp = hp;
-        if (ctx->engine == ENGINE_LAYERS) {
+        if (ctx->engine != ENGINE_MLP) {
             dp = reinterpret_cast<RoundParams *>(ctx->ws + ctx->lo.params);
             AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
             AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
@@ -374,6 +376,8 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         if (ctx->engine == ENGINE_MLP) {
             AET_HIP(ctx, launch_mlp_round(ctx->stream, ctx->profp(), dp, nact, (int)max_m, ctx->Wg(), (int)ctx->lay[0].in_size,
                                           ctx->lay[0].oc, ctx->lay[1].oc, ctx->B, ctx->ws + ctx->lo.fused, ctx->n, &ctx->epoch));
+        } else if (ctx->engine == ENGINE_SOFTMAX) {
+            AET_HIP(ctx, launch_softmax_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), (int)ctx->lay[0].in_size, ctx->lay[0].oc));
         } else {
             AET_HIP(ctx, launch_begin_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), ctx->P));
             for (int64_t u = 0; u < max_m; ++u)
@@ -448,7 +452,7 @@ aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applie
 
 // After a synchronisation: did a fused kernel give up waiting for its cluster peers?
 static aet_status check_device_flag(aet_ctx *ctx) {
-    if (ctx->engine == ENGINE_LAYERS) return AET_OK;
+    if (ctx->engine != ENGINE_MLP) return AET_OK;
     int flag = 0;
     AET_HIP(ctx, hipMemcpyAsync(&flag, mlp_error_flag_ptr(ctx->ws + ctx->lo.fused, ctx->n, ctx->B), 4, hipMemcpyDeviceToHost, ctx->stream));
     AET_HIP(ctx, hipStreamSynchronize(ctx->stream));

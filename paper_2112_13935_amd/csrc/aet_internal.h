@@ -91,6 +91,10 @@ hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, c
                                      int n_arr, int64_t P);
 hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
                                 uint32_t n_samples, int32_t *dst);
+// fused round of softmax regression, per-sample SGD (kernels_softmax.hip)
+bool softmax_round_supported(int D, int C, int B);
+hipError_t launch_softmax_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
+                                const float *Wg, int D, int C);
 // fused round of dense-ReLU-dense models (kernels_mlp.hip)
 bool mlp_round_supported(int D, int H, int C, int B);
 size_t mlp_round_scratch_bytes(int n_clients, int B);
