@@ -36,9 +36,14 @@ def per_step_bytes(model, fam_name):
     D = model.in_size()
     P = model.n_params()
     total = 0
-    if fam_name in ("k_softmax_round", "k_mlp_round"):
-        # read+write W, read+write U, the mini-batch rows and labels
+    if fam_name == "k_mlp_round":
+        # streaming model: read+write W, read+write U, the mini-batch rows and labels
         return 16 * P + B * (4 * D + 4)
+    if fam_name == "k_softmax_round":
+        # compulsory model (replica and U stay on chip for the round): rows and labels;
+        # the 12 P bytes per round for reading w_global and writing w_c and U are added
+        # by the caller
+        return B * (4 * D + 4)
     if fam_name == "k_gather":
         return B * (8 * D + 8)
     if fam_name == "k_softmax_ce":
@@ -97,6 +102,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the MLP)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--rounds", type=int, default=0, help="exploration only: fewer rounds per client")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
@@ -112,6 +118,9 @@ def main():
         sys.exit(1)
 
     wl = W.CONFIGS[args.config]()
+    if args.rounds > 0:
+        wl.rounds = args.rounds
+        wl.name += f"_first{args.rounds}rounds"
     run = Run(wl)
     names = run.lib.profile_family_names()
     total_samples = wl.total_client_samples()
@@ -150,6 +159,12 @@ def main():
     value = total_samples * args.steps / dt
     fam = names[dom]
     bytes_per_job = per_step_bytes(wl.model, fam) * total_steps
+    model_name = "streaming (16P + B(4D+4) per recursion)"
+    if fam == "k_softmax_round":
+        bytes_per_job += 12 * wl.model.n_params() * wl.n_clients * wl.rounds
+        model_name = "compulsory (B(4D+4) per recursion + 12P per round)"
+    elif fam != "k_mlp_round":
+        model_name = "per-kernel operand bytes"
     launches_per_job = launches / args.steps
     avg_launch_ms = kernel_ms / max(launches, 1)
     achieved = (bytes_per_job / launches_per_job) / (avg_launch_ms * 1e-3) / 1e9
@@ -163,7 +178,7 @@ def main():
                    "client_samples_per_step": total_samples, "ticks_per_step": ticks,
                    "params": wl.model.n_params(), "agg_scale": wl.agg_scale},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": fam,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": fam, "byte_model": model_name,
                      "avg_launch_us": avg_launch_ms * 1e3, "launches_per_step": launches_per_job,
                      "algorithmic_bytes_per_launch": bytes_per_job / launches_per_job,
                      "share_of_kernel_time": share},

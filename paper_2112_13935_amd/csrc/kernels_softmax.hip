@@ -34,6 +34,25 @@ __device__ __forceinline__ float wave_sum_dpp(float v) {
     return v;
 }
 
+#define AET_DPP_ADD(v, ctrl, rmask, bc) \
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, rmask, 0xF, bc))
+template <int N>
+__device__ __forceinline__ void wave_sum_dpp_many(float (&v)[N]) {
+#pragma unroll
+    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0xB1, 0xF, true);
+#pragma unroll
+    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x4E, 0xF, true);
+#pragma unroll
+    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x141, 0xF, true);
+#pragma unroll
+    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x140, 0xF, true);
+#pragma unroll
+    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x142, 0xA, false);
+#pragma unroll
+    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x143, 0xC, false);
+}
+#undef AET_DPP_ADD
+
 // sum / max over each row of 16 lanes (every lane of the row gets the result)
 __device__ __forceinline__ float row_sum_dpp(float v) {
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
@@ -91,13 +110,19 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *__restrict__ Wg
         if (u + 1 < p.m) load_row(sample_row(p.key, (uint64_t)(p.q0 + u + 1), p.n_samples), xn, labn);
         // partial logits of this thread's columns, summed over the wave
         float(*zp)[16] = zpart[u & 1];
+        float s[C];
 #pragma unroll
         for (int o = 0; o < C; ++o) {
-            float s = 0.f;
+            s[o] = 0.f;
 #pragma unroll
-            for (int j = 0; j < NC; ++j) s += W[o][j] * x[j];
-            s = wave_sum_dpp(s);
-            if (lane == 63) zp[wave][o] = s;
+            for (int j = 0; j < NC; ++j) s[o] += W[o][j] * x[j];
+        }
+        // the C wave reductions advance stage by stage, so that consecutive DPP operations
+        // are independent of each other
+        wave_sum_dpp_many<C>(s);
+        if (lane == 63) {
+#pragma unroll
+            for (int o = 0; o < C; ++o) zp[wave][o] = s[o];
         }
         __syncthreads();
         // lane cls of every row: logit of class cls, then the softmax inside the row
