@@ -38,7 +38,7 @@ struct RoundRec {
 };
 
 struct Layout {
-    size_t w0, Wg, W, U, loss, params, arrivals, partial, debug, labels, fused;
+    size_t w0, Wg, W, U, loss, params, arrivals, partial, debug, labels, fused, wgrad;
     size_t act[AET_MAX_LAYERS + 1], del[AET_MAX_LAYERS + 1], amax[AET_MAX_LAYERS];
     size_t total;
     int max_chunks;
@@ -122,6 +122,11 @@ bool make_layout(const LayerGeom *lay, int L, int64_t P, int B, int n, int infli
     lo->debug = take((size_t)kDebugIdx * 4);
     lo->labels = take((size_t)n * B * 4);
     lo->fused = take(mlp_round_scratch_bytes(n, B));
+    size_t wg_floats = 0;
+    for (int l = 0; l < L; ++l)
+        if (lay[l].type == AET_CONV && conv_wgrad_mfma_supported(lay[l], B))
+            wg_floats = std::max(wg_floats, conv_wgrad_partial_floats(lay[l], B, n));
+    lo->wgrad = take(wg_floats * 4);
     const size_t samples = (size_t)n * B;
     lo->act[0] = take(samples * lay[0].in_size * 4);
     lo->del[0] = 0;
@@ -268,6 +273,7 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
     for (int l = 0; l < ctx->L; ++l)
         ctx->sc.amax[l] = ctx->lay[l].type == AET_POOL ? reinterpret_cast<uint8_t *>(ctx->ws + ctx->lo.amax[l]) : nullptr;
     ctx->sc.labels = reinterpret_cast<int32_t *>(ctx->ws + ctx->lo.labels);
+    ctx->sc.wgrad = reinterpret_cast<float *>(ctx->ws + ctx->lo.wgrad);
     ctx->engine = pick_engine(ctx->lay, ctx->L, ctx->B);
 
     hipError_t e = hipSuccess;

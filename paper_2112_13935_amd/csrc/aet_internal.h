@@ -50,6 +50,7 @@ struct LayerScratch {
     float *del[17];     // d loss / d act[l] (l >= 1)
     uint8_t *amax[16];  // pool layers: which of the 4 window elements was the maximum
     int32_t *labels;    // [n_clients][batch]
+    float *wgrad;       // partial sums of the convolution weight gradients
 };
 
 // Kernel families, for the optional per-launch timing with HIP events.
@@ -91,6 +92,16 @@ hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, c
                                      int n_arr, int64_t P);
 hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
                                 uint32_t n_samples, int32_t *dst);
+// convolution on the matrix cores (kernels_conv_mfma.hip); bwd = backward-data
+bool conv_mfma_supported(const LayerGeom &L, bool bwd);
+hipError_t launch_conv_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u, int B,
+                            const LayerGeom &L, bool bwd, const float *src, float *dst,
+                            const float *mask_src);
+bool conv_wgrad_mfma_supported(const LayerGeom &L, int B);
+size_t conv_wgrad_partial_floats(const LayerGeom &L, int B, int n_clients);
+hipError_t launch_conv_wgrad_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
+                                  int B, const LayerGeom &L, const float *in, const float *dout,
+                                  float *partial);
 // fused round of softmax regression, per-sample SGD (kernels_softmax.hip)
 bool softmax_round_supported(int D, int C, int B);
 hipError_t launch_softmax_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,

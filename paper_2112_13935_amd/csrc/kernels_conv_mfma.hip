@@ -1,0 +1,435 @@
+// Convolution layers of the layer-by-layer engine on the matrix cores (fp32 MFMA 16x16x4),
+// as implicit GEMMs over tiles staged in LDS.  Stride 1, square kernels, zero padding.
+//
+// Forward and backward-data are the same kernel:
+//   dst[dc][y][x] = sum_{sc,ky,kx} src[sc][y+ky-P][x+kx-P] * Wt[dc][sc][ky][kx]
+//   forward:        src = layer input,  dst = layer output, P = pad,
+//                   Wt[dc][sc][ky][kx] = W[dc][sc][ky][kx], then bias and ReLU;
+//   backward-data:  src = d(output),    dst = d(input),     P = K-1-pad,
+//                   Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx], then the ReLU mask of the
+//                   layer below.
+// GEMM view: M = pixels (tiles of 16 consecutive x), N = dst channels (tiles of 16),
+// K = (sc, ky, kx), walked in chunks of 8 source channels.  A workgroup owns R dst rows of
+// one sample (8 M tiles), all dst channels of its N block; each of its 4 waves owns 2 M
+// tiles and all N tiles.
+//
+// Backward-weight (g = sum over the mini-batch and all pixels of d(output) x input patch):
+//   M = output channels, N = (ci, ky, kx) plus one extra column for the bias, K = pixels.
+//   A workgroup accumulates its share of (sample, row block) work items in registers and
+//   writes one partial result; a second kernel adds the partials in fixed order, scales by
+//   1/B and applies  w <- w - eta g,  U <- U + g  (the gradient itself is never stored
+//   in the canonical layout).
+#include "aet_device.h"
+#include "aet_internal.h"
+
+namespace aet {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f4 mfma16x16x4(float a, float b, f4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
+}
+
+constexpr int kCch = 8;  // source channels per K chunk
+
+struct ConvDir {
+    int SC, DC;          // source / destination channels
+    int SH, SW, DH, DW;  // source / destination height and width
+    int P;               // padding in this direction
+    int R;               // dst rows per workgroup
+    int MPR;             // M tiles (16 columns) per dst row
+    int NT;              // N tiles (16 dst channels) per workgroup
+    int rowsT, SWP;      // rows and padded width of the staged source tile
+    int64_t src_size, dst_size;  // floats per sample
+    int64_t w_off, b_off;
+    int ic, oc;          // the layer's own channel counts (weight layout W[oc][ic][K][K])
+    int relu;
+};
+
+template <int KS, bool BWD>
+__global__ void __launch_bounds__(256)
+k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const float *__restrict__ src,
+            float *__restrict__ dst, const float *__restrict__ mask_src) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    constexpr int KCH = kCch * KS * KS;  // K elements per chunk
+    constexpr int KCHP = KCH + 4;        // padded weight row in LDS
+    constexpr int STEPS = KCH / 4;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const int nblk = blockIdx.x % ((g.DC + 16 * g.NT - 1) / (16 * g.NT));
+    const int rblk = blockIdx.x / ((g.DC + 16 * g.NT - 1) / (16 * g.NT));
+    const int y0 = rblk * g.R;
+    const int dc0 = nblk * 16 * g.NT;
+    const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
+    const gcf_ptr sg = as_global(src) + sample * g.src_size;
+    const gcf_ptr wg = as_global(p.W) + g.w_off;
+
+    extern __shared__ float smem[];
+    const int tile_plane = g.rowsT * g.SWP;
+    float *Ssm = smem;                          // [kCch][rowsT][SWP]
+    float *Wsm = Ssm + kCch * tile_plane;       // [16*NT][KCHP]
+    int *koff = reinterpret_cast<int *>(Wsm + 16 * g.NT * KCHP);  // [KCH]
+
+    for (int k = tid; k < KCH; k += 256) {
+        const int c = k / (KS * KS), r = k - c * KS * KS;
+        koff[k] = c * tile_plane + (r / KS) * g.SWP + (r % KS);
+    }
+
+    // the wave's two M tiles: (row, column chunk) inside the workgroup's block
+    int abase[2];
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int mt = 2 * wave + m;
+        const int row = mt / g.MPR, cch = mt - row * g.MPR;
+        abase[m] = row * g.SWP + 16 * cch + li;
+    }
+    f4 acc[2][4];
+#pragma unroll
+    for (int m = 0; m < 2; ++m)
+#pragma unroll
+        for (int n = 0; n < 4; ++n) acc[m][n] = f4{0.f, 0.f, 0.f, 0.f};
+
+    for (int c0 = 0; c0 < g.SC; c0 += kCch) {
+        __syncthreads();
+        // stage the source tile (zero outside the image and beyond the last channel)
+        for (int e = tid; e < kCch * tile_plane; e += 256) {
+            const int c = e / tile_plane, rem = e - c * tile_plane;
+            const int ty = rem / g.SWP, tx = rem - ty * g.SWP;
+            const int sy = y0 + ty - g.P, sx = tx - g.P;
+            float v = 0.f;
+            if (c0 + c < g.SC && sy >= 0 && sy < g.SH && sx >= 0 && sx < g.SW)
+                v = sg[((int64_t)(c0 + c) * g.SH + sy) * g.SW + sx];
+            Ssm[e] = v;
+        }
+        // stage the weights of this chunk: Wsm[dc][k], k = (c, ky, kx)
+        for (int e = tid; e < 16 * g.NT * KCH; e += 256) {
+            const int d = e / KCH, k = e - d * KCH;
+            const int c = k / (KS * KS), r = k - c * KS * KS;
+            float v = 0.f;
+            if (dc0 + d < g.DC && c0 + c < g.SC) {
+                if (BWD) {
+                    // Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]
+                    v = wg[((int64_t)(c0 + c) * g.ic + (dc0 + d)) * (KS * KS) + (KS * KS - 1 - r)];
+                } else {
+                    v = wg[((int64_t)(dc0 + d) * g.ic + (c0 + c)) * (KS * KS) + r];
+                }
+            }
+            Wsm[d * KCHP + k] = v;
+        }
+        __syncthreads();
+        for (int s = 0; s < STEPS; ++s) {
+            const int k = 4 * s + lg;
+            const int ko = koff[k];
+            const float a0 = Ssm[abase[0] + ko];
+            const float a1 = Ssm[abase[1] + ko];
+#pragma unroll
+            for (int n = 0; n < 4; ++n) {
+                if (n < g.NT) {
+                    const float b = Wsm[(16 * n + li) * KCHP + k];
+                    acc[0][n] = mfma16x16x4(a0, b, acc[0][n]);
+                    acc[1][n] = mfma16x16x4(a1, b, acc[1][n]);
+                }
+            }
+        }
+    }
+
+    // epilogue: lane holds dst channel dc0+16n+li, 4 consecutive x
+    const gf_ptr dg = as_global(dst) + sample * g.dst_size;
+    const gcf_ptr mg = mask_src ? as_global(mask_src) + sample * g.dst_size : nullptr;
+#pragma unroll
+    for (int m = 0; m < 2; ++m) {
+        const int mt = 2 * wave + m;
+        const int row = mt / g.MPR, cch = mt - row * g.MPR;
+        const int y = y0 + row;
+        if (row >= g.R || y >= g.DH) continue;
+#pragma unroll
+        for (int n = 0; n < 4; ++n) {
+            if (n >= g.NT) continue;
+            const int dc = dc0 + 16 * n + li;
+            if (dc >= g.DC) continue;
+            const float bias = BWD ? 0.f : as_global(p.W)[g.b_off + dc];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int x = 16 * cch + 4 * lg + r;
+                if (x >= g.DW) continue;
+                const int64_t i = ((int64_t)dc * g.DH + y) * g.DW + x;
+                float v = acc[m][n][r] + bias;
+                if (BWD) {
+                    if (mg && !(mg[i] > 0.f)) v = 0.f;
+                } else if (g.relu && !(v > 0.f)) {
+                    v = 0.f;
+                }
+                dg[i] = v;
+            }
+        }
+    }
+}
+
+static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d) {
+    const int KS = L.k;
+    if (!(KS == 3 || KS == 5)) return false;
+    d->ic = L.ic; d->oc = L.oc; d->relu = L.relu;
+    d->w_off = L.w_off; d->b_off = L.b_off;
+    if (!bwd) {
+        d->SC = L.ic; d->DC = L.oc; d->SH = L.ih; d->SW = L.iw; d->DH = L.oh; d->DW = L.ow; d->P = L.pad;
+        d->src_size = L.in_size; d->dst_size = L.out_size;
+    } else {
+        d->SC = L.oc; d->DC = L.ic; d->SH = L.oh; d->SW = L.ow; d->DH = L.ih; d->DW = L.iw; d->P = KS - 1 - L.pad;
+        d->src_size = L.out_size; d->dst_size = L.in_size;
+    }
+    if (d->DW > 128) return false;
+    d->MPR = (d->DW + 15) / 16;
+    if (d->MPR > 8) return false;
+    d->R = 8 / d->MPR;
+    if (d->R < 1) d->R = 1;
+    // the 4 waves own 8 M tiles; with MPR in {3, 5, 6, 7} some tiles stay unused
+    d->NT = (d->DC + 15) / 16;
+    if (d->NT > 4) d->NT = 4;
+    d->rowsT = d->R + KS - 1;
+    d->SWP = 16 * d->MPR + KS - 1;
+    d->SWP += (d->SWP & 1) ? 0 : 1;  // odd row stride: fewer LDS bank conflicts
+    return true;
+}
+
+static size_t conv_lds_bytes(const ConvDir &d, int KS) {
+    const int KCH = kCch * KS * KS;
+    return sizeof(float) * ((size_t)kCch * d.rowsT * d.SWP + (size_t)16 * d.NT * (KCH + 4)) + sizeof(int) * KCH;
+}
+
+bool conv_mfma_supported(const LayerGeom &L, bool bwd) {
+    ConvDir d;
+    if (!conv_dir(L, bwd, &d)) return false;
+    return conv_lds_bytes(d, L.k) <= 64 * 1024;
+}
+
+hipError_t launch_conv_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u, int B,
+                            const LayerGeom &L, bool bwd, const float *src, float *dst,
+                            const float *mask_src) {
+    ConvDir d;
+    if (!conv_dir(L, bwd, &d)) return hipErrorInvalidValue;
+    const size_t lds = conv_lds_bytes(d, L.k);
+    const int nblocks = (d.DC + 16 * d.NT - 1) / (16 * d.NT);
+    const int rblocks = (d.DH + d.R - 1) / d.R;
+    dim3 grid((unsigned)(nblocks * rblocks), (unsigned)B, (unsigned)nact);
+    const int fam = bwd ? F_CONV_BWD_DATA : F_CONV_FWD;
+    const bool timed = prof && prof->on[fam];
+    if (timed) prof->before(fam, s);
+    if (L.k == 3) {
+        if (bwd) k_conv_mfma<3, true><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);
+        else k_conv_mfma<3, false><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);
+    } else {
+        if (bwd) k_conv_mfma<5, true><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);
+        else k_conv_mfma<5, false><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);
+    }
+    if (timed) prof->after(fam, s);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// backward-weight
+// ---------------------------------------------------------------------------------------
+struct WgradGeom {
+    int IC, OC, IH, IW, OH, OW, pad;
+    int R;            // output rows per work item
+    int rowsT, SWP;   // staged input tile: rows and padded width
+    int OWP;          // output width rounded up to a multiple of 4
+    int KTOT;         // IC*K*K + 1 (the extra column multiplies by one: the bias)
+    int NTT, MTT;     // N tiles (of 16 k) and M tiles (of 16 output channels) in total
+    int items_per_sample, S;
+    int64_t in_size, out_size, w_off, b_off;
+};
+
+template <int KS, int MT, int NTW>
+__global__ void __launch_bounds__(256)
+k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
+                  const float *__restrict__ in, const float *__restrict__ dout,
+                  float *__restrict__ partial) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const int sl = blockIdx.x;
+
+    extern __shared__ float smem[];
+    const int plane = g.rowsT * g.SWP;
+    float *Ism = smem;                       // [IC + 2][rowsT][SWP]; plane IC = ones, IC+1 = zeros
+    float *Dsm = Ism + (g.IC + 2) * plane;   // [16*MT][R][OWP]
+    const int dplane = g.R * g.OWP;
+
+    for (int e = tid; e < 2 * plane; e += 256) Ism[g.IC * plane + e] = e < plane ? 1.f : 0.f;
+
+    // B operand: lane li of N tile nt holds column k = 16*nt + li of the GEMM
+    int kb[NTW];
+#pragma unroll
+    for (int j = 0; j < NTW; ++j) {
+        const int k = 16 * (wave + 4 * j) + li;
+        int off = (g.IC + 1) * plane;  // zeros
+        if (k < g.IC * KS * KS) {
+            const int c = k / (KS * KS), r = k - c * KS * KS;
+            off = c * plane + (r / KS) * g.SWP + (r % KS);
+        } else if (k == g.IC * KS * KS) {
+            off = g.IC * plane;        // ones
+        }
+        kb[j] = off + lg;
+    }
+    f4 acc[MT][NTW];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) acc[m][j] = f4{0.f, 0.f, 0.f, 0.f};
+
+    const int items = B * g.items_per_sample;
+    for (int it = sl; it < items; it += g.S) {
+        const int b = it / g.items_per_sample, rb = it - b * g.items_per_sample;
+        const int y0 = rb * g.R;
+        const int64_t sample = (int64_t)blockIdx.z * B + b;
+        const gcf_ptr ig = as_global(in) + sample * g.in_size;
+        const gcf_ptr dg = as_global(dout) + sample * g.out_size;
+        __syncthreads();
+        for (int e = tid; e < g.IC * plane; e += 256) {
+            const int c = e / plane, rem = e - c * plane;
+            const int ty = rem / g.SWP, tx = rem - ty * g.SWP;
+            const int sy = y0 + ty - g.pad, sx = tx - g.pad;
+            float v = 0.f;
+            if (sy >= 0 && sy < g.IH && sx >= 0 && sx < g.IW) v = ig[((int64_t)c * g.IH + sy) * g.IW + sx];
+            Ism[e] = v;
+        }
+        for (int e = tid; e < 16 * MT * dplane; e += 256) {
+            const int co = e / dplane, rem = e - co * dplane;
+            const int r = rem / g.OWP, x = rem - r * g.OWP;
+            float v = 0.f;
+            if (co < g.OC && y0 + r < g.OH && x < g.OW) v = dg[((int64_t)co * g.OH + y0 + r) * g.OW + x];
+            Dsm[e] = v;
+        }
+        __syncthreads();
+        for (int r = 0; r < g.R; ++r) {
+            for (int x4 = 0; x4 < g.OWP; x4 += 4) {
+                float a[MT];
+#pragma unroll
+                for (int m = 0; m < MT; ++m) a[m] = Dsm[(16 * m + li) * dplane + r * g.OWP + x4 + lg];
+                const int po = r * g.SWP + x4;
+#pragma unroll
+                for (int j = 0; j < NTW; ++j) {
+                    const float bv = Ism[kb[j] + po];
+#pragma unroll
+                    for (int m = 0; m < MT; ++m) acc[m][j] = mfma16x16x4(a[m], bv, acc[m][j]);
+                }
+            }
+        }
+    }
+    // partial[a][slice][co][k]: lane holds k = 16*nt + li, co = 16*m + 4*lg + r
+    const int KP = 16 * g.NTT, OCP = 16 * g.MTT;
+    const gf_ptr pg = as_global(partial) + ((int64_t)blockIdx.z * g.S + sl) * OCP * KP;
+#pragma unroll
+    for (int j = 0; j < NTW; ++j) {
+        const int nt = wave + 4 * j;
+        if (nt >= g.NTT) continue;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            if (m >= g.MTT) continue;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) pg[(int64_t)(16 * m + 4 * lg + r) * KP + 16 * nt + li] = acc[m][j][r];
+        }
+    }
+}
+
+// g = (sum of the partials in slice order) / B;  w <- w - eta g;  U <- U + g
+__global__ void __launch_bounds__(256)
+k_conv_wgrad_finish(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g, int KSQ,
+                    const float *__restrict__ partial) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    const int co = blockIdx.y;
+    if (k >= g.KTOT) return;
+    const int KP = 16 * g.NTT, OCP = 16 * g.MTT;
+    const gcf_ptr pg = as_global(partial) + (int64_t)blockIdx.z * g.S * OCP * KP + (int64_t)co * KP + k;
+    float s = 0.f;
+    for (int sl = 0; sl < g.S; ++sl) s += pg[(int64_t)sl * OCP * KP];
+    s *= 1.0f / (float)B;
+    const int64_t wi = k < g.IC * KSQ ? g.w_off + (int64_t)co * g.IC * KSQ + k : g.b_off + co;
+    as_global(p.W)[wi] -= p.eta * s;
+    as_global(p.U)[wi] += s;
+}
+
+constexpr int kWgradTarget = 512;  // workgroups the partial sums are spread over
+
+static bool wgrad_geom(const LayerGeom &L, int B, int nact, WgradGeom *g) {
+    const int KS = L.k;
+    if (!(KS == 3 || KS == 5)) return false;
+    g->IC = L.ic; g->OC = L.oc; g->IH = L.ih; g->IW = L.iw; g->OH = L.oh; g->OW = L.ow; g->pad = L.pad;
+    g->in_size = L.in_size; g->out_size = L.out_size; g->w_off = L.w_off; g->b_off = L.b_off;
+    g->KTOT = L.ic * KS * KS + 1;
+    g->NTT = (g->KTOT + 15) / 16;
+    g->MTT = (L.oc + 15) / 16;
+    if (g->MTT > 4 || g->NTT > 40) return false;
+    g->R = L.oh < 4 ? L.oh : 4;
+    g->rowsT = g->R + KS - 1;
+    g->OWP = (L.ow + 3) / 4 * 4;
+    g->SWP = g->OWP + KS - 1;
+    g->SWP += (g->SWP & 1) ? 0 : 1;
+    g->items_per_sample = (L.oh + g->R - 1) / g->R;
+    const int items = B * g->items_per_sample;
+    int S = (kWgradTarget + nact - 1) / nact;
+    if (S > items) S = items;
+    if (S < 1) S = 1;
+    g->S = S;
+    return true;
+}
+
+static int wgrad_mt(const WgradGeom &g) { return g.MTT <= 2 ? 2 : 4; }
+static int wgrad_ntw(const WgradGeom &g) {
+    const int n = (g.NTT + 3) / 4;
+    return n <= 2 ? 2 : n <= 5 ? 5 : 10;
+}
+static size_t wgrad_lds_bytes(const WgradGeom &g) {
+    return sizeof(float) * ((size_t)(g.IC + 2) * g.rowsT * g.SWP + (size_t)16 * wgrad_mt(g) * g.R * g.OWP);
+}
+
+bool conv_wgrad_mfma_supported(const LayerGeom &L, int B) {
+    WgradGeom g;
+    if (!wgrad_geom(L, B, 1, &g)) return false;
+    return wgrad_lds_bytes(g) <= 64 * 1024;
+}
+
+// floats of partial-sum scratch the layer needs, whatever the number of active clients
+size_t conv_wgrad_partial_floats(const LayerGeom &L, int B, int n_clients) {
+    WgradGeom g;
+    if (!wgrad_geom(L, B, 1, &g)) return 0;
+    // nact * S <= kWgradTarget + nact
+    return (size_t)(kWgradTarget + n_clients) * 16 * g.MTT * 16 * g.NTT;
+}
+
+template <int KS>
+static void wgrad_launch(hipStream_t s, dim3 grid, size_t lds, int mt, int ntw, const RoundParams *dp, int u,
+                         int B, const WgradGeom &g, const float *in, const float *dout, float *partial) {
+#define AET_WG(MTv, NTWv)                                                                          \
+    if (mt == MTv && ntw == NTWv) {                                                                \
+        k_conv_wgrad_mfma<KS, MTv, NTWv><<<grid, 256, lds, s>>>(dp, u, B, g, in, dout, partial); \
+        return;                                                                                    \
+    }
+    AET_WG(2, 2) AET_WG(2, 5) AET_WG(2, 10) AET_WG(4, 2) AET_WG(4, 5) AET_WG(4, 10)
+#undef AET_WG
+}
+
+hipError_t launch_conv_wgrad_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
+                                  int B, const LayerGeom &L, const float *in, const float *dout,
+                                  float *partial) {
+    WgradGeom g;
+    if (!wgrad_geom(L, B, nact, &g)) return hipErrorInvalidValue;
+    const size_t lds = wgrad_lds_bytes(g);
+    const bool timed = prof && prof->on[F_CONV_BWD_WEIGHT];
+    if (timed) prof->before(F_CONV_BWD_WEIGHT, s);
+    dim3 grid((unsigned)g.S, 1, (unsigned)nact);
+    if (L.k == 3) wgrad_launch<3>(s, grid, lds, wgrad_mt(g), wgrad_ntw(g), dp, u, B, g, in, dout, partial);
+    else wgrad_launch<5>(s, grid, lds, wgrad_mt(g), wgrad_ntw(g), dp, u, B, g, in, dout, partial);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess) {
+        dim3 fgrid((unsigned)((g.KTOT + 255) / 256), (unsigned)g.OC, (unsigned)nact);
+        k_conv_wgrad_finish<<<fgrid, 256, 0, s>>>(dp, u, B, g, L.k * L.k, partial);
+        e = hipGetLastError();
+    }
+    if (timed) prof->after(F_CONV_BWD_WEIGHT, s);
+    return e;
+}
+
+}  // namespace aet

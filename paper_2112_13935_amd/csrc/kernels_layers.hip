@@ -12,6 +12,8 @@
 //   gradient g and applies  w <- w - eta g,  U <- U + g  in the same kernel
 //   (k_*_bwd_weight), so g never goes to memory.
 // Clients whose round has fewer recursions than the step counter simply exit.
+#include <cstdlib>
+
 #include "aet_device.h"
 #include "aet_internal.h"
 
@@ -344,9 +346,19 @@ static hipError_t conv_step(hipStream_t s, Profiler *prof, const RoundParams *dp
     return hipGetLastError();
 }
 
+// AET_NAIVE_CONV=1 keeps the plain kernels (used to cross-check the matrix-core path)
+static bool use_mfma_conv() {
+    static const bool v = [] { const char *e = std::getenv("AET_NAIVE_CONV"); return !(e && e[0] == '1'); }();
+    return v;
+}
+
 static hipError_t conv_dispatch(int ks, hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                                 int B, const LayerGeom &g, int which, const float *a,
                                 const float *b, float *c, const float *mask) {
+    if (which < 2 && use_mfma_conv() && conv_mfma_supported(g, which == 1))
+        return launch_conv_mfma(s, prof, dp, nact, u, B, g, which == 1, a, c, mask);
+    if (which == 2 && use_mfma_conv() && c && conv_wgrad_mfma_supported(g, B))
+        return launch_conv_wgrad_mfma(s, prof, dp, nact, u, B, g, a, b, c);
     switch (ks) {
         case 1: return conv_step<1>(s, prof, dp, nact, u, B, g, which, a, b, c, mask);
         case 2: return conv_step<2>(s, prof, dp, nact, u, B, g, which, a, b, c, mask);
@@ -392,7 +404,7 @@ hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *d
                 AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 1, sc.del[l + 1], nullptr,
                                             sc.del[l], mask));
             AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 2, sc.act[l], sc.del[l + 1],
-                                        nullptr, nullptr));
+                                        sc.wgrad, nullptr));
         } else if (g.type == 1) {
             if (l > 0) {
                 dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
