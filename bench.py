@@ -140,7 +140,9 @@ def main():
     fam_ms = [run.lib.aet_profile_read(f) for f in range(len(names))]
     run.lib.aet_profile_enable(-1, False)
     dom = int(np.argmax([ms for _, ms in fam_ms]))
-    share = fam_ms[dom][1] / max(sum(ms for _, ms in fam_ms), 1e-12)
+    total_ms = max(sum(ms for _, ms in fam_ms), 1e-12)
+    share = fam_ms[dom][1] / total_ms
+    shares = {names[f]: round(ms / total_ms, 4) for f, (_, ms) in enumerate(fam_ms) if ms > 0}
 
     run.lib.aet_profile_enable(dom, True)
     run.lib.aet_synchronize()
@@ -181,7 +183,7 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": fam, "byte_model": model_name,
                      "avg_launch_us": avg_launch_ms * 1e3, "launches_per_step": launches_per_job,
                      "algorithmic_bytes_per_launch": bytes_per_job / launches_per_job,
-                     "share_of_kernel_time": share},
+                     "share_of_kernel_time": share, "kernel_time_shares": shares},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)

@@ -274,6 +274,11 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
         ctx->sc.amax[l] = ctx->lay[l].type == AET_POOL ? reinterpret_cast<uint8_t *>(ctx->ws + ctx->lo.amax[l]) : nullptr;
     ctx->sc.labels = reinterpret_cast<int32_t *>(ctx->ws + ctx->lo.labels);
     ctx->sc.wgrad = reinterpret_cast<float *>(ctx->ws + ctx->lo.wgrad);
+    {
+        // AET_PLAIN_LAYERS=1: plain FMA kernels, to cross-check the matrix-core layer kernels
+        const char *e = std::getenv("AET_PLAIN_LAYERS");
+        ctx->sc.plain = e && e[0] == '1';
+    }
     ctx->engine = pick_engine(ctx->lay, ctx->L, ctx->B);
 
     hipError_t e = hipSuccess;

@@ -51,6 +51,7 @@ struct LayerScratch {
     uint8_t *amax[16];  // pool layers: which of the 4 window elements was the maximum
     int32_t *labels;    // [n_clients][batch]
     float *wgrad;       // partial sums of the convolution weight gradients
+    bool plain;         // use the plain (non matrix-core) layer kernels
 };
 
 // Kernel families, for the optional per-launch timing with HIP events.
@@ -102,6 +103,10 @@ size_t conv_wgrad_partial_floats(const LayerGeom &L, int B, int n_clients);
 hipError_t launch_conv_wgrad_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                                   int B, const LayerGeom &L, const float *in, const float *dout,
                                   float *partial);
+// dense layers on the matrix cores (kernels_dense_mfma.hip); mode 0 fwd, 1 bwd-data, 2 bwd-weight
+hipError_t launch_dense_mfma(hipStream_t s, Profiler *prof, int mode, const RoundParams *dp, int nact,
+                             int u, int B, int K, int O, int64_t w_off, int64_t b_off, int relu,
+                             const float *x, const float *y, float *z, const float *mask_src);
 // fused round of softmax regression, per-sample SGD (kernels_softmax.hip)
 bool softmax_round_supported(int D, int C, int B);
 hipError_t launch_softmax_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,

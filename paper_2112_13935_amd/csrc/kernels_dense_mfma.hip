@@ -1,0 +1,167 @@
+// Dense layers of the layer-by-layer engine on the matrix cores (fp32 MFMA 16x16x4):
+// one 64 x 64 output tile per workgroup, operands staged through LDS in chunks of 32 along
+// the contraction, batched over the active clients (blockIdx.z).
+//
+//   FWD         out[b][o] = relu?(bias[o] + sum_k in[b][k] W[o][k])      M = b, N = o, K = k
+//   BWD_DATA    din[b][k] = mask * sum_o dout[b][o] W[o][k]              M = b, N = k, K = o
+//   BWD_WEIGHT  g[o][k]  = (1/B) sum_b dout[b][o] in[b][k], then
+//               W -= eta g, U += g (and the bias) in the epilogue        M = o, N = k, K = b
+// The accumulator tile of BWD_WEIGHT is applied to W and U directly: g never goes to memory.
+#include "aet_device.h"
+#include "aet_internal.h"
+
+namespace aet {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+
+enum { DENSE_FWD = 0, DENSE_BWD_DATA = 1, DENSE_BWD_WEIGHT = 2 };
+
+constexpr int kDT = 64;   // output tile edge
+constexpr int kDK = 32;   // contraction chunk
+
+template <int MODE>
+__global__ void __launch_bounds__(256)
+k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
+             int64_t b_off, int relu, const float *__restrict__ x, const float *__restrict__ y,
+             float *__restrict__ z, const float *__restrict__ mask_src) {
+    // x: in (FWD, BWD_WEIGHT) or dout (BWD_DATA); y: dout (BWD_WEIGHT); z: out / din
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const gcf_ptr W = as_global(p.W) + w_off;
+    const int64_t cb = (int64_t)blockIdx.z * B;  // first sample of this client in the scratch
+
+    // GEMM extents
+    const int M = MODE == DENSE_BWD_WEIGHT ? O : B;
+    const int N = MODE == DENSE_FWD ? O : K;
+    const int KD = MODE == DENSE_FWD ? K : (MODE == DENSE_BWD_DATA ? O : B);
+    const int m0 = blockIdx.y * kDT, n0 = blockIdx.x * kDT;
+
+    __shared__ float As[kDT][kDK + 1];   // As[m][kk]
+    __shared__ float Bs[kDK][kDT + 1];   // Bs[kk][n]
+
+    // element (m, kd) of the left operand and (kd, n) of the right one, zero outside
+    auto left = [&](int m, int kd) -> float {
+        if (m >= M || kd >= KD) return 0.f;
+        if (MODE == DENSE_FWD) return as_global(x)[(cb + m) * K + kd];          // in[b][k]
+        if (MODE == DENSE_BWD_DATA) return as_global(x)[(cb + m) * O + kd];     // dout[b][o]
+        return as_global(y)[(cb + kd) * O + m];                                  // dout[b][o], m = o
+    };
+    auto right = [&](int kd, int n) -> float {
+        if (n >= N || kd >= KD) return 0.f;
+        if (MODE == DENSE_FWD) return W[(int64_t)n * K + kd];                   // W[o][k]
+        if (MODE == DENSE_BWD_DATA) return W[(int64_t)kd * K + n];              // W[o][k], n = k
+        return as_global(x)[(cb + kd) * K + n];                                  // in[b][k]
+    };
+
+    // wave w owns N tile w and all four M tiles
+    f4 acc[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) acc[m] = f4{0.f, 0.f, 0.f, 0.f};
+
+    for (int k0 = 0; k0 < KD; k0 += kDK) {
+        __syncthreads();
+        // stage with the thread index running along the dimension that is contiguous in memory
+        if (MODE == DENSE_BWD_WEIGHT) {
+            for (int e = tid; e < kDT * kDK; e += 256) {  // m fastest
+                const int kk = e / kDT, m = e - kk * kDT;
+                As[m][kk] = left(m0 + m, k0 + kk);
+            }
+        } else {
+            for (int e = tid; e < kDT * kDK; e += 256) {  // kd fastest
+                const int m = e / kDK, kk = e - m * kDK;
+                As[m][kk] = left(m0 + m, k0 + kk);
+            }
+        }
+        if (MODE == DENSE_FWD) {
+            for (int e = tid; e < kDT * kDK; e += 256) {  // kd fastest
+                const int n = e / kDK, kk = e - n * kDK;
+                Bs[kk][n] = right(k0 + kk, n0 + n);
+            }
+        } else {
+            for (int e = tid; e < kDT * kDK; e += 256) {  // n fastest
+                const int kk = e / kDT, n = e - kk * kDT;
+                Bs[kk][n] = right(k0 + kk, n0 + n);
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < kDK / 4; ++s) {
+            const float b = Bs[4 * s + lg][16 * wave + li];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(As[16 * m + li][4 * s + lg], b, acc[m], 0, 0, 0);
+        }
+    }
+
+    // epilogue: lane holds column n = n0 + 16*wave + li and rows m = m0 + 16*mt + 4*lg + r
+    const int n = n0 + 16 * wave + li;
+    if (MODE == DENSE_BWD_WEIGHT) {
+        const float invB = 1.0f / (float)B;
+        const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
+        if (n < N) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int o = m0 + 16 * mt + 4 * lg + r;
+                    if (o < M) {
+                        const float g = acc[mt][r] * invB;
+                        const int64_t wi = w_off + (int64_t)o * K + n;
+                        Wc[wi] -= p.eta * g;
+                        Uc[wi] += g;
+                    }
+                }
+        }
+        // bias: the first column block sums dout over the mini-batch
+        if (blockIdx.x == 0 && tid < kDT && m0 + tid < O) {
+            const int o = m0 + tid;
+            float s = 0.f;
+            for (int b = 0; b < B; ++b) s += as_global(y)[(cb + b) * O + o];
+            s *= invB;
+            Wc[b_off + o] -= p.eta * s;
+            Uc[b_off + o] += s;
+        }
+    } else {
+        const gf_ptr zg = as_global(z);
+        if (n < N) {
+            const float bias = MODE == DENSE_FWD ? as_global(p.W)[b_off + n] : 0.f;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int b = m0 + 16 * mt + 4 * lg + r;
+                    if (b < M) {
+                        float v = acc[mt][r] + bias;
+                        const int64_t i = (cb + b) * N + n;
+                        if (MODE == DENSE_FWD) {
+                            if (relu && !(v > 0.f)) v = 0.f;
+                        } else if (mask_src && !(as_global(mask_src)[i] > 0.f)) {
+                            v = 0.f;
+                        }
+                        zg[i] = v;
+                    }
+                }
+        }
+    }
+}
+
+hipError_t launch_dense_mfma(hipStream_t s, Profiler *prof, int mode, const RoundParams *dp, int nact,
+                             int u, int B, int K, int O, int64_t w_off, int64_t b_off, int relu,
+                             const float *x, const float *y, float *z, const float *mask_src) {
+    const int M = mode == DENSE_BWD_WEIGHT ? O : B;
+    const int N = mode == DENSE_FWD ? O : K;
+    dim3 grid((unsigned)((N + kDT - 1) / kDT), (unsigned)((M + kDT - 1) / kDT), (unsigned)nact);
+    const int fam = mode == DENSE_FWD ? F_DENSE_FWD : mode == DENSE_BWD_DATA ? F_DENSE_BWD_DATA : F_DENSE_BWD_WEIGHT;
+    const bool timed = prof && prof->on[fam];
+    if (timed) prof->before(fam, s);
+    if (mode == DENSE_FWD)
+        k_dense_mfma<DENSE_FWD><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
+    else if (mode == DENSE_BWD_DATA)
+        k_dense_mfma<DENSE_BWD_DATA><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
+    else
+        k_dense_mfma<DENSE_BWD_WEIGHT><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
+    if (timed) prof->after(fam, s);
+    return hipGetLastError();
+}
+
+}  // namespace aet

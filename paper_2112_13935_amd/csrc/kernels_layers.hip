@@ -12,8 +12,6 @@
 //   gradient g and applies  w <- w - eta g,  U <- U + g  in the same kernel
 //   (k_*_bwd_weight), so g never goes to memory.
 // Clients whose round has fewer recursions than the step counter simply exit.
-#include <cstdlib>
-
 #include "aet_device.h"
 #include "aet_internal.h"
 
@@ -346,18 +344,12 @@ static hipError_t conv_step(hipStream_t s, Profiler *prof, const RoundParams *dp
     return hipGetLastError();
 }
 
-// AET_NAIVE_CONV=1 keeps the plain kernels (used to cross-check the matrix-core path)
-static bool use_mfma_conv() {
-    static const bool v = [] { const char *e = std::getenv("AET_NAIVE_CONV"); return !(e && e[0] == '1'); }();
-    return v;
-}
-
 static hipError_t conv_dispatch(int ks, hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                                 int B, const LayerGeom &g, int which, const float *a,
-                                const float *b, float *c, const float *mask) {
-    if (which < 2 && use_mfma_conv() && conv_mfma_supported(g, which == 1))
+                                const float *b, float *c, const float *mask, bool mfma) {
+    if (which < 2 && mfma && conv_mfma_supported(g, which == 1))
         return launch_conv_mfma(s, prof, dp, nact, u, B, g, which == 1, a, c, mask);
-    if (which == 2 && use_mfma_conv() && c && conv_wgrad_mfma_supported(g, B))
+    if (which == 2 && mfma && c && conv_wgrad_mfma_supported(g, B))
         return launch_conv_wgrad_mfma(s, prof, dp, nact, u, B, g, a, b, c);
     switch (ks) {
         case 1: return conv_step<1>(s, prof, dp, nact, u, B, g, which, a, b, c, mask);
@@ -381,11 +373,14 @@ hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *d
         const LayerGeom &g = lay[l];
         if (g.type == 0) {
             AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 0, sc.act[l], nullptr,
-                                        sc.act[l + 1], nullptr));
+                                        sc.act[l + 1], nullptr, !sc.plain));
         } else if (g.type == 1) {
             dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
             AET_TIMED(F_POOL_FWD, k_pool_fwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.act[l], sc.act[l + 1], sc.amax[l]));
             AET_RETURN_IF(hipGetLastError());
+        } else if (!sc.plain) {
+            AET_RETURN_IF(launch_dense_mfma(s, prof, 0, dp, nact, u, B, (int)g.in_size, g.oc, g.w_off, g.b_off,
+                                            g.relu, sc.act[l], nullptr, sc.act[l + 1], nullptr));
         } else {
             dim3 grid((g.oc + 3) / 4, 1, nact);
             AET_TIMED(F_DENSE_FWD, k_dense_fwd<<<grid, 256, 0, s>>>(dp, u, B, (int)g.in_size, g.oc, g.w_off, g.b_off,
@@ -402,15 +397,22 @@ hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *d
         if (g.type == 0) {
             if (l > 0)
                 AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 1, sc.del[l + 1], nullptr,
-                                            sc.del[l], mask));
+                                            sc.del[l], mask, !sc.plain));
             AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 2, sc.act[l], sc.del[l + 1],
-                                        sc.wgrad, nullptr));
+                                        sc.wgrad, nullptr, !sc.plain));
         } else if (g.type == 1) {
             if (l > 0) {
                 dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
                 AET_TIMED(F_POOL_BWD, k_pool_bwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.del[l + 1], sc.amax[l], sc.del[l], mask));
                 AET_RETURN_IF(hipGetLastError());
             }
+        } else if (!sc.plain) {
+            const int K = (int)g.in_size;
+            if (l > 0)
+                AET_RETURN_IF(launch_dense_mfma(s, prof, 1, dp, nact, u, B, K, g.oc, g.w_off, g.b_off, 0,
+                                                sc.del[l + 1], nullptr, sc.del[l], mask));
+            AET_RETURN_IF(launch_dense_mfma(s, prof, 2, dp, nact, u, B, K, g.oc, g.w_off, g.b_off, 0,
+                                            sc.act[l], sc.del[l + 1], nullptr, nullptr));
         } else {
             const int K = (int)g.in_size;
             if (l > 0) {

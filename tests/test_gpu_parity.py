@@ -115,6 +115,17 @@ def test_layer_engine_on_fused_shapes(gpu, oracle_libs, monkeypatch):
     run.close()
 
 
+@pytest.mark.parametrize("name", ["lenet16_factors_stragglers", "cnn8_factors", "mlp_ragged_stragglers"])
+def test_plain_layer_kernels(gpu, oracle_libs, monkeypatch, name):
+    """The plain FMA layer kernels (the matrix-core ones switched off) against the oracle."""
+    from parity import lockstep
+    monkeypatch.setenv("AET_PLAIN_LAYERS", "1")
+    wl = small_cases()[name]
+    run, orc = _both(gpu, wl)
+    report("plain layer kernels on " + name, lockstep(wl, run, orc))
+    run.close()
+
+
 def test_U_invariant_on_gpu(gpu):
     """w_start - w_end = eta_i U_i holds for the GPU's own numbers (fp32 rounding)."""
     wl = small_cases()["mlp_fused_b16_ragged_d"]
