@@ -30,7 +30,8 @@ __device__ __forceinline__ f4 mfma16x16x4(float a, float b, f4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-constexpr int kCch = 8;  // source channels per K chunk
+constexpr int kCch = 8;    // source channels per K chunk
+constexpr int kStage = 8;  // global loads in flight per thread while a tile is staged
 
 struct ConvDir {
     int SC, DC;          // source / destination channels
@@ -92,29 +93,46 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     for (int c0 = 0; c0 < g.SC; c0 += kCch) {
         __syncthreads();
         // stage the source tile (zero outside the image and beyond the last channel)
-        for (int e = tid; e < kCch * tile_plane; e += 256) {
-            const int c = e / tile_plane, rem = e - c * tile_plane;
-            const int ty = rem / g.SWP, tx = rem - ty * g.SWP;
-            const int sy = y0 + ty - g.P, sx = tx - g.P;
-            float v = 0.f;
-            if (c0 + c < g.SC && sy >= 0 && sy < g.SH && sx >= 0 && sx < g.SW)
-                v = sg[((int64_t)(c0 + c) * g.SH + sy) * g.SW + sx];
-            Ssm[e] = v;
+        // (loads are issued in batches of kStage so that their latencies overlap)
+        for (int e0 = tid; e0 < kCch * tile_plane; e0 += 256 * kStage) {
+            float v[kStage];
+#pragma unroll
+            for (int q = 0; q < kStage; ++q) {
+                const int e = e0 + 256 * q;
+                const int c = e / tile_plane, rem = e - c * tile_plane;
+                const int ty = rem / g.SWP, tx = rem - ty * g.SWP;
+                const int sy = y0 + ty - g.P, sx = tx - g.P;
+                v[q] = 0.f;
+                if (e < kCch * tile_plane && c0 + c < g.SC && sy >= 0 && sy < g.SH && sx >= 0 && sx < g.SW)
+                    v[q] = sg[((int64_t)(c0 + c) * g.SH + sy) * g.SW + sx];
+            }
+#pragma unroll
+            for (int q = 0; q < kStage; ++q)
+                if (e0 + 256 * q < kCch * tile_plane) Ssm[e0 + 256 * q] = v[q];
         }
         // stage the weights of this chunk: Wsm[dc][k], k = (c, ky, kx)
-        for (int e = tid; e < 16 * g.NT * KCH; e += 256) {
-            const int d = e / KCH, k = e - d * KCH;
-            const int c = k / (KS * KS), r = k - c * KS * KS;
-            float v = 0.f;
-            if (dc0 + d < g.DC && c0 + c < g.SC) {
-                if (BWD) {
-                    // Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]
-                    v = wg[((int64_t)(c0 + c) * g.ic + (dc0 + d)) * (KS * KS) + (KS * KS - 1 - r)];
-                } else {
-                    v = wg[((int64_t)(dc0 + d) * g.ic + (c0 + c)) * (KS * KS) + r];
+        for (int e0 = tid; e0 < 16 * g.NT * KCH; e0 += 256 * kStage) {
+            float v[kStage];
+#pragma unroll
+            for (int q = 0; q < kStage; ++q) {
+                const int e = e0 + 256 * q;
+                const int d = e / KCH, k = e - d * KCH;
+                const int c = k / (KS * KS), r = k - c * KS * KS;
+                v[q] = 0.f;
+                if (e < 16 * g.NT * KCH && dc0 + d < g.DC && c0 + c < g.SC) {
+                    if (BWD) {
+                        // Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]
+                        v[q] = wg[((int64_t)(c0 + c) * g.ic + (dc0 + d)) * (KS * KS) + (KS * KS - 1 - r)];
+                    } else {
+                        v[q] = wg[((int64_t)(dc0 + d) * g.ic + (c0 + c)) * (KS * KS) + r];
+                    }
                 }
             }
-            Wsm[d * KCHP + k] = v;
+#pragma unroll
+            for (int q = 0; q < kStage; ++q) {
+                const int e = e0 + 256 * q;
+                if (e < 16 * g.NT * KCH) Wsm[(e / KCH) * KCHP + (e % KCH)] = v[q];
+            }
         }
         __syncthreads();
         for (int s = 0; s < STEPS; ++s) {
@@ -285,20 +303,36 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
         const gcf_ptr ig = as_global(in) + sample * g.in_size;
         const gcf_ptr dg = as_global(dout) + sample * g.out_size;
         __syncthreads();
-        for (int e = tid; e < g.IC * plane; e += 256) {
-            const int c = e / plane, rem = e - c * plane;
-            const int ty = rem / g.SWP, tx = rem - ty * g.SWP;
-            const int sy = y0 + ty - g.pad, sx = tx - g.pad;
-            float v = 0.f;
-            if (sy >= 0 && sy < g.IH && sx >= 0 && sx < g.IW) v = ig[((int64_t)c * g.IH + sy) * g.IW + sx];
-            Ism[e] = v;
+        for (int e0 = tid; e0 < g.IC * plane; e0 += 256 * kStage) {
+            float v[kStage];
+#pragma unroll
+            for (int q = 0; q < kStage; ++q) {
+                const int e = e0 + 256 * q;
+                const int c = e / plane, rem = e - c * plane;
+                const int ty = rem / g.SWP, tx = rem - ty * g.SWP;
+                const int sy = y0 + ty - g.pad, sx = tx - g.pad;
+                v[q] = 0.f;
+                if (e < g.IC * plane && sy >= 0 && sy < g.IH && sx >= 0 && sx < g.IW)
+                    v[q] = ig[((int64_t)c * g.IH + sy) * g.IW + sx];
+            }
+#pragma unroll
+            for (int q = 0; q < kStage; ++q)
+                if (e0 + 256 * q < g.IC * plane) Ism[e0 + 256 * q] = v[q];
         }
-        for (int e = tid; e < 16 * MT * dplane; e += 256) {
-            const int co = e / dplane, rem = e - co * dplane;
-            const int r = rem / g.OWP, x = rem - r * g.OWP;
-            float v = 0.f;
-            if (co < g.OC && y0 + r < g.OH && x < g.OW) v = dg[((int64_t)co * g.OH + y0 + r) * g.OW + x];
-            Dsm[e] = v;
+        for (int e0 = tid; e0 < 16 * MT * dplane; e0 += 256 * kStage) {
+            float v[kStage];
+#pragma unroll
+            for (int q = 0; q < kStage; ++q) {
+                const int e = e0 + 256 * q;
+                const int co = e / dplane, rem = e - co * dplane;
+                const int r = rem / g.OWP, x = rem - r * g.OWP;
+                v[q] = 0.f;
+                if (e < 16 * MT * dplane && co < g.OC && y0 + r < g.OH && x < g.OW)
+                    v[q] = dg[((int64_t)co * g.OH + y0 + r) * g.OW + x];
+            }
+#pragma unroll
+            for (int q = 0; q < kStage; ++q)
+                if (e0 + 256 * q < 16 * MT * dplane) Dsm[e0 + 256 * q] = v[q];
         }
         __syncthreads();
         for (int r = 0; r < g.R; ++r) {

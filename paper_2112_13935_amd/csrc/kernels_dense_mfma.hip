@@ -19,7 +19,9 @@ enum { DENSE_FWD = 0, DENSE_BWD_DATA = 1, DENSE_BWD_WEIGHT = 2 };
 constexpr int kDT = 64;   // output tile edge
 constexpr int kDK = 32;   // contraction chunk
 
-template <int MODE>
+// NTW: N tiles (of 16) per workgroup: 4 (each wave owns one N tile and all four M tiles) or
+// 1 (each wave owns one M tile): the narrow form gives more workgroups when N is small.
+template <int MODE, int NTW>
 __global__ void __launch_bounds__(256)
 k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
              int64_t b_off, int relu, const float *__restrict__ x, const float *__restrict__ y,
@@ -35,10 +37,11 @@ k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int
     const int M = MODE == DENSE_BWD_WEIGHT ? O : B;
     const int N = MODE == DENSE_FWD ? O : K;
     const int KD = MODE == DENSE_FWD ? K : (MODE == DENSE_BWD_DATA ? O : B);
-    const int m0 = blockIdx.y * kDT, n0 = blockIdx.x * kDT;
+    constexpr int NW = 16 * NTW;  // columns per workgroup
+    const int m0 = blockIdx.y * kDT, n0 = blockIdx.x * NW;
 
     __shared__ float As[kDT][kDK + 1];   // As[m][kk]
-    __shared__ float Bs[kDK][kDT + 1];   // Bs[kk][n]
+    __shared__ float Bs[kDK][NW + 1];    // Bs[kk][n]
 
     // element (m, kd) of the left operand and (kd, n) of the right one, zero outside
     auto left = [&](int m, int kd) -> float {
@@ -54,10 +57,11 @@ k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int
         return as_global(x)[(cb + kd) * K + n];                                  // in[b][k]
     };
 
-    // wave w owns N tile w and all four M tiles
-    f4 acc[4];
+    constexpr int MA = NTW == 4 ? 4 : 1;  // accumulator tiles per wave
+    const int ntile = NTW == 4 ? wave : 0;
+    f4 acc[MA];
 #pragma unroll
-    for (int m = 0; m < 4; ++m) acc[m] = f4{0.f, 0.f, 0.f, 0.f};
+    for (int m = 0; m < MA; ++m) acc[m] = f4{0.f, 0.f, 0.f, 0.f};
 
     for (int k0 = 0; k0 < KD; k0 += kDK) {
         __syncthreads();
@@ -74,38 +78,41 @@ k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int
             }
         }
         if (MODE == DENSE_FWD) {
-            for (int e = tid; e < kDT * kDK; e += 256) {  // kd fastest
+            for (int e = tid; e < NW * kDK; e += 256) {  // kd fastest
                 const int n = e / kDK, kk = e - n * kDK;
                 Bs[kk][n] = right(k0 + kk, n0 + n);
             }
         } else {
-            for (int e = tid; e < kDT * kDK; e += 256) {  // n fastest
-                const int kk = e / kDT, n = e - kk * kDT;
+            for (int e = tid; e < NW * kDK; e += 256) {  // n fastest
+                const int kk = e / NW, n = e - kk * NW;
                 Bs[kk][n] = right(k0 + kk, n0 + n);
             }
         }
         __syncthreads();
 #pragma unroll
         for (int s = 0; s < kDK / 4; ++s) {
-            const float b = Bs[4 * s + lg][16 * wave + li];
+            const float b = Bs[4 * s + lg][16 * ntile + li];
 #pragma unroll
-            for (int m = 0; m < 4; ++m) acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(As[16 * m + li][4 * s + lg], b, acc[m], 0, 0, 0);
+            for (int m = 0; m < MA; ++m) {
+                const int mt = NTW == 4 ? m : wave;
+                acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(As[16 * mt + li][4 * s + lg], b, acc[m], 0, 0, 0);
+            }
         }
     }
 
     // epilogue: lane holds column n = n0 + 16*wave + li and rows m = m0 + 16*mt + 4*lg + r
-    const int n = n0 + 16 * wave + li;
+    const int n = n0 + 16 * ntile + li;
     if (MODE == DENSE_BWD_WEIGHT) {
         const float invB = 1.0f / (float)B;
         const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
         if (n < N) {
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int m = 0; m < MA; ++m)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int o = m0 + 16 * mt + 4 * lg + r;
+                    const int o = m0 + 16 * (NTW == 4 ? m : wave) + 4 * lg + r;
                     if (o < M) {
-                        const float g = acc[mt][r] * invB;
+                        const float g = acc[m][r] * invB;
                         const int64_t wi = w_off + (int64_t)o * K + n;
                         Wc[wi] -= p.eta * g;
                         Uc[wi] += g;
@@ -126,12 +133,12 @@ k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int
         if (n < N) {
             const float bias = MODE == DENSE_FWD ? as_global(p.W)[b_off + n] : 0.f;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt)
+            for (int m = 0; m < MA; ++m)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const int b = m0 + 16 * mt + 4 * lg + r;
+                    const int b = m0 + 16 * (NTW == 4 ? m : wave) + 4 * lg + r;
                     if (b < M) {
-                        float v = acc[mt][r] + bias;
+                        float v = acc[m][r] + bias;
                         const int64_t i = (cb + b) * N + n;
                         if (MODE == DENSE_FWD) {
                             if (relu && !(v > 0.f)) v = 0.f;
@@ -150,16 +157,21 @@ hipError_t launch_dense_mfma(hipStream_t s, Profiler *prof, int mode, const Roun
                              const float *x, const float *y, float *z, const float *mask_src) {
     const int M = mode == DENSE_BWD_WEIGHT ? O : B;
     const int N = mode == DENSE_FWD ? O : K;
-    dim3 grid((unsigned)((N + kDT - 1) / kDT), (unsigned)((M + kDT - 1) / kDT), (unsigned)nact);
+    // narrow column blocks for the forward pass when wide ones would leave most of the GPU idle
+    const bool narrow = mode == DENSE_FWD && (int64_t)((N + kDT - 1) / kDT) * ((M + kDT - 1) / kDT) * nact < 512;
+    const int nw = narrow ? 16 : kDT;
+    dim3 grid((unsigned)((N + nw - 1) / nw), (unsigned)((M + kDT - 1) / kDT), (unsigned)nact);
     const int fam = mode == DENSE_FWD ? F_DENSE_FWD : mode == DENSE_BWD_DATA ? F_DENSE_BWD_DATA : F_DENSE_BWD_WEIGHT;
     const bool timed = prof && prof->on[fam];
     if (timed) prof->before(fam, s);
-    if (mode == DENSE_FWD)
-        k_dense_mfma<DENSE_FWD><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
+    if (mode == DENSE_FWD && narrow)
+        k_dense_mfma<DENSE_FWD, 1><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
+    else if (mode == DENSE_FWD)
+        k_dense_mfma<DENSE_FWD, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
     else if (mode == DENSE_BWD_DATA)
-        k_dense_mfma<DENSE_BWD_DATA><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
+        k_dense_mfma<DENSE_BWD_DATA, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
     else
-        k_dense_mfma<DENSE_BWD_WEIGHT><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
+        k_dense_mfma<DENSE_BWD_WEIGHT, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
     if (timed) prof->after(fam, s);
     return hipGetLastError();
 }
