@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the MLP)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rounds", type=int, default=0, help="exploration only: fewer rounds per client")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (calibrates the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
@@ -133,6 +135,15 @@ def main():
     for _ in range(max(args.warmup, 0)):
         job()
     run.lib.aet_synchronize()
+
+    if args.copy_probe:
+        # a plain copy of known size: reads 256 MiB and writes 256 MiB per dispatch
+        src = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # which kernel family dominates: one untimed job with every family's launches timed
     run.lib.aet_profile_enable(-1, True)

@@ -402,19 +402,21 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *__restrict__ W
         }
         // ---- first layer: dW1^T = X^T dh on the matrix cores, update in registers -------
         {
+            // contraction step s of lane group lg takes sample 16*(s/4) + (s%4) + 4*lg: with
+            // rows 4*lg apart the four lane groups read LDS banks 16 apart (ld = 4 mod 32)
             float dhb[4 * NBT];
 #pragma unroll
-            for (int s = 0; s < 4 * NBT; ++s) dhb[s] = dhs[(4 * s + lg) * 16 + li];
+            for (int s = 0; s < 4 * NBT; ++s) dhb[s] = dhs[(16 * (s >> 2) + (s & 3) + 4 * lg) * 16 + li];
             float xb[2][4 * NBT];
-            const float *xcol = Xs + opaque(lg * ld + col0 + li);
+            const float *xcol = Xs + opaque(4 * lg * ld + col0 + li);
 #pragma unroll
-            for (int s = 0; s < 4 * NBT; ++s) xb[0][s] = xcol[4 * s * ld];
+            for (int s = 0; s < 4 * NBT; ++s) xb[0][s] = xcol[(16 * (s >> 2) + (s & 3)) * ld];
             const float eb = p.eta * invB;
 #pragma unroll
             for (int tt = 0; tt < TPW; ++tt) {
                 if (tt + 1 < TPW) {
 #pragma unroll
-                    for (int s = 0; s < 4 * NBT; ++s) xb[(tt + 1) & 1][s] = xcol[4 * s * ld + 16 * (tt + 1)];
+                    for (int s = 0; s < 4 * NBT; ++s) xb[(tt + 1) & 1][s] = xcol[(16 * (s >> 2) + (s & 3)) * ld + 16 * (tt + 1)];
                 }
                 // two independent accumulation chains per tile
                 f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
