@@ -15,6 +15,10 @@
  *     uniformly from D_c; g = grad f(w_c, xi); w_c -= eta_i g;
  *     U += g; h += 1; then send (c, U_i, i)                            : Algorithm 2, MainComputeNode
  *   - a received (v, U, k) is applied as w -= eta_k * U, H_v += 1      : Algorithm 2, Receive
+ *   - peer-to-peer form: every node keeps its own model, sends
+ *     (c, U_i, i) to its neighbours only and applies what they send    : Algorithm 2 as printed;
+ *                                                                        Section 2.2.1 (undirected
+ *                                                                        topology, neighbour lists given)
  *   - the delay checkpoint max_e (i - H_e) > d                         : Algorithm 2, Synchronize
  *   - round lengths s_i = a*i^p + b with p = 1; step size
  *     eta0 / (1 + beta * t^power), constant inside a round             : Section 3.1, Experiments
@@ -82,6 +86,8 @@ typedef struct orc_ctx {
     int64_t *N;
     real *Wg, *W;
     int64_t *i_c, *t_c, *q_c, *free_at, *H;
+    int p2p;                 /* 1: peer-to-peer form on the topology below */
+    int32_t *nbr_off, *nbr;  /* neighbour lists, CSR: nbr[nbr_off[c] .. nbr_off[c+1]) ascending */
     int64_t tick;
     uint64_t seed;
     msg_t *queue; int n_queue, cap_queue;
@@ -368,6 +374,7 @@ void orc_destroy(orc_ctx *C) {
     free(C->X); free(C->y); free(C->N);
     free(C->Wg); free(C->W);
     free(C->i_c); free(C->t_c); free(C->q_c); free(C->free_at); free(C->H);
+    free(C->nbr_off); free(C->nbr);
     free(C);
 }
 
@@ -407,9 +414,41 @@ orc_ctx *orc_create(const orc_model *m, int32_t n_clients, const float *const *X
 static int fail(orc_ctx *C, const char *msg) { snprintf(C->err, sizeof C->err, "%s", msg); return -1; }
 const char *orc_last_error(const orc_ctx *C) { return C->err; }
 
+/* Switch to the peer-to-peer form of Algorithm 2 on an undirected topology (Section 2.2.1:
+ * the neighbour list of every node is given).  nbr_off has n+1 entries; the neighbours of c
+ * are nbr[nbr_off[c] .. nbr_off[c+1]), strictly ascending, never c itself, and v is listed
+ * for c exactly when c is listed for v.  Only before the first round.  From then on every
+ * node keeps its own model from round to round (no global model is adopted), a message
+ * goes to the sender's neighbours, and the delay checkpoint looks at neighbours only. */
+int orc_set_topology(orc_ctx *C, const int32_t *nbr_off, const int32_t *nbr) {
+    if (C->tick != 0 || C->n_queue != 0) return fail(C, "topology must be set before the first round");
+    for (int c = 0; c < C->n; ++c) if (C->i_c[c] != 0) return fail(C, "topology must be set before the first round");
+    if (nbr_off[0] != 0) return fail(C, "nbr_off[0] must be 0");
+    for (int c = 0; c < C->n; ++c) {
+        if (nbr_off[c + 1] < nbr_off[c]) return fail(C, "nbr_off must not decrease");
+        for (int32_t j = nbr_off[c]; j < nbr_off[c + 1]; ++j) {
+            const int32_t v = nbr[j];
+            if (v < 0 || v >= C->n || v == c) return fail(C, "neighbour out of range or self loop");
+            if (j > nbr_off[c] && nbr[j - 1] >= v) return fail(C, "neighbour lists must be strictly ascending");
+            int back = 0;
+            for (int32_t q = nbr_off[v]; q < nbr_off[v + 1]; ++q) if (nbr[q] == c) back = 1;
+            if (!back) return fail(C, "topology is not undirected");
+        }
+    }
+    free(C->nbr_off); free(C->nbr);
+    const int32_t E = nbr_off[C->n];
+    C->nbr_off = (int32_t *)malloc(sizeof(int32_t) * (C->n + 1));
+    C->nbr = (int32_t *)malloc(sizeof(int32_t) * (E > 0 ? E : 1));
+    memcpy(C->nbr_off, nbr_off, sizeof(int32_t) * (C->n + 1));
+    if (E > 0) memcpy(C->nbr, nbr, sizeof(int32_t) * E);
+    C->p2p = 1;
+    return 0;
+}
+
 /* One tick of local rounds (Algorithm 2, MainComputeNode, one pass of the round loop for
  * every client that is free).  A client starts round i = i_c if it is idle, has rounds
- * left and passes the delay checkpoint; it adopts the global model, runs m = s_i / B
+ * left and passes the delay checkpoint; it adopts the global model (server form; in the
+ * peer-to-peer form it goes on from its own model), runs m = s_i / B
  * mini-batch recursions with the round's step size, and posts (c, U_i, i).
  * Outputs: the clients that ran and their round numbers, ascending client order. */
 int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0, double beta,
@@ -424,11 +463,21 @@ int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0,
     int na = 0;
     for (int c = 0; c < C->n; ++c) {
         if (C->free_at[c] > C->tick || C->i_c[c] >= rounds) continue;
-        /* Synchronize: d_c = max over the other nodes e of (i - H_e); wait while d_c > d */
+        /* Synchronize: d_c = max over the map H of (i - H_e); wait while d_c > d.  The map
+         * holds the other nodes (server form) or the node's neighbours (peer-to-peer form).
+         * A message reaches all neighbours of its sender in the same tick, so every
+         * neighbour's count of v's rounds is the one number H_v. */
         if (d_max >= 0) {
             int64_t dc = 0;
-            for (int e = 0; e < C->n; ++e)
-                if (e != c && C->i_c[c] - C->H[e] > dc) dc = C->i_c[c] - C->H[e];
+            if (C->p2p) {
+                for (int32_t j = C->nbr_off[c]; j < C->nbr_off[c + 1]; ++j) {
+                    const int e = C->nbr[j];
+                    if (C->i_c[c] - C->H[e] > dc) dc = C->i_c[c] - C->H[e];
+                }
+            } else {
+                for (int e = 0; e < C->n; ++e)
+                    if (e != c && C->i_c[c] - C->H[e] > dc) dc = C->i_c[c] - C->H[e];
+            }
             if (dc > d_max) continue;
         }
         int64_t s = orc_threshold(a, b, C->i_c[c]);
@@ -451,7 +500,8 @@ int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0,
         real *g = (real *)malloc(sizeof(real) * C->P);
         scratch_t sc;
         if (!U || !g || scratch_alloc(C->lay, C->L, &sc)) { oom = 1; free(U); free(g); continue; }
-        for (int64_t p = 0; p < C->P; ++p) Wc[p] = C->Wg[p];          /* adopt the broadcast */
+        if (!C->p2p)
+            for (int64_t p = 0; p < C->P; ++p) Wc[p] = C->Wg[p];      /* adopt the broadcast */
         real loss_sum = 0;
         for (int64_t u = 0; u < m; ++u) {
             for (int64_t p = 0; p < C->P; ++p) g[p] = 0;
@@ -503,32 +553,75 @@ int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0,
     return 0;
 }
 
+/* The message with the smallest (round, client) among those arriving in this tick; -1: none */
+static int next_arrival(const orc_ctx *C) {
+    int best = -1;
+    for (int j = 0; j < C->n_queue; ++j) {
+        if (C->queue[j].arrival != C->tick) continue;
+        if (best < 0 || C->queue[j].k < C->queue[best].k ||
+            (C->queue[j].k == C->queue[best].k && C->queue[j].c < C->queue[best].c)) best = j;
+    }
+    return best;
+}
+
+static void log_event(orc_ctx *C, int32_t c, int32_t k) {
+    if (C->n_ev == C->cap_ev) {
+        C->cap_ev = C->cap_ev ? 2 * C->cap_ev : 256;
+        C->ev_tick = (int64_t *)realloc(C->ev_tick, sizeof(int64_t) * C->cap_ev);
+        C->ev_c = (int32_t *)realloc(C->ev_c, sizeof(int32_t) * C->cap_ev);
+        C->ev_k = (int32_t *)realloc(C->ev_k, sizeof(int32_t) * C->cap_ev);
+    }
+    C->ev_tick[C->n_ev] = C->tick; C->ev_c[C->n_ev] = c; C->ev_k[C->n_ev] = k; C->n_ev++;
+}
+
 /* Server form of Receive: every message whose arrival tick is the current tick is
  * applied, in (round, client) ascending order, as Wg -= (agg_scale * eta_k) * U with the
  * SENDER's round step size, and H_c += 1.  Then the tick advances. */
 int orc_server_aggregate(orc_ctx *C, double agg_scale, int32_t *n_applied, int32_t *app_client,
                          int32_t *app_round) {
+    if (C->p2p) return fail(C, "peer-to-peer form: use orc_receive");
     int na = 0;
     for (;;) {
-        int best = -1;
-        for (int j = 0; j < C->n_queue; ++j) {
-            if (C->queue[j].arrival != C->tick) continue;
-            if (best < 0 || C->queue[j].k < C->queue[best].k ||
-                (C->queue[j].k == C->queue[best].k && C->queue[j].c < C->queue[best].c)) best = j;
-        }
+        const int best = next_arrival(C);
         if (best < 0) break;
         msg_t *q = &C->queue[best];
         const real scale = (real)(agg_scale * q->eta);
         for (int64_t p = 0; p < C->P; ++p) C->Wg[p] -= scale * q->U[p];
         C->H[q->c] += 1;
-        if (C->n_ev == C->cap_ev) {
-            C->cap_ev = C->cap_ev ? 2 * C->cap_ev : 256;
-            C->ev_tick = (int64_t *)realloc(C->ev_tick, sizeof(int64_t) * C->cap_ev);
-            C->ev_c = (int32_t *)realloc(C->ev_c, sizeof(int32_t) * C->cap_ev);
-            C->ev_k = (int32_t *)realloc(C->ev_k, sizeof(int32_t) * C->cap_ev);
-        }
-        C->ev_tick[C->n_ev] = C->tick; C->ev_c[C->n_ev] = q->c; C->ev_k[C->n_ev] = q->k; C->n_ev++;
+        log_event(C, q->c, q->k);
         if (app_client) app_client[na] = q->c;
+        if (app_round) app_round[na] = q->k;
+        na++;
+        free(q->U);
+        C->queue[best] = C->queue[--C->n_queue];
+    }
+    if (n_applied) *n_applied = na;
+    C->tick += 1;
+    return 0;
+}
+
+/* Receive as Algorithm 2 prints it: a message (v, U, k) arriving in this tick is applied
+ * by every neighbour r of v to its own model, w_r -= (scale * eta_k) * U, with the step
+ * size of the sender's round k (scale = 1 is the paper's rule), and H_v += 1.  Messages
+ * are taken in (round, sender) ascending order, so each node applies its arrivals in
+ * that order.  A node whose round occupies several ticks did its recursions in the
+ * round's first tick; what arrives meanwhile lands on the model as that round left it.
+ * Outputs: the messages delivered (sender, round).  Then the tick advances. */
+int orc_receive(orc_ctx *C, double scale, int32_t *n_applied, int32_t *app_sender, int32_t *app_round) {
+    if (!C->p2p) return fail(C, "no topology set: use orc_server_aggregate");
+    int na = 0;
+    for (;;) {
+        const int best = next_arrival(C);
+        if (best < 0) break;
+        msg_t *q = &C->queue[best];
+        const real sc = (real)(scale * q->eta);
+        for (int32_t j = C->nbr_off[q->c]; j < C->nbr_off[q->c + 1]; ++j) {
+            real *Wr = C->W + (int64_t)C->nbr[j] * C->P;
+            for (int64_t p = 0; p < C->P; ++p) Wr[p] -= sc * q->U[p];
+        }
+        C->H[q->c] += 1;
+        log_event(C, q->c, q->k);
+        if (app_sender) app_sender[na] = q->c;
         if (app_round) app_round[na] = q->k;
         na++;
         free(q->U);

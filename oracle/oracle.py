@@ -85,6 +85,10 @@ def load(prec: str = "f64"):
                                   vp, vp, vp]
     lib.orc_server_aggregate.restype = C.c_int
     lib.orc_server_aggregate.argtypes = [vp, dbl, vp, vp, vp]
+    lib.orc_set_topology.restype = C.c_int
+    lib.orc_set_topology.argtypes = [vp, vp, vp]
+    lib.orc_receive.restype = C.c_int
+    lib.orc_receive.argtypes = [vp, dbl, vp, vp, vp]
     lib.orc_all_done.restype = C.c_int
     lib.orc_all_done.argtypes = [vp, i32]
     for name in ("orc_tick", "orc_queue_len", "orc_params", "orc_event_count"):
@@ -159,6 +163,9 @@ class Oracle:
             wl.compute_factor[: self.n], dtype=np.int32)
         self._st = None if wl.is_straggler is None else np.ascontiguousarray(
             wl.is_straggler[: self.n], dtype=np.uint8)
+        self.p2p = False
+        if getattr(wl, "topology", None) is not None and self.n == wl.n_clients:
+            self.set_topology(*wl.topology)
 
     def close(self):
         if self.ctx:
@@ -197,6 +204,27 @@ class Oracle:
             self.ctx, self.wl.agg_scale if agg_scale is None else agg_scale,
             C.byref(na), _ptr(ac), _ptr(ar)))
         return list(zip(ac[: na.value].tolist(), ar[: na.value].tolist()))
+
+    def set_topology(self, nbr_off, nbr):
+        """Peer-to-peer form on the given neighbour lists (CSR)."""
+        self._nbr_off = np.ascontiguousarray(nbr_off, dtype=np.int32)
+        self._nbr = np.ascontiguousarray(nbr, dtype=np.int32)
+        assert self._nbr_off.shape[0] == self.n + 1
+        self._check(self.lib.orc_set_topology(self.ctx, _ptr(self._nbr_off), _ptr(self._nbr)))
+        self.p2p = True
+
+    def receive(self, scale: Optional[float] = None):
+        na = C.c_int32(0)
+        cap = max(1, int(self.lib.orc_queue_len(self.ctx)))
+        ac = np.zeros(cap, dtype=np.int32)
+        ar = np.zeros(cap, dtype=np.int32)
+        self._check(self.lib.orc_receive(
+            self.ctx, self.wl.agg_scale if scale is None else scale, C.byref(na), _ptr(ac), _ptr(ar)))
+        return list(zip(ac[: na.value].tolist(), ar[: na.value].tolist()))
+
+    def exchange(self, scale: Optional[float] = None):
+        """The tick's second half: Receive at the neighbours or at the server."""
+        return self.receive(scale) if self.p2p else self.server_aggregate(scale)
 
     def all_done(self, rounds: Optional[int] = None) -> bool:
         return bool(self.lib.orc_all_done(self.ctx, self.wl.rounds if rounds is None else rounds))
@@ -240,7 +268,7 @@ class Oracle:
         ticks = 0
         while not self.all_done(R):
             self.run_round(R)
-            self.server_aggregate()
+            self.exchange()
             ticks += 1
             if ticks > max_ticks:
                 raise RuntimeError("oracle did not finish")

@@ -127,10 +127,40 @@ class Workload:
     delay_seed: int = 0
     d_max: int = -1                # SYNCHRONIZE gate off
     notes: str = ""
+    topology: Optional[tuple] = None   # (nbr_off, nbr) neighbour lists: peer-to-peer form
 
     def total_client_samples(self, rounds: Optional[int] = None) -> int:
         R = self.rounds if rounds is None else rounds
         return self.n_clients * sum(self.a * i + self.b for i in range(R))
+
+
+def topology_from_edges(n: int, edges) -> tuple:
+    """Neighbour lists (CSR: nbr_off int32 [n+1], nbr int32, ascending per node) of the
+    undirected graph with the given edges; duplicates and self loops are dropped."""
+    adj = [set() for _ in range(n)]
+    for u, v in edges:
+        u, v = int(u) % n, int(v) % n
+        if u != v:
+            adj[u].add(v)
+            adj[v].add(u)
+    off = np.zeros(n + 1, dtype=np.int32)
+    for c in range(n):
+        off[c + 1] = off[c] + len(adj[c])
+    nbr = np.array([v for c in range(n) for v in sorted(adj[c])], dtype=np.int32)
+    return off, nbr
+
+
+def ring_topology(n: int) -> tuple:
+    """Every node talks to its two ring neighbours (one neighbour when n = 2, none when n = 1)."""
+    return topology_from_edges(n, [(c, c + 1) for c in range(n)])
+
+
+def line_topology(n: int) -> tuple:
+    return topology_from_edges(n, [(c, c + 1) for c in range(n - 1)])
+
+
+def complete_topology(n: int) -> tuple:
+    return topology_from_edges(n, [(u, v) for u in range(n) for v in range(u + 1, n)])
 
 
 def _rng(seed: int, stream: int) -> np.random.Generator:
