@@ -143,7 +143,8 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
  * every client that is idle, has rounds left and passes the delay checkpoint).  Such a
  * client c, at its round i:
  *   adopts the server's current global model (client-server paragraph of the
- *   Introduction: the server broadcasts its most recent model);
+ *   Introduction: the server broadcasts its most recent model), or, once a topology is
+ *   set, goes on from its own model (Algorithm 2 as printed);
  *   h = 0, U = 0; for each of the s_i / batch recursions: draws `batch` sample indices,
  *   g = mean of grad f(w_c; xi) over them, w_c <- w_c - eta_i g, U <- U + g;
  *   posts the message (c, U_i, i) with arrival tick
@@ -165,7 +166,38 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
 aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applied,
                                 int32_t *applied_client, int32_t *applied_round);
 
-/* Driver loop: repeats { aet_run_round; aet_server_aggregate } with the same parameters
+/* Peer-to-peer form (Algorithm 2 as printed; Section 2.2.1: undirected topology, the
+ * neighbour list of every node is given).  After this call every node keeps its own model
+ * from round to round, a message goes to the sender's neighbours (aet_receive), and the
+ * delay checkpoint of node c looks at its neighbours only:  max over e in N(c) of
+ * (i_c - H_e) > d_max  holds c back.  Only before the first round.
+ *   nbr_off   HOST, n_clients + 1 entries, nbr_off[0] = 0, not decreasing
+ *   nbr       HOST, nbr_off[n_clients] entries: the neighbours of c are
+ *             nbr[nbr_off[c] .. nbr_off[c+1]), strictly ascending, never c itself, and v is
+ *             listed for c exactly when c is listed for v (else AET_EINVAL)
+ *   workspace DEVICE, 256-byte aligned, at least aet_topology_workspace_bytes(n_clients,
+ *             nbr_off[n_clients]) bytes; owned by the caller, kept alive until aet_destroy.
+ * The host arrays are copied during the call. */
+size_t aet_topology_workspace_bytes(int32_t n_clients, int32_t n_neighbour_entries);
+aet_status aet_set_topology(aet_ctx *ctx, const int32_t *nbr_off, const int32_t *nbr, void *workspace,
+                            size_t workspace_bytes);
+
+/* Receive as Algorithm 2 prints it, for a context with a topology: every message (v, U, k)
+ * whose arrival tick is the current tick is applied by each neighbour r of v to its own
+ * model,  w_r <- w_r - scale * eta_k * U  (sender's round step size; scale = 1 is the
+ * paper's rule), H_v <- H_v + 1.  A node applies the tick's arrivals in (k ascending, v
+ * ascending) order.  A node whose round occupies several ticks did its recursions in the
+ * round's first tick, so what arrives meanwhile lands on the model as that round left it.
+ * Then the tick counter advances.
+ *   n_applied, applied_sender, applied_round : HOST outputs, the messages delivered
+ *   (capacity: the number of messages in flight, at most n_clients * max_inflight; any may
+ *   be NULL).
+ * AET_ESTATE without a topology; aet_server_aggregate returns AET_ESTATE with one. */
+aet_status aet_receive(aet_ctx *ctx, float scale, int32_t *n_applied, int32_t *applied_sender,
+                       int32_t *applied_round);
+
+/* Driver loop: repeats { aet_run_round; aet_server_aggregate } (with a topology:
+ * { aet_run_round; aet_receive }, agg_scale being the scale) with the same parameters
  * until every client has completed thr->rounds local rounds and the message queue has
  * drained, or max_ticks ticks have run.  *ticks_done (HOST, may be NULL) receives the
  * number of ticks run; it is valid also when a tick fails. */

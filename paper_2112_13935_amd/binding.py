@@ -23,6 +23,7 @@ EXPORTS = [
     "aet_all_done", "aet_tick", "aet_history", "aet_inflight", "aet_synchronize",
     "aet_last_error", "aet_destroy", "aet_reset", "aet_profile_families",
     "aet_profile_family_name", "aet_profile_enable", "aet_profile_read", "aet_run_ticks",
+    "aet_topology_workspace_bytes", "aet_set_topology", "aet_receive",
 ]
 
 
@@ -110,6 +111,12 @@ def load_library():
     lib.aet_last_error.argtypes = [vp]
     lib.aet_reset.restype = C.c_int
     lib.aet_reset.argtypes = [vp]
+    lib.aet_topology_workspace_bytes.restype = C.c_size_t
+    lib.aet_topology_workspace_bytes.argtypes = [i32, i32]
+    lib.aet_set_topology.restype = C.c_int
+    lib.aet_set_topology.argtypes = [vp, vp, vp, vp, C.c_size_t]
+    lib.aet_receive.restype = C.c_int
+    lib.aet_receive.argtypes = [vp, C.c_float, C.POINTER(i32), vp, vp]
     lib.aet_profile_families.restype = i32
     lib.aet_profile_families.argtypes = []
     lib.aet_profile_family_name.restype = C.c_char_p
@@ -222,6 +229,24 @@ class AetSgd:
         na = C.c_int32(0)
         self._check(self.lib.aet_server_aggregate(self.ctx, C.c_float(agg_scale), C.byref(na),
                                                   _hptr(self._ac), _hptr(self._ar)))
+        return list(zip(self._ac[: na.value].tolist(), self._ar[: na.value].tolist()))
+
+    def aet_set_topology(self, nbr_off: np.ndarray, nbr: np.ndarray):
+        """Peer-to-peer form on the given neighbour lists (CSR, host arrays)."""
+        off = np.ascontiguousarray(nbr_off, dtype=np.int32)
+        nb = np.ascontiguousarray(nbr, dtype=np.int32)
+        if off.shape[0] != self.n + 1:
+            raise ValueError("nbr_off needs n_clients + 1 entries")
+        nbytes = int(self.lib.aet_topology_workspace_bytes(self.n, int(off[-1])))
+        self._topo_ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+        ptr = (self._topo_ws.data_ptr() + 255) & ~255
+        self._check(self.lib.aet_set_topology(self.ctx, _hptr(off), _hptr(nb) if nb.size else None,
+                                              C.c_void_p(ptr), nbytes))
+
+    def aet_receive(self, scale: float) -> List[Tuple[int, int]]:
+        na = C.c_int32(0)
+        self._check(self.lib.aet_receive(self.ctx, C.c_float(scale), C.byref(na),
+                                         _hptr(self._ac), _hptr(self._ar)))
         return list(zip(self._ac[: na.value].tolist(), self._ar[: na.value].tolist()))
 
     def aet_get_U(self, client: int, round_: int) -> np.ndarray:

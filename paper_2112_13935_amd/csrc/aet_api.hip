@@ -162,6 +162,10 @@ struct aet_ctx {
     hipEvent_t ev_params[kRing] = {}, ev_arr[kRing] = {};
     int ring_p = 0, ring_a = 0;
     bool dead = false;
+    // peer-to-peer form: neighbour lists (host copy and device copy in the caller's buffer)
+    bool p2p = false;
+    std::vector<int32_t> nbr_off, nbr;
+    int32_t *d_nbr_off = nullptr, *d_nbr = nullptr;
     int engine = 0;
     uint32_t epoch = 0;  // step-tag base of the fused kernels' exchange records
     std::string err;
@@ -327,10 +331,15 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
     int64_t max_m = 0;
     for (int c = 0; c < ctx->n; ++c) {
         if (ctx->free_at[c] > ctx->tick || ctx->i_c[c] >= thr->rounds) continue;
-        if (d_gate >= 0) {  // Synchronize: d_c = max over the other nodes of (i - H_e)
+        if (d_gate >= 0) {  // Synchronize: d_c = max over the map H of (i - H_e)
             int64_t dc = 0;
-            for (int e = 0; e < ctx->n; ++e)
-                if (e != c) dc = std::max(dc, ctx->i_c[c] - ctx->H[e]);
+            if (ctx->p2p) {  // the map holds the neighbours
+                for (int32_t j = ctx->nbr_off[c]; j < ctx->nbr_off[c + 1]; ++j)
+                    dc = std::max(dc, ctx->i_c[c] - ctx->H[ctx->nbr[j]]);
+            } else {         // the map holds every other node
+                for (int e = 0; e < ctx->n; ++e)
+                    if (e != c) dc = std::max(dc, ctx->i_c[c] - ctx->H[e]);
+            }
             if (dc > d_gate) continue;
         }
         if (cf && cf[c] < 1) return fail(ctx, AET_EINVAL, "compute_factor[%d] < 1", c);
@@ -384,13 +393,16 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
             AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
             AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
         }
+        // server form: every round starts from the global model; peer-to-peer form: from the
+        // client's own replica
+        const float *start = ctx->p2p ? nullptr : ctx->Wg();
         if (ctx->engine == ENGINE_MLP) {
-            AET_HIP(ctx, launch_mlp_round(ctx->stream, ctx->profp(), dp, nact, (int)max_m, ctx->Wg(), (int)ctx->lay[0].in_size,
+            AET_HIP(ctx, launch_mlp_round(ctx->stream, ctx->profp(), dp, nact, (int)max_m, start, (int)ctx->lay[0].in_size,
                                           ctx->lay[0].oc, ctx->lay[1].oc, ctx->B, ctx->ws + ctx->lo.fused, ctx->n, &ctx->epoch));
         } else if (ctx->engine == ENGINE_SOFTMAX) {
-            AET_HIP(ctx, launch_softmax_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), (int)ctx->lay[0].in_size, ctx->lay[0].oc));
+            AET_HIP(ctx, launch_softmax_round(ctx->stream, ctx->profp(), dp, nact, start, (int)ctx->lay[0].in_size, ctx->lay[0].oc));
         } else {
-            AET_HIP(ctx, launch_begin_round(ctx->stream, ctx->profp(), dp, nact, ctx->Wg(), ctx->P));
+            AET_HIP(ctx, launch_begin_round(ctx->stream, ctx->profp(), dp, nact, start, ctx->P));
             for (int64_t u = 0; u < max_m; ++u)
                 AET_HIP(ctx, launch_layer_step(ctx->stream, ctx->profp(), dp, nact, (int)u, ctx->lay, ctx->L, ctx->B, ctx->sc));
         }
@@ -411,53 +423,147 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
     return AET_OK;
 }
 
-aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applied,
-                                int32_t *applied_client, int32_t *applied_round) {
-    if (!ctx) return AET_EINVAL;
-    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
-    if (!std::isfinite(agg_scale)) return fail(ctx, AET_EINVAL, "agg_scale is not finite");
-    std::vector<Msg> arr;
+// This tick's arrivals in (round, client) order, staged for a kernel: by value when the
+// list is short (*pack_out = &pack), else through the pinned ring into device memory (*dev_out).
+static aet_status stage_arrivals(aet_ctx *ctx, float scale, std::vector<Msg> *arr_out, ArrivalPack *pack,
+                                 const ArrivalPack **pack_out, const Arrival **dev_out) {
+    std::vector<Msg> &arr = *arr_out;
+    arr.clear();
     for (const Msg &m : ctx->queue)
         if (m.arrival == ctx->tick) arr.push_back(m);
     std::sort(arr.begin(), arr.end(), [](const Msg &x, const Msg &y) { return x.k != y.k ? x.k < y.k : x.c < y.c; });
     const int na = (int)arr.size();
+    *pack_out = nullptr;
+    *dev_out = nullptr;
+    if (na == 0) return AET_OK;
+    Arrival *dst = pack->a;
+    int ring = -1;
+    if (na > kArrivalPack) {
+        ring = ctx->ring_a;
+        ctx->ring_a = (ring + 1) % kRing;
+        AET_HIP(ctx, hipEventSynchronize(ctx->ev_arr[ring]));
+        dst = ctx->h_arr[ring];
+    }
+    for (int j = 0; j < na; ++j) {
+        dst[j].U = ctx->Uslot(arr[j].slot);
+        dst[j].scale = (float)((double)scale * (double)arr[j].eta);
+        dst[j].sender = arr[j].c;
+    }
+    if (ring < 0) {
+        *pack_out = pack;
+    } else {
+        Arrival *da = reinterpret_cast<Arrival *>(ctx->ws + ctx->lo.arrivals);
+        AET_HIP(ctx, hipMemcpyAsync(da, dst, (size_t)na * sizeof(Arrival), hipMemcpyHostToDevice, ctx->stream));
+        AET_HIP(ctx, hipEventRecord(ctx->ev_arr[ring], ctx->stream));
+        *dev_out = da;
+    }
+    return AET_OK;
+}
+
+// bookkeeping after the arrivals were applied: H, slots, queue, outputs, tick
+static void retire_arrivals(aet_ctx *ctx, const std::vector<Msg> &arr, int32_t *n_applied,
+                            int32_t *applied_client, int32_t *applied_round) {
+    const int na = (int)arr.size();
+    for (int j = 0; j < na; ++j) {
+        ctx->H[arr[j].c] += 1;
+        ctx->free_slots.push_back(arr[j].slot);
+        if (applied_client) applied_client[j] = arr[j].c;
+        if (applied_round) applied_round[j] = arr[j].k;
+    }
     if (na > 0) {
-        if (na <= kArrivalPack) {
-            // few arrivals: the list travels in the kernel arguments
-            ArrivalPack pack;
-            for (int j = 0; j < na; ++j) {
-                pack.a[j].U = ctx->Uslot(arr[j].slot);
-                pack.a[j].scale = (float)((double)agg_scale * (double)arr[j].eta);
-                pack.a[j].pad_ = 0;
-            }
-            AET_HIP(ctx, launch_server_apply_small(ctx->stream, ctx->profp(), ctx->Wg(), pack, na, ctx->P));
-        } else {
-            const int ring = ctx->ring_a;
-            ctx->ring_a = (ring + 1) % kRing;
-            AET_HIP(ctx, hipEventSynchronize(ctx->ev_arr[ring]));
-            Arrival *ha = ctx->h_arr[ring];
-            for (int j = 0; j < na; ++j) {
-                ha[j].U = ctx->Uslot(arr[j].slot);
-                ha[j].scale = (float)((double)agg_scale * (double)arr[j].eta);
-                ha[j].pad_ = 0;
-            }
-            Arrival *da = reinterpret_cast<Arrival *>(ctx->ws + ctx->lo.arrivals);
-            AET_HIP(ctx, hipMemcpyAsync(da, ha, (size_t)na * sizeof(Arrival), hipMemcpyHostToDevice, ctx->stream));
-            AET_HIP(ctx, hipEventRecord(ctx->ev_arr[ring], ctx->stream));
-            AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->profp(), ctx->Wg(), da, na, ctx->P,
-                                              reinterpret_cast<float *>(ctx->ws + ctx->lo.partial), ctx->lo.max_chunks));
-        }
-        for (int j = 0; j < na; ++j) {
-            ctx->H[arr[j].c] += 1;
-            ctx->free_slots.push_back(arr[j].slot);
-            if (applied_client) applied_client[j] = arr[j].c;
-            if (applied_round) applied_round[j] = arr[j].k;
-        }
         const int64_t now = ctx->tick;
         ctx->queue.erase(std::remove_if(ctx->queue.begin(), ctx->queue.end(), [now](const Msg &m) { return m.arrival == now; }), ctx->queue.end());
     }
     if (n_applied) *n_applied = na;
     ctx->tick += 1;
+}
+
+aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applied,
+                                int32_t *applied_client, int32_t *applied_round) {
+    if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
+    if (ctx->p2p) return fail(ctx, AET_ESTATE, "a topology is set: the tick's second half is aet_receive");
+    if (!std::isfinite(agg_scale)) return fail(ctx, AET_EINVAL, "agg_scale is not finite");
+    std::vector<Msg> arr;
+    ArrivalPack pack;
+    const ArrivalPack *by_value = nullptr;
+    const Arrival *on_device = nullptr;
+    const aet_status st = stage_arrivals(ctx, agg_scale, &arr, &pack, &by_value, &on_device);
+    if (st != AET_OK) return st;
+    const int na = (int)arr.size();
+    if (by_value) {
+        AET_HIP(ctx, launch_server_apply_small(ctx->stream, ctx->profp(), ctx->Wg(), *by_value, na, ctx->P));
+    } else if (on_device) {
+        AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->profp(), ctx->Wg(), on_device, na, ctx->P,
+                                          reinterpret_cast<float *>(ctx->ws + ctx->lo.partial), ctx->lo.max_chunks));
+    }
+    retire_arrivals(ctx, arr, n_applied, applied_client, applied_round);
+    return AET_OK;
+}
+
+size_t aet_topology_workspace_bytes(int32_t n_clients, int32_t n_neighbour_entries) {
+    if (n_clients < 1 || n_neighbour_entries < 0) return 0;
+    return align_up((size_t)(n_clients + 1) * 4) + align_up((size_t)std::max(n_neighbour_entries, 1) * 4);
+}
+
+aet_status aet_set_topology(aet_ctx *ctx, const int32_t *nbr_off, const int32_t *nbr, void *workspace,
+                            size_t workspace_bytes) {
+    if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
+    if (!nbr_off || !workspace) return fail(ctx, AET_EINVAL, "NULL argument");
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(ctx, AET_EINVAL, "workspace must be 256-byte aligned");
+    if (ctx->tick != 0 || !ctx->queue.empty()) return fail(ctx, AET_ESTATE, "the topology must be set before the first round");
+    for (int c = 0; c < ctx->n; ++c)
+        if (ctx->i_c[c] != 0) return fail(ctx, AET_ESTATE, "the topology must be set before the first round");
+    const int n = ctx->n;
+    if (nbr_off[0] != 0) return fail(ctx, AET_EINVAL, "nbr_off[0] must be 0");
+    for (int c = 0; c < n; ++c)
+        if (nbr_off[c + 1] < nbr_off[c]) return fail(ctx, AET_EINVAL, "nbr_off must not decrease");
+    const int32_t E = nbr_off[n];
+    if (E > 0 && !nbr) return fail(ctx, AET_EINVAL, "NULL argument");
+    for (int c = 0; c < n; ++c)
+        for (int32_t j = nbr_off[c]; j < nbr_off[c + 1]; ++j) {
+            const int32_t v = nbr[j];
+            if (v < 0 || v >= n || v == c) return fail(ctx, AET_EINVAL, "node %d: neighbour %d out of range or the node itself", c, v);
+            if (j > nbr_off[c] && nbr[j - 1] >= v) return fail(ctx, AET_EINVAL, "node %d: neighbours must be strictly ascending", c);
+        }
+    // every list is sorted now, so the reverse edge can be looked up by bisection
+    for (int c = 0; c < n; ++c)
+        for (int32_t j = nbr_off[c]; j < nbr_off[c + 1]; ++j) {
+            const int32_t v = nbr[j];
+            if (!std::binary_search(nbr + nbr_off[v], nbr + nbr_off[v + 1], (int32_t)c))
+                return fail(ctx, AET_EINVAL, "topology is not undirected: %d lists %d but not the reverse", c, v);
+        }
+    const size_t need = aet_topology_workspace_bytes(n, E);
+    if (workspace_bytes < need) return fail(ctx, AET_ENOMEM, "topology workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
+    ctx->nbr_off.assign(nbr_off, nbr_off + n + 1);
+    ctx->nbr.assign(nbr, nbr + E);
+    ctx->d_nbr_off = static_cast<int32_t *>(workspace);
+    ctx->d_nbr = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + align_up((size_t)(n + 1) * 4));
+    // the host copies above outlive the call, so the asynchronous uploads may read them
+    AET_HIP(ctx, hipMemcpyAsync(ctx->d_nbr_off, ctx->nbr_off.data(), (size_t)(n + 1) * 4, hipMemcpyHostToDevice, ctx->stream));
+    if (E > 0) AET_HIP(ctx, hipMemcpyAsync(ctx->d_nbr, ctx->nbr.data(), (size_t)E * 4, hipMemcpyHostToDevice, ctx->stream));
+    AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    ctx->p2p = true;
+    return AET_OK;
+}
+
+aet_status aet_receive(aet_ctx *ctx, float scale, int32_t *n_applied, int32_t *applied_sender,
+                       int32_t *applied_round) {
+    if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
+    if (!ctx->p2p) return fail(ctx, AET_ESTATE, "no topology set: the tick's second half is aet_server_aggregate");
+    if (!std::isfinite(scale)) return fail(ctx, AET_EINVAL, "scale is not finite");
+    std::vector<Msg> arr;
+    ArrivalPack pack;
+    const ArrivalPack *by_value = nullptr;
+    const Arrival *on_device = nullptr;
+    const aet_status st = stage_arrivals(ctx, scale, &arr, &pack, &by_value, &on_device);
+    if (st != AET_OK) return st;
+    if (by_value || on_device)
+        AET_HIP(ctx, launch_apply_neighbour_U(ctx->stream, ctx->profp(), ctx->Wc(0), ctx->Ps, ctx->P, ctx->n,
+                                              ctx->d_nbr_off, ctx->d_nbr, by_value, on_device, (int)arr.size()));
+    retire_arrivals(ctx, arr, n_applied, applied_sender, applied_round);
     return AET_OK;
 }
 
@@ -484,7 +590,8 @@ aet_status aet_run_ticks(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
     while (done < max_ticks && !aet_all_done(ctx, thr->rounds)) {
         aet_status st = aet_run_round(ctx, thr, eta, delay, nullptr, nullptr, nullptr);
         if (st != AET_OK) return st;
-        st = aet_server_aggregate(ctx, agg_scale, nullptr, nullptr, nullptr);
+        st = ctx->p2p ? aet_receive(ctx, agg_scale, nullptr, nullptr, nullptr)
+                      : aet_server_aggregate(ctx, agg_scale, nullptr, nullptr, nullptr);
         if (st != AET_OK) return st;
         ++done;
         if (ticks_done) *ticks_done = done;
@@ -570,8 +677,11 @@ aet_status aet_synchronize(aet_ctx *ctx) {
 aet_status aet_reset(aet_ctx *ctx) {
     if (!ctx) return AET_EINVAL;
     if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
-    // the replicas need no copy: every round starts by adopting the global model
+    // server form: the replicas need no copy, every round starts by adopting the global model
     AET_HIP(ctx, hipMemcpyAsync(ctx->Wg(), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    if (ctx->p2p)
+        for (int c = 0; c < ctx->n; ++c)
+            AET_HIP(ctx, hipMemcpyAsync(ctx->Wc(c), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream));
     std::fill(ctx->i_c.begin(), ctx->i_c.end(), 0);
     std::fill(ctx->t_c.begin(), ctx->t_c.end(), 0);
     std::fill(ctx->q_c.begin(), ctx->q_c.end(), 0);

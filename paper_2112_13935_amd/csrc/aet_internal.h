@@ -31,11 +31,11 @@ struct RoundParams {
     int32_t client;
 };
 
-// One arriving message for the server step: Wg -= scale * U.
+// One arriving message: w -= scale * U at the server, or at every neighbour of the sender.
 struct Arrival {
     const float *U;
     float scale;
-    int32_t pad_;
+    int32_t sender;
 };
 
 // A short arrival list that is passed to the kernel by value.
@@ -58,7 +58,7 @@ struct LayerScratch {
 enum Family {
     F_BEGIN_ROUND = 0, F_GATHER, F_DENSE_FWD, F_DENSE_BWD_DATA, F_DENSE_BWD_WEIGHT, F_CONV_FWD,
     F_CONV_BWD_DATA, F_CONV_BWD_WEIGHT, F_POOL_FWD, F_POOL_BWD, F_SOFTMAX_CE, F_SERVER_REDUCE,
-    F_SOFTMAX_ROUND, F_MLP_ROUND, F_COUNT
+    F_SOFTMAX_ROUND, F_MLP_ROUND, F_NEIGHBOUR_APPLY, F_COUNT
 };
 const char *family_name(int fam);
 
@@ -83,6 +83,7 @@ struct Profiler {
 };
 
 // ---- launchers (each returns the launch status) --------------------------------------
+// Wg == NULL (here and in the fused round kernels): the clients go on from their own replicas
 hipError_t launch_begin_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
                               const float *Wg, int64_t P);
 hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
@@ -91,6 +92,12 @@ hipError_t launch_server_reduce(hipStream_t s, Profiler *prof, float *Wg, const 
                                 int n_arr, int64_t P, float *partial, int max_chunks);
 hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, const ArrivalPack &pack,
                                      int n_arr, int64_t P);
+// Receive at the neighbours: replica r takes the arrivals whose sender is in nbr[nbr_off[r] ..
+// nbr_off[r+1]), in list order.  The list comes by value (pack != NULL, n_arr <= kArrivalPack)
+// or from device memory (darr).  W: the replicas, Ps floats apart.
+hipError_t launch_apply_neighbour_U(hipStream_t s, Profiler *prof, float *W, int64_t Ps, int64_t P,
+                                    int n_clients, const int32_t *nbr_off, const int32_t *nbr,
+                                    const ArrivalPack *pack, const Arrival *darr, int n_arr);
 hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
                                 uint32_t n_samples, int32_t *dst);
 // convolution on the matrix cores (kernels_conv_mfma.hip); bwd = backward-data

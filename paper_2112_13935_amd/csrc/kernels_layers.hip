@@ -36,7 +36,7 @@ __global__ void k_begin_round(const RoundParams *__restrict__ rp, const float *_
     const RoundParams p = rp[blockIdx.y];
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < P) {
-        p.W[i] = Wg[i];  // adopt the broadcast global model
+        if (Wg) p.W[i] = Wg[i];  // adopt the broadcast global model (server form)
         p.U[i] = 0.f;
     }
     if (i == 0) *p.loss = 0.f;

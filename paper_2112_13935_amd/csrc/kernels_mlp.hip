@@ -78,7 +78,7 @@ struct MlpPack {
 
 template <int NBT, int TPW, bool FAST>
 __global__ void __launch_bounds__(kMlpThreads, 1)
-k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *__restrict__ Wg,
+k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             int D, int H, int C, int G, unsigned long long *__restrict__ xrec, uint32_t tag0,
             int *__restrict__ errflag) {
     constexpr int B = 16 * NBT;
@@ -146,7 +146,9 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *__restrict__ W
         return x;
     };
 
-    // ---- adopt the global model: own slice into registers / LDS; U = 0 -----------------
+    // ---- adopt the global model (server form) or go on from the own replica (Wg == NULL:
+    // peer-to-peer form): own slice into registers / LDS; U = 0 -------------------------
+    if (!Wg) Wg = p.W;
     f4 W1r[TPW], U1r[TPW];
 #pragma unroll
     for (int tt = 0; tt < TPW; ++tt) {

@@ -1,4 +1,5 @@
-// Server step (Algorithm 2, Receive, in its client-server form):
+// Receive (Algorithm 2), at the server and at the neighbours.
+// Server step (Receive in its client-server form):
 //   w_global <- w_global - sum over this tick's arrivals of (agg_scale * eta_k) * U_{k,c}.
 // The U's are streamed once from HBM.  With few arrivals a single pass applies them in
 // order; with many, the arrivals are cut into chunks that are summed in parallel
@@ -59,6 +60,123 @@ hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, c
     if (timed) prof->before(F_SERVER_REDUCE, s);
     k_server_apply_small<<<(unsigned)((P + 255) / 256), 256, 0, s>>>(Wg, pack, n_arr, P);
     if (timed) prof->after(F_SERVER_REDUCE, s);
+    return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------
+// Receive at the neighbours (Algorithm 2 as printed): replica r applies, in list order,
+// the arrivals whose sender is one of its neighbours:  w_r -= (scale * eta_k) * U_{k,v}.
+// One block owns kNbElems consecutive parameters of one replica.  Its first wave picks the
+// matching arrivals out of the tick's list (a window of kNbWin at a time, order kept by
+// ballot + prefix count); then every thread carries its parameters through them.
+// ---------------------------------------------------------------------------------------
+constexpr int kNbWin = 256;     // arrivals examined per window
+constexpr int kNbVec = 2;       // float4 per thread
+constexpr int kNbElems = 256 * 4 * kNbVec;
+
+typedef float nf4 __attribute__((ext_vector_type(4)));
+
+template <bool PACK>
+__global__ void __launch_bounds__(256)
+k_apply_neighbour_U(float *__restrict__ W, int64_t Ps, const int32_t *__restrict__ nbr_off,
+                    const int32_t *__restrict__ nbr, ArrivalPack pack,
+                    const Arrival *__restrict__ arr, int n_arr) {
+    const int r = blockIdx.y;
+    const int n0 = nbr_off[r], n1 = nbr_off[r + 1];
+    if (n0 == n1) return;
+    __shared__ const float *selU[kNbWin];
+    __shared__ float selS[kNbWin];
+    __shared__ int nsel;
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * kNbElems + 4 * tid;
+    float *Wr = W + (int64_t)r * Ps;
+    nf4 w[kNbVec];
+    bool loaded = false;
+
+    for (int j0 = 0; j0 < n_arr; j0 += kNbWin) {
+        if (PACK) {
+            // the short list sits in the kernel arguments: a uniform scan, one writer
+            if (tid == 0) {
+                int cnt = 0;
+                for (int j = 0; j < n_arr; ++j) {
+                    const int v = pack.a[j].sender;
+                    bool hit = false;
+                    for (int q = n0; q < n1; ++q) hit = hit || nbr[q] == v;
+                    if (hit) { selU[cnt] = pack.a[j].U; selS[cnt] = pack.a[j].scale; ++cnt; }
+                }
+                nsel = cnt;
+            }
+        } else if (tid < 64) {
+            int cnt = 0;
+            const int jend = min(j0 + kNbWin, n_arr);
+            for (int t = j0; t < jend; t += 64) {
+                const int j = t + tid;
+                bool hit = false;
+                Arrival a = {nullptr, 0.f, -1};
+                if (j < jend) {
+                    a = arr[j];
+                    for (int q = n0; q < n1; ++q) hit = hit || nbr[q] == a.sender;
+                }
+                const unsigned long long mask = __ballot(hit);
+                if (hit) {
+                    const int pos = cnt + __popcll(mask & ((1ull << tid) - 1ull));
+                    selU[pos] = a.U;
+                    selS[pos] = a.scale;
+                }
+                cnt += __popcll(mask);
+            }
+            if (tid == 0) nsel = cnt;
+        }
+        __syncthreads();
+        const int ns = nsel;
+        if (ns > 0) {
+            if (!loaded) {
+#pragma unroll
+                for (int v = 0; v < kNbVec; ++v) {
+                    const int64_t i = base + 1024 * v;
+                    w[v] = i < Ps ? *reinterpret_cast<const nf4 *>(Wr + i) : nf4{0.f, 0.f, 0.f, 0.f};
+                }
+                loaded = true;
+            }
+            for (int s = 0; s < ns; ++s) {
+                const float *U = selU[s];
+                const float sc = selS[s];
+#pragma unroll
+                for (int v = 0; v < kNbVec; ++v) {
+                    const int64_t i = base + 1024 * v;
+                    if (i < Ps) {
+                        const nf4 u = *reinterpret_cast<const nf4 __attribute__((address_space(1))) *>(as_global(U) + i);
+                        w[v] -= sc * u;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+    }
+    if (loaded) {
+#pragma unroll
+        for (int v = 0; v < kNbVec; ++v) {
+            const int64_t i = base + 1024 * v;
+            if (i < Ps) *reinterpret_cast<nf4 *>(Wr + i) = w[v];
+        }
+    }
+}
+
+hipError_t launch_apply_neighbour_U(hipStream_t s, Profiler *prof, float *W, int64_t Ps, int64_t P,
+                                    int n_clients, const int32_t *nbr_off, const int32_t *nbr,
+                                    const ArrivalPack *pack, const Arrival *darr, int n_arr) {
+    (void)P;
+    if (n_arr <= 0) return hipSuccess;
+    const bool timed = prof && prof->on[F_NEIGHBOUR_APPLY];
+    if (timed) prof->before(F_NEIGHBOUR_APPLY, s);
+    dim3 grid((unsigned)((Ps + kNbElems - 1) / kNbElems), (unsigned)n_clients);
+    if (pack) {
+        k_apply_neighbour_U<true><<<grid, 256, 0, s>>>(W, Ps, nbr_off, nbr, *pack, nullptr, n_arr);
+    } else {
+        ArrivalPack none = {};
+        k_apply_neighbour_U<false><<<grid, 256, 0, s>>>(W, Ps, nbr_off, nbr, none, darr, n_arr);
+    }
+    if (timed) prof->after(F_NEIGHBOUR_APPLY, s);
     return hipGetLastError();
 }
 

@@ -72,7 +72,7 @@ __device__ __forceinline__ float row_max_dpp(float v) {
 // C classes (<= 16), NC columns per thread; EXACT: D == 512 * NC, no column guards
 template <int C, int NC, bool EXACT>
 __global__ void __launch_bounds__(kSmThreads, 1)
-k_softmax_round(const RoundParams *__restrict__ rp, const float *__restrict__ Wg, int D) {
+k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
     const RoundParams p = rp[blockIdx.x];
     const gcf_ptr Xg = as_global(p.X);
     const gci_ptr yg = as_global(p.y);
@@ -81,7 +81,9 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *__restrict__ Wg
 
     __shared__ float zpart[2][kSmWaves][16];
 
-    // adopt the global model; U = 0.  Lane `cls` of every row keeps bias and its U entry.
+    // adopt the global model (server form) or go on from the own replica (Wg == NULL:
+    // peer-to-peer form); U = 0.  Lane `cls` of every row keeps bias and its U entry.
+    if (!Wg) Wg = p.W;
     float W[C][NC], U[C][NC];
 #pragma unroll
     for (int o = 0; o < C; ++o) {

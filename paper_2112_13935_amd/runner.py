@@ -1,5 +1,6 @@
 """Drive a workload record (model, shards, schedule parameters) through the library:
-upload the shards with PyTorch, then call aet_run_round / aet_server_aggregate per tick.
+upload the shards with PyTorch, then call aet_run_round and aet_server_aggregate (or
+aet_receive, when the workload has a topology) per tick.
 Marshalling only; used by the tests, the smoke check and the benchmark."""
 from __future__ import annotations
 
@@ -25,6 +26,9 @@ class Run:
         self.lib = AetSgd(wl.model, self.X, self.y, wl.w0, wl.seed,
                           max_inflight=wl.delay_max + 1,
                           max_rounds=max(1, wl.rounds if max_rounds is None else max_rounds))
+        self.p2p = getattr(wl, "topology", None) is not None and self.n == wl.n_clients
+        if self.p2p:
+            self.lib.aet_set_topology(*wl.topology)
 
     def run_round(self, rounds: Optional[int] = None):
         wl = self.wl
@@ -37,12 +41,19 @@ class Run:
     def server_aggregate(self):
         return self.lib.aet_server_aggregate(self.wl.agg_scale)
 
+    def receive(self):
+        return self.lib.aet_receive(self.wl.agg_scale)
+
+    def exchange(self):
+        """The tick's second half: Receive at the neighbours or at the server."""
+        return self.receive() if self.p2p else self.server_aggregate()
+
     def run_all(self, rounds: Optional[int] = None, max_ticks: int = 100000) -> int:
         R = self.wl.rounds if rounds is None else rounds
         ticks = 0
         while not self.lib.aet_all_done(R):
             self.run_round(R)
-            self.server_aggregate()
+            self.exchange()
             ticks += 1
             if ticks > max_ticks:
                 raise RuntimeError("run did not finish")

@@ -151,13 +151,16 @@ def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_tick
                 et = None if twin is None else [abs(twin.round_info(c, k)["loss"] - io["loss"]) /
                                                 max(abs(io["loss"]), 1e-12)]
                 led.add("loss", what, [e], et)
-        app_o = orc.server_aggregate()
-        app_g = run.server_aggregate()
+        app_o = orc.exchange()
+        app_g = run.exchange()
         assert app_g == app_o, f"tick {orc.tick - 1}: aggregation order differs"
         if twin is not None:
-            assert twin.server_aggregate() == app_o
+            assert twin.exchange() == app_o
         if check_every_tick:
             compare_global(f"after tick {orc.tick - 1}")
+            if orc.p2p:   # Receive has moved the neighbours' models
+                for c in (range(orc.n) if check_clients is None else check_clients):
+                    compare_client(c, f"client {c} after tick {orc.tick - 1}")
         ticks += 1
         assert ticks <= max_ticks
     assert run.lib.aet_all_done(R)
