@@ -74,6 +74,64 @@ def per_step_bytes(model, fam_name):
     return total
 
 
+def per_step_flops(model, fam_name):
+    """Useful flops (2 per multiply-add, no tile padding) one client spends in one SGD
+    recursion inside the matrix-core kernels of one family; 0 for the other families."""
+    import workloads as W
+    B = model.batch
+    shp = model.shapes()
+    total = 0
+    first = True
+    for L, sl, (c, h, w), (oc, oh, ow) in zip(model.layers, model.param_slices(), shp[:-1], shp[1:]):
+        if L.type == W.DENSE:
+            macs = B * sl[1]
+            kind = "dense"
+        elif L.type == W.CONV:
+            macs = B * sl[1] * oh * ow
+            kind = "conv"
+        else:
+            continue
+        if fam_name == f"k_{kind}_fwd" or fam_name == f"k_{kind}_bwd_weight":
+            total += 2 * macs
+        elif fam_name == f"k_{kind}_bwd_data" and not first:   # no dX for the first layer
+            total += 2 * macs
+        first = False
+    return total
+
+
+def receive_record(run, wl, names):
+    """The tick's second half (server reduce, or Receive at the neighbours) timed over one
+    job run tick by tick: algorithmic bytes = read+write of every model that changes (8P)
+    plus one read of every U per model it is applied to (4P)."""
+    fam = names.index("k_apply_neighbour_U" if run.p2p else "server_reduce")
+    P4 = 4 * wl.model.n_params()
+    run.lib.aet_reset()
+    run.lib.aet_profile_enable(fam, True)
+    nbytes = 0
+    if run.p2p:
+        off, nbr = wl.topology
+    while not run.lib.aet_all_done(wl.rounds):
+        run.run_round()
+        senders = [c for c, _ in run.exchange()]
+        if not senders:
+            continue
+        if run.p2p:
+            receivers = set()
+            for c in senders:
+                receivers.update(nbr[off[c]:off[c + 1]].tolist())
+            nbytes += 2 * P4 * len(receivers) + P4 * sum(int(off[c + 1] - off[c]) for c in senders)
+        else:
+            nbytes += 2 * P4 + P4 * len(senders)
+    launches, ms = run.lib.aet_profile_read(fam)
+    run.lib.aet_profile_enable(fam, False)
+    if launches == 0 or ms <= 0:
+        return None
+    gbs = nbytes / (ms * 1e-3) / 1e9
+    return {"kernel": names[fam], "bound": "hbm", "launches_per_step": launches,
+            "avg_launch_us": ms * 1e3 / launches, "algorithmic_bytes_per_launch": nbytes / launches,
+            "achieved": gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS}
+
+
 def cpu_baseline(wl, budget_s=12.0):
     """The fp64 oracle as it stands, on the host cores, for about budget_s seconds of the
     same workload from its start (whole ticks); client-samples per second."""
@@ -86,7 +144,7 @@ def cpu_baseline(wl, budget_s=12.0):
     while not orc.all_done() and time.perf_counter() - t0 < budget_s:
         for c, k in orc.run_round():
             done += orc.round_info(c, k)["s"]
-        orc.server_aggregate()
+        orc.exchange()
         ticks += 1
     dt = time.perf_counter() - t0
     orc.close()
@@ -103,6 +161,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload 1..5 (default 2: the MLP)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--rounds", type=int, default=0, help="exploration only: fewer rounds per client")
+    ap.add_argument("--topology", choices=["server", "ring"], default="server",
+                    help="server: clients and a server (default); ring: peer-to-peer form, every "
+                         "node sends to its two ring neighbours")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run a plain 256 MiB device copy (calibrates the HBM byte counters)")
     args = ap.parse_args()
@@ -123,6 +184,10 @@ def main():
     if args.rounds > 0:
         wl.rounds = args.rounds
         wl.name += f"_first{args.rounds}rounds"
+    if args.topology == "ring":
+        wl.topology = W.ring_topology(wl.n_clients)
+        wl.agg_scale = 1.0 / 3.0      # a node and its two neighbours
+        wl.name += "_ring"
     run = Run(wl)
     names = run.lib.profile_family_names()
     total_samples = wl.total_client_samples()
@@ -181,6 +246,22 @@ def main():
     launches_per_job = launches / args.steps
     avg_launch_ms = kernel_ms / max(launches, 1)
     achieved = (bytes_per_job / launches_per_job) / (avg_launch_ms * 1e-3) / 1e9
+    roof = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": fam, "byte_model": model_name,
+            "avg_launch_us": avg_launch_ms * 1e3, "launches_per_step": launches_per_job,
+            "algorithmic_bytes_per_launch": bytes_per_job / launches_per_job}
+    flops_per_job = per_step_flops(wl.model, fam) * total_steps
+    if flops_per_job > 0:
+        # a contraction on the matrix cores: priced against the fp32 MFMA peak
+        tf = (flops_per_job / launches_per_job) / (avg_launch_ms * 1e-3) / 1e12
+        roof = {"bound": "mfma", "achieved": tf, "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                "frac": tf / FP32_MFMA_PEAK_TFLOPS, "traffic": None, "kernel": fam,
+                "flop_model": "useful multiply-adds x 2, no tile padding",
+                "avg_launch_us": avg_launch_ms * 1e3, "launches_per_step": launches_per_job,
+                "algorithmic_flops_per_launch": flops_per_job / launches_per_job}
+    roof["share_of_kernel_time"] = share
+    roof["kernel_time_shares"] = shares
+    recv = receive_record(run, wl, names)
     out = {
         "metric": "client SGD samples/sec (all clients, 1 GPU)",
         "value": value, "unit": "client-samples/s", "n_gpus": 1, "steps": args.steps,
@@ -190,12 +271,11 @@ def main():
                    "batch": wl.model.batch, "threshold": f"s_i = {wl.a}*i + {wl.b}",
                    "client_samples_per_step": total_samples, "ticks_per_step": ticks,
                    "params": wl.model.n_params(), "agg_scale": wl.agg_scale},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "kernel": fam, "byte_model": model_name,
-                     "avg_launch_us": avg_launch_ms * 1e3, "launches_per_step": launches_per_job,
-                     "algorithmic_bytes_per_launch": bytes_per_job / launches_per_job,
-                     "share_of_kernel_time": share, "kernel_time_shares": shares},
+        "roofline": roof,
     }
+    out["config"]["topology"] = args.topology
+    if recv is not None:
+        out["receive"] = recv
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     run.close()

@@ -12,45 +12,62 @@ namespace aet {
 
 constexpr int kChunk = 16;  // arrivals per chunk of the two-stage form
 
+typedef float sf4 __attribute__((ext_vector_type(4)));
+typedef const sf4 __attribute__((address_space(1))) *gcv4_ptr;
+
+// Every kernel here moves float4s: the models and the U slots are padded to a multiple of
+// 64 floats (nv = padded length / 4), the padding is carried along and never looked at.
 __global__ void __launch_bounds__(256)
-k_server_apply(float *__restrict__ Wg, const Arrival *__restrict__ arr, int n_arr, int64_t P) {
+k_server_apply(float *__restrict__ Wg, const Arrival *__restrict__ arr, int n_arr, int64_t nv) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= P) return;
-    float w = Wg[i];
-    for (int j = 0; j < n_arr; ++j) w -= arr[j].scale * arr[j].U[i];
-    Wg[i] = w;
+    if (i >= nv) return;
+    sf4 w = reinterpret_cast<const sf4 *>(Wg)[i];
+#pragma unroll 4
+    for (int j = 0; j < n_arr; ++j) w -= arr[j].scale * reinterpret_cast<gcv4_ptr>(as_global(arr[j].U))[i];
+    reinterpret_cast<sf4 *>(Wg)[i] = w;
 }
 
 // the same with the arrival list in the kernel arguments (no staging copy)
 __global__ void __launch_bounds__(256)
-k_server_apply_small(float *__restrict__ Wg, ArrivalPack pack, int n_arr, int64_t P) {
+k_server_apply_small(float *__restrict__ Wg, ArrivalPack pack, int n_arr, int64_t nv) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= P) return;
-    float w = Wg[i];
-    for (int j = 0; j < n_arr; ++j) w -= pack.a[j].scale * as_global(pack.a[j].U)[i];
-    Wg[i] = w;
+    if (i >= nv) return;
+    sf4 w = reinterpret_cast<const sf4 *>(Wg)[i];
+#pragma unroll 4
+    for (int j = 0; j < n_arr; ++j) w -= pack.a[j].scale * reinterpret_cast<gcv4_ptr>(as_global(pack.a[j].U))[i];
+    reinterpret_cast<sf4 *>(Wg)[i] = w;
 }
 
 __global__ void __launch_bounds__(256)
-k_server_partial(const Arrival *__restrict__ arr, int n_arr, int64_t P, int64_t stride,
-                 float *__restrict__ partial) {
+k_server_partial(const Arrival *__restrict__ arr, int n_arr, int64_t nv, float *__restrict__ partial) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= P) return;
+    if (i >= nv) return;
     const int j0 = blockIdx.y * kChunk;
-    const int j1 = min(j0 + kChunk, n_arr);
-    float s = 0.f;
-    for (int j = j0; j < j1; ++j) s += arr[j].scale * arr[j].U[i];
-    partial[(int64_t)blockIdx.y * stride + i] = s;
+    sf4 u[kChunk];
+    float sc[kChunk];
+    // all loads of the chunk are in flight together; the sum keeps the list order
+#pragma unroll
+    for (int j = 0; j < kChunk; ++j) {
+        const bool in = j0 + j < n_arr;
+        const Arrival a = arr[in ? j0 + j : j0];
+        sc[j] = in ? a.scale : 0.f;
+        u[j] = reinterpret_cast<gcv4_ptr>(as_global(a.U))[i];
+    }
+    sf4 s = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < kChunk; ++j)
+        if (j0 + j < n_arr) s += sc[j] * u[j];
+    reinterpret_cast<sf4 *>(partial)[(int64_t)blockIdx.y * nv + i] = s;
 }
 
 __global__ void __launch_bounds__(256)
-k_server_finish(float *__restrict__ Wg, const float *__restrict__ partial, int chunks, int64_t P,
-                int64_t stride) {
+k_server_finish(float *__restrict__ Wg, const float *__restrict__ partial, int chunks, int64_t nv) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= P) return;
-    float w = Wg[i];
-    for (int c = 0; c < chunks; ++c) w -= partial[(int64_t)c * stride + i];
-    Wg[i] = w;
+    if (i >= nv) return;
+    sf4 w = reinterpret_cast<const sf4 *>(Wg)[i];
+#pragma unroll 8
+    for (int c = 0; c < chunks; ++c) w -= reinterpret_cast<const sf4 *>(partial)[(int64_t)c * nv + i];
+    reinterpret_cast<sf4 *>(Wg)[i] = w;
 }
 
 hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, const ArrivalPack &pack,
@@ -58,7 +75,8 @@ hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, c
     if (n_arr <= 0) return hipSuccess;
     const bool timed = prof && prof->on[F_SERVER_REDUCE];
     if (timed) prof->before(F_SERVER_REDUCE, s);
-    k_server_apply_small<<<(unsigned)((P + 255) / 256), 256, 0, s>>>(Wg, pack, n_arr, P);
+    const int64_t nv = (P + 63) / 64 * 16;
+    k_server_apply_small<<<(unsigned)((nv + 255) / 256), 256, 0, s>>>(Wg, pack, n_arr, nv);
     if (timed) prof->after(F_SERVER_REDUCE, s);
     return hipGetLastError();
 }
@@ -190,18 +208,18 @@ hipError_t launch_server_reduce(hipStream_t s, Profiler *prof, float *Wg, const 
     if (n_arr <= 0) return hipSuccess;
     const bool timed = prof && prof->on[F_SERVER_REDUCE];
     if (timed) prof->before(F_SERVER_REDUCE, s);
-    const unsigned gx = (unsigned)((P + 255) / 256);
+    const int64_t nv = (P + 63) / 64 * 16;   // float4s per padded model
+    const unsigned gx = (unsigned)((nv + 255) / 256);
     const int chunks = server_reduce_chunks(n_arr, P);
     if (chunks == 1 || chunks > max_chunks) {
-        k_server_apply<<<gx, 256, 0, s>>>(Wg, darr, n_arr, P);
+        k_server_apply<<<gx, 256, 0, s>>>(Wg, darr, n_arr, nv);
         if (timed) prof->after(F_SERVER_REDUCE, s);
         return hipGetLastError();
     }
-    const int64_t stride = (P + 63) / 64 * 64;
-    k_server_partial<<<dim3(gx, chunks), 256, 0, s>>>(darr, n_arr, P, stride, partial);
+    k_server_partial<<<dim3(gx, chunks), 256, 0, s>>>(darr, n_arr, nv, partial);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    k_server_finish<<<gx, 256, 0, s>>>(Wg, partial, chunks, P, stride);
+    k_server_finish<<<gx, 256, 0, s>>>(Wg, partial, chunks, nv);
     if (timed) prof->after(F_SERVER_REDUCE, s);
     return hipGetLastError();
 }
