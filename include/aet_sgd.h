@@ -166,6 +166,18 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
 aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applied,
                                 int32_t *applied_client, int32_t *applied_round);
 
+/* Setup (Algorithm 1): round lengths from coin flips.  After this call the threshold given
+ * to aet_run_round is the GLOBAL sequence s_i = a*i + b (samples over all nodes), each of
+ * the s_i / batch recursions of global round i is assigned to node c with probability
+ * p_c = weights[c] / sum(weights), and node c's round i has
+ *   s_{i,c} = batch * |{ t : a(i,t) = c }|     (E[s_{i,c}] = p_c s_i; 0 is possible: the
+ * node then sends an empty message).  a(i,t): value t of the SplitMix64 stream keyed by
+ * (seed, round i), top 32 bits mapped onto [0, sum(weights)) by multiply-shift, located
+ * in the cumulative weights; integer arithmetic only, a pure function of (seed, i, t).
+ *   weights  HOST, n_clients entries, sum in [1, 2^32); copied during the call.
+ * Only before the first round (AET_ESTATE later). */
+aet_status aet_set_setup(aet_ctx *ctx, const uint32_t *weights, uint64_t seed);
+
 /* Peer-to-peer form (Algorithm 2 as printed; Section 2.2.1: undirected topology, the
  * neighbour list of every node is given).  After this call every node keeps its own model
  * from round to round, a message goes to the sender's neighbours (aet_receive), and the

@@ -20,6 +20,8 @@
  *                                                                        Section 2.2.1 (undirected
  *                                                                        topology, neighbour lists given)
  *   - the delay checkpoint max_e (i - H_e) > d                         : Algorithm 2, Synchronize
+ *   - Setup: each of the s_i recursions of global round i is assigned
+ *     to node c with probability p_c; s_{i,c} counts node c's share    : Algorithm 1
  *   - round lengths s_i = a*i^p + b with p = 1; step size
  *     eta0 / (1 + beta * t^power), constant inside a round             : Section 3.1, Experiments
  *                                                                        ("Objective function"), Table 5
@@ -86,6 +88,9 @@ typedef struct orc_ctx {
     int64_t *N;
     real *Wg, *W;
     int64_t *i_c, *t_c, *q_c, *free_at, *H;
+    int setup;               /* 1: round lengths from the coin flips of Algorithm 1 */
+    uint64_t setup_seed;
+    uint64_t *cumw;          /* cumulative node weights, cumw[c] = w_0 + ... + w_c */
     int p2p;                 /* 1: peer-to-peer form on the topology below */
     int32_t *nbr_off, *nbr;  /* neighbour lists, CSR: nbr[nbr_off[c] .. nbr_off[c+1]) ascending */
     int64_t tick;
@@ -112,6 +117,7 @@ uint64_t orc_draw(uint64_t seed, uint64_t k) { return mix64(seed + (k + 1) * GAM
 
 #define TAG_SAMPLE 0
 #define TAG_NET 1
+#define TAG_SETUP 2
 /* one stream per (seed, purpose, client); element `ctr` of that stream */
 uint64_t orc_stream(uint64_t seed, uint64_t tag, uint64_t c, uint64_t ctr) {
     return orc_draw(orc_draw(orc_draw(seed, tag), c), ctr);
@@ -374,7 +380,7 @@ void orc_destroy(orc_ctx *C) {
     free(C->X); free(C->y); free(C->N);
     free(C->Wg); free(C->W);
     free(C->i_c); free(C->t_c); free(C->q_c); free(C->free_at); free(C->H);
-    free(C->nbr_off); free(C->nbr);
+    free(C->nbr_off); free(C->nbr); free(C->cumw);
     free(C);
 }
 
@@ -413,6 +419,46 @@ orc_ctx *orc_create(const orc_model *m, int32_t n_clients, const float *const *X
 
 static int fail(orc_ctx *C, const char *msg) { snprintf(C->err, sizeof C->err, "%s", msg); return -1; }
 const char *orc_last_error(const orc_ctx *C) { return C->err; }
+
+/* Algorithm 1 (Setup): recursion t of global round i belongs to node a(i,t) = c with
+ * probability p_c = weight_c / sum of weights.  The draw is element t of the hash stream of
+ * (seed, round i), mapped to [0, sum of weights) by multiply-shift; c is the node whose
+ * cumulative-weight interval holds it.  Integer arithmetic only. */
+int32_t orc_setup_owner(uint64_t seed, const uint64_t *cumw, int32_t n, int64_t i, int64_t t) {
+    const uint64_t r = to_range(orc_stream(seed, TAG_SETUP, (uint64_t)i, (uint64_t)t), cumw[n - 1]);
+    int32_t c = 0;
+    while (r >= cumw[c]) ++c;
+    return c;
+}
+
+/* From now on the threshold a*i + b is the GLOBAL sequence s_i (samples over all nodes) and
+ * node c's round i has s_{i,c} = batch * |{ t < s_i / batch : a(i,t) = c }| samples: the
+ * unit that is handed out is one recursion (one mini-batch).  weights: n non-negative
+ * integers, their sum in [1, 2^32). */
+int orc_set_setup(orc_ctx *C, const uint32_t *weights, uint64_t seed) {
+    uint64_t sum = 0;
+    for (int c = 0; c < C->n; ++c) sum += weights[c];
+    if (sum < 1 || sum >= (1ULL << 32)) return fail(C, "sum of the weights must be in [1, 2^32)");
+    for (int c = 0; c < C->n; ++c) if (C->i_c[c] != 0) return fail(C, "Setup comes before the first round");
+    free(C->cumw);
+    C->cumw = (uint64_t *)malloc(sizeof(uint64_t) * C->n);
+    sum = 0;
+    for (int c = 0; c < C->n; ++c) { sum += weights[c]; C->cumw[c] = sum; }
+    C->setup = 1; C->setup_seed = seed;
+    return 0;
+}
+
+/* s_{i,c}: the node's round length in samples (-1: s_i is not a multiple of the batch) */
+static int64_t round_length(const orc_ctx *C, int c, int64_t i, int64_t a, int64_t b) {
+    const int64_t s = orc_threshold(a, b, i);
+    const int B = C->model.batch;
+    if (s % B) return -1;
+    if (!C->setup) return s;
+    int64_t mine = 0;
+    for (int64_t t = 0; t < s / B; ++t)
+        if (orc_setup_owner(C->setup_seed, C->cumw, C->n, i, t) == c) mine += 1;
+    return mine * B;
+}
 
 /* Switch to the peer-to-peer form of Algorithm 2 on an undirected topology (Section 2.2.1:
  * the neighbour list of every node is given).  nbr_off has n+1 entries; the neighbours of c
@@ -480,8 +526,10 @@ int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0,
             }
             if (dc > d_max) continue;
         }
-        int64_t s = orc_threshold(a, b, C->i_c[c]);
-        if (s % B) { free(act); return fail(C, "round length is not a multiple of the mini-batch"); }
+        if (round_length(C, c, C->i_c[c], a, b) < 0) {
+            free(act);
+            return fail(C, "round length is not a multiple of the mini-batch");
+        }
         if (compute_factor && compute_factor[c] < 1) { free(act); return fail(C, "compute factor < 1"); }
         act[na++] = c;
     }
@@ -492,7 +540,7 @@ int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0,
     for (int ai = 0; ai < na; ++ai) {
         const int c = act[ai];
         const int64_t i = C->i_c[c];
-        const int64_t s = orc_threshold(a, b, i), m = s / B;
+        const int64_t s = round_length(C, c, i, a, b), m = s / B;
         const double eta_d = orc_eta(eta0, beta, power, C->t_c[c]);
         const real eta = (real)eta_d;
         real *Wc = C->W + (int64_t)c * C->P;

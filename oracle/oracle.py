@@ -85,6 +85,10 @@ def load(prec: str = "f64"):
                                   vp, vp, vp]
     lib.orc_server_aggregate.restype = C.c_int
     lib.orc_server_aggregate.argtypes = [vp, dbl, vp, vp, vp]
+    lib.orc_set_setup.restype = C.c_int
+    lib.orc_set_setup.argtypes = [vp, vp, u64]
+    lib.orc_setup_owner.restype = i32
+    lib.orc_setup_owner.argtypes = [u64, vp, i32, i64, i64]
     lib.orc_set_topology.restype = C.c_int
     lib.orc_set_topology.argtypes = [vp, vp, vp]
     lib.orc_receive.restype = C.c_int
@@ -166,6 +170,8 @@ class Oracle:
         self.p2p = False
         if getattr(wl, "topology", None) is not None and self.n == wl.n_clients:
             self.set_topology(*wl.topology)
+        if getattr(wl, "setup_weights", None) is not None and self.n == wl.n_clients:
+            self.set_setup(wl.setup_weights, wl.setup_seed)
 
     def close(self):
         if self.ctx:
@@ -204,6 +210,13 @@ class Oracle:
             self.ctx, self.wl.agg_scale if agg_scale is None else agg_scale,
             C.byref(na), _ptr(ac), _ptr(ar)))
         return list(zip(ac[: na.value].tolist(), ar[: na.value].tolist()))
+
+    def set_setup(self, weights, seed: int):
+        """Round lengths from the coin flips of Algorithm 1 (Setup); the workload's
+        threshold becomes the global sequence."""
+        self._weights = np.ascontiguousarray(weights, dtype=np.uint32)
+        assert self._weights.shape[0] == self.n
+        self._check(self.lib.orc_set_setup(self.ctx, _ptr(self._weights), C.c_uint64(seed)))
 
     def set_topology(self, nbr_off, nbr):
         """Peer-to-peer form on the given neighbour lists (CSR)."""

@@ -23,7 +23,7 @@ EXPORTS = [
     "aet_all_done", "aet_tick", "aet_history", "aet_inflight", "aet_synchronize",
     "aet_last_error", "aet_destroy", "aet_reset", "aet_profile_families",
     "aet_profile_family_name", "aet_profile_enable", "aet_profile_read", "aet_run_ticks",
-    "aet_topology_workspace_bytes", "aet_set_topology", "aet_receive",
+    "aet_topology_workspace_bytes", "aet_set_topology", "aet_receive", "aet_set_setup",
 ]
 
 
@@ -111,6 +111,8 @@ def load_library():
     lib.aet_last_error.argtypes = [vp]
     lib.aet_reset.restype = C.c_int
     lib.aet_reset.argtypes = [vp]
+    lib.aet_set_setup.restype = C.c_int
+    lib.aet_set_setup.argtypes = [vp, vp, C.c_uint64]
     lib.aet_topology_workspace_bytes.restype = C.c_size_t
     lib.aet_topology_workspace_bytes.argtypes = [i32, i32]
     lib.aet_set_topology.restype = C.c_int
@@ -230,6 +232,13 @@ class AetSgd:
         self._check(self.lib.aet_server_aggregate(self.ctx, C.c_float(agg_scale), C.byref(na),
                                                   _hptr(self._ac), _hptr(self._ar)))
         return list(zip(self._ac[: na.value].tolist(), self._ar[: na.value].tolist()))
+
+    def aet_set_setup(self, weights: np.ndarray, seed: int):
+        """Round lengths from the coin flips of Algorithm 1; p_c = weights[c] / sum."""
+        w = np.ascontiguousarray(weights, dtype=np.uint32)
+        if w.shape[0] != self.n:
+            raise ValueError("weights needs n_clients entries")
+        self._check(self.lib.aet_set_setup(self.ctx, _hptr(w), C.c_uint64(seed)))
 
     def aet_set_topology(self, nbr_off: np.ndarray, nbr: np.ndarray):
         """Peer-to-peer form on the given neighbour lists (CSR, host arrays)."""

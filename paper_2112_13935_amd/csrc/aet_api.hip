@@ -24,6 +24,7 @@ constexpr int kRing = 4;            // pinned staging buffers in flight
 constexpr int kDebugIdx = 65536;    // capacity of the debug index buffer
 constexpr uint64_t kTagSample = 0;  // stream purposes of the counter hash
 constexpr uint64_t kTagNet = 1;
+constexpr uint64_t kTagSetup = 2;
 
 struct Msg {
     int32_t c, k;
@@ -166,6 +167,12 @@ struct aet_ctx {
     bool p2p = false;
     std::vector<int32_t> nbr_off, nbr;
     int32_t *d_nbr_off = nullptr, *d_nbr = nullptr;
+    // Setup (Algorithm 1): node weights and, per global round, every node's share of it
+    bool setup = false;
+    uint64_t setup_seed = 0;
+    std::vector<uint64_t> cumw;
+    int64_t setup_a = -1, setup_b = -1;
+    std::vector<std::vector<int64_t>> setup_share;  // [round][node] recursions
     int engine = 0;
     uint32_t epoch = 0;  // step-tag base of the fused kernels' exchange records
     std::string err;
@@ -203,6 +210,31 @@ aet_status hip_fail(aet_ctx *ctx, hipError_t e, const char *what) {
         hipError_t e_ = (call);                              \
         if (e_ != hipSuccess) return hip_fail(ctx, e_, #call); \
     } while (0)
+
+// Recursions of global round i that the coin flips of Algorithm 1 hand to every node:
+// recursion t goes to the node whose cumulative-weight interval holds the t-th value of the
+// hash stream of (seed, round i), mapped onto [0, sum of weights) by multiply-shift.
+const std::vector<int64_t> &setup_shares(aet_ctx *ctx, int64_t i, int64_t a, int64_t b) {
+    if (a != ctx->setup_a || b != ctx->setup_b) {
+        ctx->setup_share.clear();
+        ctx->setup_a = a;
+        ctx->setup_b = b;
+    }
+    if ((int64_t)ctx->setup_share.size() <= i) ctx->setup_share.resize(i + 1);
+    std::vector<int64_t> &sh = ctx->setup_share[i];
+    if (sh.empty()) {
+        sh.assign(ctx->n, 0);
+        const uint64_t key = splitmix_at(splitmix_at(ctx->setup_seed, kTagSetup), (uint64_t)i);
+        const uint64_t W = ctx->cumw.back();
+        const int64_t steps = (a * i + b) / ctx->B;
+        for (int64_t t = 0; t < steps; ++t) {
+            const uint64_t r = ((splitmix_at(key, (uint64_t)t) >> 32) * W) >> 32;
+            const int c = (int)(std::upper_bound(ctx->cumw.begin(), ctx->cumw.end(), r) - ctx->cumw.begin());
+            sh[c] += 1;
+        }
+    }
+    return sh;
+}
 
 }  // namespace
 
@@ -344,8 +376,9 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         }
         if (cf && cf[c] < 1) return fail(ctx, AET_EINVAL, "compute_factor[%d] < 1", c);
         const int64_t i = ctx->i_c[c];
-        const int64_t s = thr->a * i + thr->b;
+        int64_t s = thr->a * i + thr->b;
         if (s % ctx->B) return fail(ctx, AET_EINVAL, "round length s_%lld = %lld of client %d is not a multiple of batch %d", (long long)i, (long long)s, c, ctx->B);
+        if (ctx->setup) s = setup_shares(ctx, i, thr->a, thr->b)[c] * ctx->B;  // s_{i,c} of Algorithm 1
         const int64_t m = s / ctx->B;
         if (m > 2147483647LL) return fail(ctx, AET_EINVAL, "round too long");
         RoundRec r;
@@ -498,6 +531,23 @@ aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applie
                                           reinterpret_cast<float *>(ctx->ws + ctx->lo.partial), ctx->lo.max_chunks));
     }
     retire_arrivals(ctx, arr, n_applied, applied_client, applied_round);
+    return AET_OK;
+}
+
+aet_status aet_set_setup(aet_ctx *ctx, const uint32_t *weights, uint64_t seed) {
+    if (!ctx) return AET_EINVAL;
+    if (!weights) return fail(ctx, AET_EINVAL, "NULL argument");
+    for (int c = 0; c < ctx->n; ++c)
+        if (ctx->i_c[c] != 0) return fail(ctx, AET_ESTATE, "Setup comes before the first round");
+    uint64_t sum = 0;
+    for (int c = 0; c < ctx->n; ++c) sum += weights[c];
+    if (sum < 1 || sum >= (1ull << 32)) return fail(ctx, AET_EINVAL, "the sum of the weights must be in [1, 2^32)");
+    ctx->cumw.resize(ctx->n);
+    sum = 0;
+    for (int c = 0; c < ctx->n; ++c) { sum += weights[c]; ctx->cumw[c] = sum; }
+    ctx->setup = true;
+    ctx->setup_seed = seed;
+    ctx->setup_share.clear();
     return AET_OK;
 }
 

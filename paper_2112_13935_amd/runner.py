@@ -26,6 +26,8 @@ class Run:
         self.lib = AetSgd(wl.model, self.X, self.y, wl.w0, wl.seed,
                           max_inflight=wl.delay_max + 1,
                           max_rounds=max(1, wl.rounds if max_rounds is None else max_rounds))
+        if getattr(wl, "setup_weights", None) is not None and self.n == wl.n_clients:
+            self.lib.aet_set_setup(wl.setup_weights, wl.setup_seed)
         self.p2p = getattr(wl, "topology", None) is not None and self.n == wl.n_clients
         if self.p2p:
             self.lib.aet_set_topology(*wl.topology)

@@ -128,9 +128,13 @@ class Workload:
     d_max: int = -1                # SYNCHRONIZE gate off
     notes: str = ""
     topology: Optional[tuple] = None   # (nbr_off, nbr) neighbour lists: peer-to-peer form
+    setup_weights: Optional[np.ndarray] = None    # uint32 [n]: p_c = w_c / sum(w); the threshold
+    setup_seed: int = 0                           # is then the global sequence s_i (Algorithm 1)
 
     def total_client_samples(self, rounds: Optional[int] = None) -> int:
         R = self.rounds if rounds is None else rounds
+        if self.setup_weights is not None:      # the nodes share the global rounds
+            return sum(self.a * i + self.b for i in range(R))
         return self.n_clients * sum(self.a * i + self.b for i in range(R))
 
 
