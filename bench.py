@@ -74,6 +74,36 @@ def per_step_bytes(model, fam_name):
     return total
 
 
+def counter_traffic(fam_name, workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter
+    summary (FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a
+    plain copy of known size), or None: no summary for this kernel and workload, or the
+    kernel source has changed since the counters were taken."""
+    import hashlib
+    path = os.path.join(ROOT, "profiles", f"{fam_name}_{workload}_pmc.md")
+    if not os.path.exists(path):
+        return None
+    rec = {}
+    for line in open(path):
+        parts = line.strip().split(": ", 1)
+        if len(parts) == 2 and line.startswith("    "):
+            rec[parts[0]] = parts[1]
+    src = {"k_mlp_round": "kernels_mlp.hip", "k_softmax_round": "kernels_softmax.hip"}.get(fam_name)
+    if src is None or "source_sha256" not in rec:
+        return None
+    h = hashlib.sha256()
+    for f in (src, "aet_device.h", "aet_internal.h"):
+        with open(os.path.join(ROOT, "paper_2112_13935_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    if h.hexdigest() != rec["source_sha256"]:
+        return None
+    try:
+        return 1024.0 * (float(rec["fetch_kib_per_launch"]) * float(rec["fetch_scale"]) +
+                         float(rec["write_kib_per_launch"]) * float(rec["write_scale"]))
+    except (KeyError, ValueError):
+        return None
+
+
 def per_step_flops(model, fam_name):
     """Useful flops (2 per multiply-add, no tile padding) one client spends in one SGD
     recursion inside the matrix-core kernels of one family; 0 for the other families."""
@@ -259,6 +289,8 @@ def main():
                 "flop_model": "useful multiply-adds x 2, no tile padding",
                 "avg_launch_us": avg_launch_ms * 1e3, "launches_per_step": launches_per_job,
                 "algorithmic_flops_per_launch": flops_per_job / launches_per_job}
+    if args.rounds == 0 and args.topology == "server":
+        roof["traffic"] = counter_traffic(fam, wl.name)
     roof["share_of_kernel_time"] = share
     roof["kernel_time_shares"] = shares
     recv = receive_record(run, wl, names)
