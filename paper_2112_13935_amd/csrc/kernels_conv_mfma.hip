@@ -253,11 +253,24 @@ struct WgradGeom {
     int OWP;          // output width rounded up to a multiple of 4
     int KTOT;         // IC*K*K + 1 (the extra column multiplies by one: the bias)
     int NTT, MTT;     // N tiles (of 16 k) and M tiles (of 16 output channels) in total
+    int MTS;          // M tiles staged in LDS (what the waves' tiling covers, >= MTT)
+    int DPL;          // floats per channel of the staged d(output) tile: R*OWP padded to 4 mod 32,
+                      // so that the 16 channels x 4 pixels of an A operand fall into distinct banks
     int items_per_sample, S;
     int64_t in_size, out_size, w_off, b_off;
 };
 
-template <int KS, int MT, int NTW>
+constexpr int kPreIn = 32;  // input-tile elements one thread carries from one work item to the next
+constexpr int kPreD = 16;   // the same for the d(output) tile
+
+// MT x NTW accumulator tiles per wave.  WM = 1: a wave owns M tiles 0..MT-1 and N tiles
+// wave, wave+4, ...; WM = 2 (few N tiles): the waves form a 2 x 2 grid, wave w owns M tiles
+// w/2, w/2+2, ... and N tiles w%2, w%2+2, ...
+//
+// Staging: a thread is tied to one position of the tile (row, column) and walks the channels,
+// so the loop has no index arithmetic; the next work item's elements are fetched into
+// registers before the products of the current one start and go to LDS after them.
+template <int KS, int MT, int NTW, int WM>
 __global__ void __launch_bounds__(256)
 k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
                   const float *__restrict__ in, const float *__restrict__ dout,
@@ -266,11 +279,14 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
     if (u >= p.m) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
     const int sl = blockIdx.x;
+    const int m0 = WM == 1 ? 0 : (wave >> 1);   // first M tile of the wave, stride WM
+    const int n0 = WM == 1 ? wave : (wave & 1);  // first N tile of the wave, stride NS
+    constexpr int NS = 4 / WM;
 
     extern __shared__ float smem[];
     const int plane = g.rowsT * g.SWP;
     float *Ism = smem;                       // [IC + 2][rowsT][SWP]; plane IC = ones, IC+1 = zeros
-    float *Dsm = Ism + (g.IC + 2) * plane;   // [16*MT][R][OWP]
+    float *Dsm = Ism + (g.IC + 2) * plane;   // [16*MTS][DPL]
     const int dplane = g.R * g.OWP;
 
     for (int e = tid; e < 2 * plane; e += 256) Ism[g.IC * plane + e] = e < plane ? 1.f : 0.f;
@@ -279,7 +295,7 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
     int kb[NTW];
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
-        const int k = 16 * (wave + 4 * j) + li;
+        const int k = 16 * (n0 + NS * j) + li;
         int off = (g.IC + 1) * plane;  // zeros
         if (k < g.IC * KS * KS) {
             const int c = k / (KS * KS), r = k - c * KS * KS;
@@ -295,51 +311,54 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
 #pragma unroll
         for (int j = 0; j < NTW; ++j) acc[m][j] = f4{0.f, 0.f, 0.f, 0.f};
 
+    // this thread's position in the input tile and in the d(output) tile
+    const int gin = 256 / plane;                 // channel groups walking the input tile
+    const int ipos = tid % plane, igrp = tid / plane;
+    const int ity = ipos / g.SWP, itx = ipos - ity * g.SWP;
+    const bool ixok = igrp < gin && (unsigned)(itx - g.pad) < (unsigned)g.IW;
+    const int nq_in = igrp < gin ? (g.IC - igrp + gin - 1) / gin : 0;
+    const int gd = 256 / dplane;
+    const int dpos = tid % dplane, dgrp = tid / dplane;
+    const int dr = dpos / g.OWP, dx = dpos - dr * g.OWP;
+    const bool dxok = dgrp < gd && dx < g.OW;
+    const int nq_d = dgrp < gd ? (16 * g.MTS - dgrp + gd - 1) / gd : 0;
+    const int64_t ihw = (int64_t)g.IH * g.IW, ohw = (int64_t)g.OH * g.OW;
+
+    float pin[kPreIn], pd[kPreD];
     const int items = B * g.items_per_sample;
-    for (int it = sl; it < items; it += g.S) {
+    auto fetch = [&](int it) {
         const int b = it / g.items_per_sample, rb = it - b * g.items_per_sample;
         const int y0 = rb * g.R;
         const int64_t sample = (int64_t)blockIdx.z * B + b;
-        const gcf_ptr ig = as_global(in) + sample * g.in_size;
-        const gcf_ptr dg = as_global(dout) + sample * g.out_size;
+        const int sy = y0 + ity - g.pad;
+        const bool iok = ixok && (unsigned)sy < (unsigned)g.IH;
+        const gcf_ptr src = as_global(in) + sample * g.in_size + igrp * ihw + (int64_t)sy * g.IW + (itx - g.pad);
+#pragma unroll
+        for (int q = 0; q < kPreIn; ++q) pin[q] = (iok && q < nq_in) ? src[(int64_t)q * gin * ihw] : 0.f;
+        const bool dok = dxok && y0 + dr < g.OH;
+        const gcf_ptr dsrc = as_global(dout) + sample * g.out_size + dgrp * ohw + (int64_t)(y0 + dr) * g.OW + dx;
+#pragma unroll
+        for (int q = 0; q < kPreD; ++q)
+            pd[q] = (dok && q < nq_d && dgrp + gd * q < g.OC) ? dsrc[(int64_t)q * gd * ohw] : 0.f;
+    };
+
+    int it = sl;
+    if (it < items) fetch(it);
+    for (; it < items; it += g.S) {
+        __syncthreads();   // the products of the previous item are done with the tiles
+#pragma unroll
+        for (int q = 0; q < kPreIn; ++q)
+            if (q < nq_in) Ism[(igrp + gin * q) * plane + ipos] = pin[q];
+#pragma unroll
+        for (int q = 0; q < kPreD; ++q)
+            if (q < nq_d) Dsm[(dgrp + gd * q) * g.DPL + dpos] = pd[q];
         __syncthreads();
-        for (int e0 = tid; e0 < g.IC * plane; e0 += 256 * kStage) {
-            float v[kStage];
-#pragma unroll
-            for (int q = 0; q < kStage; ++q) {
-                const int e = e0 + 256 * q;
-                const int c = e / plane, rem = e - c * plane;
-                const int ty = rem / g.SWP, tx = rem - ty * g.SWP;
-                const int sy = y0 + ty - g.pad, sx = tx - g.pad;
-                v[q] = 0.f;
-                if (e < g.IC * plane && sy >= 0 && sy < g.IH && sx >= 0 && sx < g.IW)
-                    v[q] = ig[((int64_t)c * g.IH + sy) * g.IW + sx];
-            }
-#pragma unroll
-            for (int q = 0; q < kStage; ++q)
-                if (e0 + 256 * q < g.IC * plane) Ism[e0 + 256 * q] = v[q];
-        }
-        for (int e0 = tid; e0 < 16 * MT * dplane; e0 += 256 * kStage) {
-            float v[kStage];
-#pragma unroll
-            for (int q = 0; q < kStage; ++q) {
-                const int e = e0 + 256 * q;
-                const int co = e / dplane, rem = e - co * dplane;
-                const int r = rem / g.OWP, x = rem - r * g.OWP;
-                v[q] = 0.f;
-                if (e < 16 * MT * dplane && co < g.OC && y0 + r < g.OH && x < g.OW)
-                    v[q] = dg[((int64_t)co * g.OH + y0 + r) * g.OW + x];
-            }
-#pragma unroll
-            for (int q = 0; q < kStage; ++q)
-                if (e0 + 256 * q < 16 * MT * dplane) Dsm[e0 + 256 * q] = v[q];
-        }
-        __syncthreads();
+        if (it + g.S < items) fetch(it + g.S);   // in flight while the products run
         for (int r = 0; r < g.R; ++r) {
             for (int x4 = 0; x4 < g.OWP; x4 += 4) {
                 float a[MT];
 #pragma unroll
-                for (int m = 0; m < MT; ++m) a[m] = Dsm[(16 * m + li) * dplane + r * g.OWP + x4 + lg];
+                for (int m = 0; m < MT; ++m) a[m] = Dsm[(16 * (m0 + WM * m) + li) * g.DPL + r * g.OWP + x4 + lg];
                 const int po = r * g.SWP + x4;
 #pragma unroll
                 for (int j = 0; j < NTW; ++j) {
@@ -350,18 +369,19 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
             }
         }
     }
-    // partial[a][slice][co][k]: lane holds k = 16*nt + li, co = 16*m + 4*lg + r
+    // partial[a][slice][co][k]: lane holds k = 16*nt + li, co = 16*mt + 4*lg + r
     const int KP = 16 * g.NTT, OCP = 16 * g.MTT;
     const gf_ptr pg = as_global(partial) + ((int64_t)blockIdx.z * g.S + sl) * OCP * KP;
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
-        const int nt = wave + 4 * j;
+        const int nt = n0 + NS * j;
         if (nt >= g.NTT) continue;
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
-            if (m >= g.MTT) continue;
+            const int mt = m0 + WM * m;
+            if (mt >= g.MTT) continue;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) pg[(int64_t)(16 * m + 4 * lg + r) * KP + 16 * nt + li] = acc[m][j][r];
+            for (int r = 0; r < 4; ++r) pg[(int64_t)(16 * mt + 4 * lg + r) * KP + 16 * nt + li] = acc[m][j][r];
         }
     }
 }
@@ -387,6 +407,13 @@ k_conv_wgrad_finish(const RoundParams *__restrict__ rp, int u, int B, WgradGeom 
 
 constexpr int kWgradTarget = 512;  // workgroups the partial sums are spread over
 
+// accumulator tiling of the wave: WM = 2 (2 x 2 waves) when there are at most 2 N tiles
+static int wgrad_wm(const WgradGeom &g) { return g.NTT <= 2 ? 2 : 1; }
+static int wgrad_mt(const WgradGeom &g) {
+    const int n = (g.MTT + wgrad_wm(g) - 1) / wgrad_wm(g);
+    return n <= 1 ? 1 : n <= 2 ? 2 : 4;
+}
+
 static bool wgrad_geom(const LayerGeom &L, int B, int nact, WgradGeom *g) {
     const int KS = L.k;
     if (!(KS == 3 || KS == 5)) return false;
@@ -402,26 +429,31 @@ static bool wgrad_geom(const LayerGeom &L, int B, int nact, WgradGeom *g) {
     g->SWP = g->OWP + KS - 1;
     g->SWP += (g->SWP & 1) ? 0 : 1;
     g->items_per_sample = (L.oh + g->R - 1) / g->R;
-    const int items = B * g->items_per_sample;
-    int S = (kWgradTarget + nact - 1) / nact;
-    if (S > items) S = items;
-    if (S < 1) S = 1;
-    g->S = S;
+    (void)nact;
+    g->S = 1;  // set by the launcher from the number of resident workgroups
+    g->MTS = wgrad_wm(*g) * wgrad_mt(*g);
+    g->DPL = g->R * g->OWP + ((4 - (g->R * g->OWP) % 32 + 32) % 32);
     return true;
 }
 
-static int wgrad_mt(const WgradGeom &g) { return g.MTT <= 2 ? 2 : 4; }
 static int wgrad_ntw(const WgradGeom &g) {
+    if (wgrad_wm(g) == 2) return 1;
     const int n = (g.NTT + 3) / 4;
     return n <= 2 ? 2 : n <= 5 ? 5 : 10;
 }
 static size_t wgrad_lds_bytes(const WgradGeom &g) {
-    return sizeof(float) * ((size_t)(g.IC + 2) * g.rowsT * g.SWP + (size_t)16 * wgrad_mt(g) * g.R * g.OWP);
+    return sizeof(float) * ((size_t)(g.IC + 2) * g.rowsT * g.SWP + (size_t)16 * g.MTS * g.DPL);
 }
 
 bool conv_wgrad_mfma_supported(const LayerGeom &L, int B) {
     WgradGeom g;
     if (!wgrad_geom(L, B, 1, &g)) return false;
+    // a thread is tied to one tile position: both tiles must fit the 256 threads, and the
+    // channels one thread walks must fit its prefetch registers
+    const int plane = g.rowsT * g.SWP, dplane = g.R * g.OWP;
+    if (plane > 256 || dplane > 256) return false;
+    const int gin = 256 / plane, gd = 256 / dplane;
+    if ((g.IC + gin - 1) / gin > kPreIn || (16 * g.MTS + gd - 1) / gd > kPreD) return false;
     return wgrad_lds_bytes(g) <= 64 * 1024;
 }
 
@@ -433,16 +465,49 @@ size_t conv_wgrad_partial_floats(const LayerGeom &L, int B, int n_clients) {
     return (size_t)(kWgradTarget + n_clients) * 16 * g.MTT * 16 * g.NTT;
 }
 
-template <int KS>
-static void wgrad_launch(hipStream_t s, dim3 grid, size_t lds, int mt, int ntw, const RoundParams *dp, int u,
-                         int B, const WgradGeom &g, const float *in, const float *dout, float *partial) {
-#define AET_WG(MTv, NTWv)                                                                          \
-    if (mt == MTv && ntw == NTWv) {                                                                \
-        k_conv_wgrad_mfma<KS, MTv, NTWv><<<grid, 256, lds, s>>>(dp, u, B, g, in, dout, partial); \
-        return;                                                                                    \
+// resident workgroups per compute unit of one instantiation (cached); 0 = no such instantiation
+template <int KS, int MT, int NTW, int WM>
+static int wgrad_blocks_per_cu(size_t lds) {
+    static int cached = -1;
+    static size_t cached_lds = 0;
+    if (cached < 0 || cached_lds != lds) {
+        int n = 0;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_wgrad_mfma<KS, MT, NTW, WM>, 256, lds) != hipSuccess || n < 1)
+            n = 1;
+        cached = n;
+        cached_lds = lds;
     }
-    AET_WG(2, 2) AET_WG(2, 5) AET_WG(2, 10) AET_WG(4, 2) AET_WG(4, 5) AET_WG(4, 10)
+    return cached;
+}
+
+// which: 0 = resident workgroups per compute unit, 1 = launch
+template <int KS>
+static int wgrad_dispatch(int which, hipStream_t s, dim3 grid, size_t lds, int mt, int ntw, int wm,
+                          const RoundParams *dp, int u, int B, const WgradGeom &g, const float *in,
+                          const float *dout, float *partial) {
+#define AET_WG(MTv, NTWv, WMv)                                                                          \
+    if (mt == MTv && ntw == NTWv && wm == WMv) {                                                        \
+        if (which == 0) return wgrad_blocks_per_cu<KS, MTv, NTWv, WMv>(lds);                            \
+        k_conv_wgrad_mfma<KS, MTv, NTWv, WMv><<<grid, 256, lds, s>>>(dp, u, B, g, in, dout, partial); \
+        return 1;                                                                                       \
+    }
+    AET_WG(1, 1, 2) AET_WG(2, 1, 2)
+    AET_WG(1, 2, 1) AET_WG(1, 5, 1) AET_WG(1, 10, 1)
+    AET_WG(2, 2, 1) AET_WG(2, 5, 1) AET_WG(2, 10, 1)
+    AET_WG(4, 2, 1) AET_WG(4, 5, 1) AET_WG(4, 10, 1)
 #undef AET_WG
+    return 0;
+}
+
+static int device_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+    }
+    return cus;
 }
 
 hipError_t launch_conv_wgrad_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
@@ -451,11 +516,28 @@ hipError_t launch_conv_wgrad_mfma(hipStream_t s, Profiler *prof, const RoundPara
     WgradGeom g;
     if (!wgrad_geom(L, B, nact, &g)) return hipErrorInvalidValue;
     const size_t lds = wgrad_lds_bytes(g);
+    const int mt = wgrad_mt(g), ntw = wgrad_ntw(g), wm = wgrad_wm(g);
+    dim3 none(1, 1, 1);
+    const int per_cu = L.k == 3 ? wgrad_dispatch<3>(0, s, none, lds, mt, ntw, wm, dp, u, B, g, in, dout, partial)
+                                : wgrad_dispatch<5>(0, s, none, lds, mt, ntw, wm, dp, u, B, g, in, dout, partial);
+    if (per_cu < 1) return hipErrorInvalidValue;
+    // Slices per client: all workgroups of the launch resident at once (a few workgroups more
+    // than fit would cost a whole second pass), never more than the partial-sum scratch holds
+    // (kWgradTarget + n_clients slices), and the work items spread evenly.
+    const int items = B * g.items_per_sample;
+    int cap = per_cu * device_cus();
+    if (cap > kWgradTarget) cap = kWgradTarget;
+    int S = cap / nact;
+    if (S < 1) S = 1;
+    if (S > items) S = items;
+    const int per_slice = (items + S - 1) / S;
+    S = (items + per_slice - 1) / per_slice;  // the fewest slices with the same longest share
+    g.S = S;
     const bool timed = prof && prof->on[F_CONV_BWD_WEIGHT];
     if (timed) prof->before(F_CONV_BWD_WEIGHT, s);
     dim3 grid((unsigned)g.S, 1, (unsigned)nact);
-    if (L.k == 3) wgrad_launch<3>(s, grid, lds, wgrad_mt(g), wgrad_ntw(g), dp, u, B, g, in, dout, partial);
-    else wgrad_launch<5>(s, grid, lds, wgrad_mt(g), wgrad_ntw(g), dp, u, B, g, in, dout, partial);
+    if (L.k == 3) wgrad_dispatch<3>(1, s, grid, lds, mt, ntw, wm, dp, u, B, g, in, dout, partial);
+    else wgrad_dispatch<5>(1, s, grid, lds, mt, ntw, wm, dp, u, B, g, in, dout, partial);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess) {
         dim3 fgrid((unsigned)((g.KTOT + 255) / 256), (unsigned)g.OC, (unsigned)nact);
