@@ -224,6 +224,11 @@ aet_status aet_get_U(aet_ctx *ctx, int32_t client, int32_t round, float *dst, in
 /* client < 0: the global model; else the local model w_c as its last round left it. */
 aet_status aet_get_weights(aet_ctx *ctx, int32_t client, float *dst, int32_t on_host);
 
+/* Import: overwrite the global model (client < 0) or the local model w_c with P floats in
+ * the canonical layout.  src: HOST if on_host != 0 (copied before the call returns), else
+ * DEVICE (enqueued on the stream).  Counters, queue and history are left as they are. */
+aet_status aet_set_weights(aet_ctx *ctx, int32_t client, const float *src, int32_t on_host);
+
 /* Bookkeeping of local round `round` of `client` (HOST outputs):
  *   ints[6] = { s_i, recursions m_i, first sample counter q0, recursions before the round
  *               t0, start tick, arrival tick };

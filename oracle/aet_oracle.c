@@ -704,6 +704,13 @@ int orc_get_weights(orc_ctx *C, int32_t c, real *dst) {
     memcpy(dst, c < 0 ? C->Wg : C->W + (int64_t)c * C->P, sizeof(real) * C->P);
     return 0;
 }
+/* overwrite the global model (client < 0) or a client's local model: lets a test restart
+ * both sides of a comparison from the same state */
+int orc_set_weights(orc_ctx *C, int32_t c, const real *src) {
+    if (c >= C->n) return fail(C, "client out of range");
+    memcpy(c < 0 ? C->Wg : C->W + (int64_t)c * C->P, src, sizeof(real) * C->P);
+    return 0;
+}
 /* bookkeeping of round k of client c: s, m, q0, t0, start tick, arrival tick; eta, loss */
 int orc_get_round_info(orc_ctx *C, int32_t c, int32_t k, int64_t *ints6, double *dbl2) {
     if (c < 0 || c >= C->n || k < 0 || k >= C->n_rinfo[c]) return fail(C, "no such round");

@@ -102,6 +102,8 @@ def load(prec: str = "f64"):
     lib.orc_get_U.argtypes = [vp, i32, i32, vp]
     lib.orc_get_weights.restype = C.c_int
     lib.orc_get_weights.argtypes = [vp, i32, vp]
+    lib.orc_set_weights.restype = C.c_int
+    lib.orc_set_weights.argtypes = [vp, i32, vp]
     lib.orc_get_round_info.restype = C.c_int
     lib.orc_get_round_info.argtypes = [vp, i32, i32, vp, vp]
     lib.orc_get_events.restype = None
@@ -251,6 +253,11 @@ class Oracle:
         out = np.empty(self.P, dtype=self.dtype)
         self._check(self.lib.orc_get_weights(self.ctx, c, _ptr(out)))
         return out
+
+    def set_weights(self, c: int, w: np.ndarray):
+        w = np.ascontiguousarray(w, dtype=self.dtype)
+        assert w.size == self.P
+        self._check(self.lib.orc_set_weights(self.ctx, c, _ptr(w)))
 
     def round_info(self, c: int, k: int) -> dict:
         ints = np.zeros(6, dtype=np.int64)

@@ -24,6 +24,7 @@ EXPORTS = [
     "aet_last_error", "aet_destroy", "aet_reset", "aet_profile_families",
     "aet_profile_family_name", "aet_profile_enable", "aet_profile_read", "aet_run_ticks",
     "aet_topology_workspace_bytes", "aet_set_topology", "aet_receive", "aet_set_setup",
+    "aet_set_weights",
 ]
 
 
@@ -111,6 +112,8 @@ def load_library():
     lib.aet_last_error.argtypes = [vp]
     lib.aet_reset.restype = C.c_int
     lib.aet_reset.argtypes = [vp]
+    lib.aet_set_weights.restype = C.c_int
+    lib.aet_set_weights.argtypes = [vp, i32, vp, i32]
     lib.aet_set_setup.restype = C.c_int
     lib.aet_set_setup.argtypes = [vp, vp, C.c_uint64]
     lib.aet_topology_workspace_bytes.restype = C.c_size_t
@@ -267,6 +270,12 @@ class AetSgd:
         out = np.empty(self.P, dtype=np.float32)
         self._check(self.lib.aet_get_weights(self.ctx, client, _hptr(out), 1))
         return out
+
+    def aet_set_weights(self, client: int, w: np.ndarray):
+        w = np.ascontiguousarray(w, dtype=np.float32)
+        if w.size != self.P:
+            raise ValueError(f"got {w.size} values, the model has {self.P} parameters")
+        self._check(self.lib.aet_set_weights(self.ctx, client, _hptr(w), 1))
 
     def aet_get_weights_device(self, client: int = -1) -> torch.Tensor:
         out = torch.empty(self.P, dtype=torch.float32, device=self.device)

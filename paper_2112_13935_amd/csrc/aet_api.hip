@@ -675,6 +675,17 @@ aet_status aet_get_weights(aet_ctx *ctx, int32_t client, float *dst, int32_t on_
     return copy_out(ctx, client < 0 ? ctx->Wg() : ctx->Wc(client), dst, on_host);
 }
 
+aet_status aet_set_weights(aet_ctx *ctx, int32_t client, const float *src, int32_t on_host) {
+    if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
+    if (!src) return fail(ctx, AET_EINVAL, "src is NULL");
+    if (client >= ctx->n) return fail(ctx, AET_EINVAL, "client out of range");
+    float *dst = client < 0 ? ctx->Wg() : ctx->Wc(client);
+    AET_HIP(ctx, hipMemcpyAsync(dst, src, (size_t)ctx->P * 4, on_host ? hipMemcpyHostToDevice : hipMemcpyDeviceToDevice, ctx->stream));
+    if (on_host) AET_HIP(ctx, hipStreamSynchronize(ctx->stream));  // src is the caller's: done with it on return
+    return AET_OK;
+}
+
 aet_status aet_get_round_info(aet_ctx *ctx, int32_t client, int32_t round, int64_t *ints,
                               double *dbls) {
     if (!ctx) return AET_EINVAL;

@@ -19,8 +19,7 @@ enum { DENSE_FWD = 0, DENSE_BWD_DATA = 1, DENSE_BWD_WEIGHT = 2 };
 constexpr int kDT = 64;   // output tile edge
 constexpr int kDK = 32;   // contraction chunk
 
-// NTW: N tiles (of 16) per workgroup: 4 (each wave owns one N tile and all four M tiles) or
-// 1 (each wave owns one M tile): the narrow form gives more workgroups when N is small.
+// NTW: N tiles (of 16) per workgroup: 4 (each wave owns one N tile and all four M tiles).
 template <int MODE, int NTW>
 __global__ void __launch_bounds__(256)
 k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
@@ -152,21 +151,99 @@ k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int
     }
 }
 
+// Forward pass of a layer with few output tiles (small mini-batch, moderate width): one
+// workgroup per 16 x 16 output tile, its 4 waves split the contraction (wave w takes the
+// 16-wide chunks w, w+4, ...) and feed the matrix cores straight from global memory: lane
+// (li, lg) loads the four consecutive k = 16c + 4lg .. 4lg+3 of row li of both operands, and
+// product r of the chunk contracts the r-th of them (the order of k inside a chunk is free
+// as long as both operands agree).  The four partial tiles are added in wave order in LDS.
+template <bool VEC>
+__global__ void __launch_bounds__(256)
+k_dense_fwd_direct(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
+                   int64_t b_off, int relu, const float *__restrict__ x, float *__restrict__ z) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const int n0 = blockIdx.x * 16, m0 = blockIdx.y * 16;
+    const int64_t cb = (int64_t)blockIdx.z * B;
+    const bool arow = m0 + li < B, brow = n0 + li < O;
+    const gcf_ptr ap = as_global(x) + (cb + (arow ? m0 + li : 0)) * K + 4 * lg;
+    const gcf_ptr bp = as_global(p.W) + w_off + (int64_t)(brow ? n0 + li : 0) * K + 4 * lg;
+    typedef const f4 __attribute__((address_space(1))) *gv4;
+
+    auto load = [&](gcf_ptr q, bool row, int k) -> f4 {   // k = first of the lane's four
+        f4 v = {0.f, 0.f, 0.f, 0.f};
+        if (!row) return v;
+        if (VEC) {
+            if (k + 3 < K) v = *reinterpret_cast<gv4>(q);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                if (k + r < K) v[r] = q[r];
+        }
+        return v;
+    };
+
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    constexpr int UN = 4;   // chunks in flight per wave
+    const int nchunk = (K + 15) / 16;
+    for (int c0 = wave; c0 < nchunk; c0 += 4 * UN) {
+        f4 a[UN], b[UN];
+#pragma unroll
+        for (int j = 0; j < UN; ++j) {
+            const int c = c0 + 4 * j;
+            a[j] = f4{0.f, 0.f, 0.f, 0.f};
+            b[j] = a[j];
+            if (c < nchunk) {
+                a[j] = load(ap + 16 * c, arow, 16 * c + 4 * lg);
+                b[j] = load(bp + 16 * c, brow, 16 * c + 4 * lg);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < UN; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][r], b[j][r], acc, 0, 0, 0);
+    }
+    __shared__ float part[4][16][17];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) part[wave][4 * lg + r][li] = acc[r];   // (sample, feature)
+    __syncthreads();
+    {
+        const int b = tid >> 4, o = tid & 15;   // 256 threads = the 16 x 16 tile
+        if (m0 + b < B && n0 + o < O) {
+            float v = as_global(p.W)[b_off + n0 + o];
+            v += part[0][b][o];
+            v += part[1][b][o];
+            v += part[2][b][o];
+            v += part[3][b][o];
+            if (relu && !(v > 0.f)) v = 0.f;
+            as_global(z)[(cb + m0 + b) * O + n0 + o] = v;
+        }
+    }
+}
+
 hipError_t launch_dense_mfma(hipStream_t s, Profiler *prof, int mode, const RoundParams *dp, int nact,
                              int u, int B, int K, int O, int64_t w_off, int64_t b_off, int relu,
                              const float *x, const float *y, float *z, const float *mask_src) {
     const int M = mode == DENSE_BWD_WEIGHT ? O : B;
     const int N = mode == DENSE_FWD ? O : K;
-    // narrow column blocks for the forward pass when wide ones would leave most of the GPU idle
+    // forward pass: 16 x 16 tiles straight from global memory when the wide tiling would leave
+    // most of the GPU idle
     const bool narrow = mode == DENSE_FWD && (int64_t)((N + kDT - 1) / kDT) * ((M + kDT - 1) / kDT) * nact < 512;
     const int nw = narrow ? 16 : kDT;
     dim3 grid((unsigned)((N + nw - 1) / nw), (unsigned)((M + kDT - 1) / kDT), (unsigned)nact);
     const int fam = mode == DENSE_FWD ? F_DENSE_FWD : mode == DENSE_BWD_DATA ? F_DENSE_BWD_DATA : F_DENSE_BWD_WEIGHT;
     const bool timed = prof && prof->on[fam];
     if (timed) prof->before(fam, s);
-    if (mode == DENSE_FWD && narrow)
-        k_dense_mfma<DENSE_FWD, 1><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
-    else if (mode == DENSE_FWD)
+    if (mode == DENSE_FWD && narrow) {
+        dim3 dgrid((unsigned)((N + 15) / 16), (unsigned)((M + 15) / 16), (unsigned)nact);
+        // float4 loads need 16-byte aligned rows: K a multiple of 4 (all offsets are multiples
+        // of 64 floats otherwise) and the parameter offset a multiple of 4
+        if ((K & 3) == 0 && (w_off & 3) == 0)
+            k_dense_fwd_direct<true><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
+        else
+            k_dense_fwd_direct<false><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
+    } else if (mode == DENSE_FWD)
         k_dense_mfma<DENSE_FWD, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
     else if (mode == DENSE_BWD_DATA)
         k_dense_mfma<DENSE_BWD_DATA, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);

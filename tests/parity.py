@@ -25,6 +25,14 @@ shows exactly these jumps against the fp64 oracle.  For such models the tests ma
 therefore pass a twin: it runs in lock step, and the bar for tensor j of a quantity is
     max(1e-4, 3 * worst error of the twin on tensor j of that quantity over the run),
 never more than 1e-2.  Without a twin the bar is 1e-4 flat.
+
+Long runs of a convolutional ReLU network.  Such a training run is sensitive to its own
+rounding: the fp32 twin of the reduced CNN workload drifts from the fp64 oracle by 1e-2 in
+single tensors within 20 rounds, and by more than 10 % when the step size is raised so that
+the loss actually falls.  What a comparison over that horizon measures is this drift, not
+the arithmetic.  lockstep(resync=True) therefore restarts all sides from the oracle's global
+model (rounded to fp32) after every tick: every local round and every aggregation is still
+compared, over the full number of rounds, but each from a common starting point.
 """
 from __future__ import annotations
 
@@ -103,8 +111,11 @@ class Ledger:
 
 
 def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_ticks=10000,
-             check_clients=None, twin=None):
-    """Tick all sides until done; returns the worst relative errors seen."""
+             check_clients=None, twin=None, resync=False):
+    """Tick all sides until done; returns the worst relative errors seen.
+    resync: after every tick all sides take the oracle's global model (rounded to fp32), so
+    every round is compared from a common starting point and differences cannot feed on
+    themselves over the run (server form only)."""
     R = wl.rounds if rounds is None else rounds
     model = wl.model
     kinks = has_kinks(model)
@@ -156,8 +167,16 @@ def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_tick
         assert app_g == app_o, f"tick {orc.tick - 1}: aggregation order differs"
         if twin is not None:
             assert twin.exchange() == app_o
-        if check_every_tick:
+        if check_every_tick or resync:
             compare_global(f"after tick {orc.tick - 1}")
+        if resync:
+            assert not orc.p2p
+            w32 = orc.get_weights(-1).astype(np.float32)
+            orc.set_weights(-1, w32)
+            run.lib.aet_set_weights(-1, w32)
+            if twin is not None:
+                twin.set_weights(-1, w32)
+        if check_every_tick:
             if orc.p2p:   # Receive has moved the neighbours' models
                 for c in (range(orc.n) if check_clients is None else check_clients):
                     compare_client(c, f"client {c} after tick {orc.tick - 1}")
@@ -165,7 +184,8 @@ def lockstep(wl, run, orc, rounds=None, check_every_tick=True, tol=TOL, max_tick
         assert ticks <= max_ticks
     assert run.lib.aet_all_done(R)
     assert run.lib.aet_inflight() == 0
-    compare_global("end of run")
+    if not resync:
+        compare_global("end of run")
     for c in range(orc.n):
         assert run.lib.aet_history(c) == orc.history(c)
         if check_clients is None or c in check_clients:
