@@ -90,48 +90,53 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
 #pragma unroll
         for (int n = 0; n < 4; ++n) acc[m][n] = f4{0.f, 0.f, 0.f, 0.f};
 
+    // Staging without per-element index arithmetic: a thread is tied to positions of the
+    // source tile and walks the chunk's channels, and to one k = (c, ky, kx) of the weight
+    // chunk and walks the destination channels.
+    constexpr int WG_ = 256 / KCH > 0 ? 256 / KCH : 1;   // dst-channel groups staging the weights
+    const int wk = tid % KCH, wd0 = tid / KCH;           // this thread's k and first dst channel
+    const int wc = wk / (KS * KS), wr = wk - wc * (KS * KS);
+    const bool wactive = wd0 < WG_;
+    const int64_t shw = (int64_t)g.SH * g.SW;
+    // element (d, wk) of chunk c0 sits at wbase + c0 * wcstep + d * wdstep
+    const int64_t wdstep = BWD ? (int64_t)(KS * KS) : (int64_t)g.ic * (KS * KS);
+    const int64_t wcstep = BWD ? (int64_t)g.ic * (KS * KS) : (int64_t)(KS * KS);
+    const int64_t wbase = BWD ? ((int64_t)wc * g.ic + dc0) * (KS * KS) + (KS * KS - 1 - wr)
+                              : ((int64_t)dc0 * g.ic + wc) * (KS * KS) + wr;
+    const int nd = 16 * g.NT;
+
     for (int c0 = 0; c0 < g.SC; c0 += kCch) {
         __syncthreads();
-        // stage the source tile (zero outside the image and beyond the last channel)
-        // (loads are issued in batches of kStage so that their latencies overlap)
-        for (int e0 = tid; e0 < kCch * tile_plane; e0 += 256 * kStage) {
-            float v[kStage];
+        // source tile (zero outside the image and beyond the last channel); the loads of
+        // the chunk's channels are in flight together
+        for (int pos = tid; pos < tile_plane; pos += 256) {
+            const int ty = pos / g.SWP, tx = pos - ty * g.SWP;
+            const int sy = y0 + ty - g.P, sx = tx - g.P;
+            const bool ok = (unsigned)sy < (unsigned)g.SH && (unsigned)sx < (unsigned)g.SW;
+            const gcf_ptr q = sg + ((int64_t)c0 * g.SH + sy) * g.SW + sx;
+            float v[kCch];
 #pragma unroll
-            for (int q = 0; q < kStage; ++q) {
-                const int e = e0 + 256 * q;
-                const int c = e / tile_plane, rem = e - c * tile_plane;
-                const int ty = rem / g.SWP, tx = rem - ty * g.SWP;
-                const int sy = y0 + ty - g.P, sx = tx - g.P;
-                v[q] = 0.f;
-                if (e < kCch * tile_plane && c0 + c < g.SC && sy >= 0 && sy < g.SH && sx >= 0 && sx < g.SW)
-                    v[q] = sg[((int64_t)(c0 + c) * g.SH + sy) * g.SW + sx];
-            }
+            for (int c = 0; c < kCch; ++c) v[c] = (ok && c0 + c < g.SC) ? q[c * shw] : 0.f;
 #pragma unroll
-            for (int q = 0; q < kStage; ++q)
-                if (e0 + 256 * q < kCch * tile_plane) Ssm[e0 + 256 * q] = v[q];
+            for (int c = 0; c < kCch; ++c) Ssm[c * tile_plane + pos] = v[c];
         }
-        // stage the weights of this chunk: Wsm[dc][k], k = (c, ky, kx)
-        for (int e0 = tid; e0 < 16 * g.NT * KCH; e0 += 256 * kStage) {
-            float v[kStage];
+        // weights of this chunk: Wsm[d][k]; forward Wt = W[dc][sc][ky][kx], backward-data
+        // Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]
+        if (wactive) {
+            const bool cok = c0 + wc < g.SC;
+            const gcf_ptr q = wg + wbase + c0 * wcstep;
+            for (int d0 = wd0; d0 < nd; d0 += WG_ * kStage) {
+                float v[kStage];
 #pragma unroll
-            for (int q = 0; q < kStage; ++q) {
-                const int e = e0 + 256 * q;
-                const int d = e / KCH, k = e - d * KCH;
-                const int c = k / (KS * KS), r = k - c * KS * KS;
-                v[q] = 0.f;
-                if (e < 16 * g.NT * KCH && dc0 + d < g.DC && c0 + c < g.SC) {
-                    if (BWD) {
-                        // Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]
-                        v[q] = wg[((int64_t)(c0 + c) * g.ic + (dc0 + d)) * (KS * KS) + (KS * KS - 1 - r)];
-                    } else {
-                        v[q] = wg[((int64_t)(dc0 + d) * g.ic + (c0 + c)) * (KS * KS) + r];
-                    }
+                for (int j = 0; j < kStage; ++j) {
+                    const int d = d0 + WG_ * j;
+                    v[j] = (cok && d < nd && dc0 + d < g.DC) ? q[d * wdstep] : 0.f;
                 }
-            }
 #pragma unroll
-            for (int q = 0; q < kStage; ++q) {
-                const int e = e0 + 256 * q;
-                if (e < 16 * g.NT * KCH) Wsm[(e / KCH) * KCHP + (e % KCH)] = v[q];
+                for (int j = 0; j < kStage; ++j) {
+                    const int d = d0 + WG_ * j;
+                    if (d < nd) Wsm[d * KCHP + wk] = v[j];
+                }
             }
         }
         __syncthreads();
