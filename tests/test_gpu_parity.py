@@ -242,6 +242,68 @@ def test_config5_full_clients_8_rounds(gpu, oracle_libs):
     run.close()
 
 
+def _final_state_check(wl, run, orc, name, clients):
+    """Whole job through aet_run_ticks, twice (aet_reset in between, as the benchmark does),
+    against the oracle's end state: global model, sampled clients' models, histories."""
+    from parity import TOL, tensor_relerrs
+    ticks_o = orc.run_all()
+    worst = {}
+    for attempt in range(2):
+        if attempt:
+            run.lib.aet_reset()
+        assert run.run_ticks() == ticks_o
+        assert run.lib.aet_all_done(wl.rounds) and run.lib.aet_inflight() == 0
+        e = max(tensor_relerrs(wl.model, run.lib.aet_get_weights(-1), orc.get_weights(-1)))
+        worst["Wg"] = max(worst.get("Wg", 0.0), e)
+        for c in clients:
+            e = max(tensor_relerrs(wl.model, run.lib.aet_get_weights(c), orc.get_weights(c)))
+            worst["w_c"] = max(worst.get("w_c", 0.0), e)
+            assert run.lib.aet_history(c) == orc.history(c) == wl.rounds
+            for k in (0, wl.rounds - 1):
+                io, ig = orc.round_info(c, k), run.lib.aet_get_round_info(c, k)
+                for key in ("s", "m", "q0", "t0", "start_tick", "arrival"):
+                    assert ig[key] == io[key], (c, k, key)
+                worst["loss"] = max(worst.get("loss", 0.0), abs(ig["loss"] - io["loss"]) / max(abs(io["loss"]), 1e-12))
+    report(name, worst)
+    assert all(v <= TOL for v in worst.values()), worst
+
+
+def test_config2_whole_job_as_benchmarked(gpu, oracle_libs):
+    """The benchmark's workload at full size in the benchmark's launch configuration:
+    all 16 clients, all 50 rounds, one aet_run_ticks call per job."""
+    wl = W.config2()
+    run, orc = _both(gpu, wl)
+    _final_state_check(wl, run, orc, "config 2 whole job (16 clients, 50 rounds, aet_run_ticks)", range(16))
+    run.close()
+
+
+def test_config2_ring_whole_job_as_benchmarked(gpu, oracle_libs):
+    wl = W.config2()
+    wl.agg_scale = 1.0 / 3.0
+    wl.topology = W.ring_topology(wl.n_clients)
+    run, orc = _both(gpu, wl)
+    _final_state_check(wl, run, orc, "config 2 on a ring, whole job (aet_run_ticks)", range(16))
+    run.close()
+
+
+def test_set_weights_round_trip(gpu):
+    """aet_set_weights / aet_get_weights for the global model and a client's model."""
+    wl = small_cases()["mlp_ragged_stragglers"]
+    run = gpu(wl)
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal(run.lib.P).astype(np.float32)
+    b = rng.standard_normal(run.lib.P).astype(np.float32)
+    run.lib.aet_set_weights(-1, a)
+    run.lib.aet_set_weights(2, b)
+    assert np.array_equal(run.lib.aet_get_weights(-1), a)
+    assert np.array_equal(run.lib.aet_get_weights(2), b)
+    assert np.array_equal(run.lib.aet_get_weights(1), wl.w0)
+    # the next round starts from the imported global model
+    run.run_round()
+    assert not np.array_equal(run.lib.aet_get_weights(1), wl.w0)
+    run.close()
+
+
 def test_error_paths(gpu):
     """Bad arguments come back as status codes and leave the context usable."""
     from paper_2112_13935_amd import AetError

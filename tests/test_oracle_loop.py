@@ -303,3 +303,37 @@ def test_f32_twin_tracks_f64_on_a_well_conditioned_run(oracle_libs):
     a, b = o64.get_weights(-1), o32.get_weights(-1).astype(np.float64)
     assert np.abs(a - b).max() / np.abs(a).max() < 1e-5
     assert o64.events() == o32.events()
+
+
+def test_delay_checkpoint_sweep(oracle_libs):
+    """Synchronize with growing d on a schedule with slow nodes: the gate can only delay
+    starts, so the number of ticks to finish does not grow with d; a large d is the ungated
+    run; d = 0 lets nobody start round i before every other node has delivered i rounds;
+    the models never depend on anything but the schedule (same events => same result)."""
+    wl = small_mlp(n=4, rounds=5)
+    wl.compute_factor = np.array([1, 1, 2, 4], dtype=np.int32)
+    ticks = {}
+    starts = {}
+    for d in (0, 1, 2, 3, 50, -1):
+        wl.d_max = d
+        o = Oracle(wl)
+        st = {}
+        while not o.all_done():
+            t = o.tick
+            for c, k in o.run_round():
+                st[(c, k)] = t
+            o.server_aggregate()
+            assert t < 1000
+        ticks[d], starts[d] = o.tick, st
+    assert ticks[0] >= ticks[1] >= ticks[2] >= ticks[3] >= ticks[50] == ticks[-1]
+    # the gate does bite on this schedule: ungated, the fast node 0 is done after 5 ticks;
+    # the slowest node sets the end of the run either way
+    assert starts[-1][(0, 4)] == 4 and starts[0][(0, 4)] == 16 and ticks[-1] == 20
+    assert starts[50] == starts[-1]
+    # d = 0: the slowest node (factor 4) paces everybody: round i starts at tick 4 i
+    for c in range(4):
+        for k in range(5):
+            assert starts[0][(c, k)] == 4 * k
+    # every gated schedule starts each round no earlier than the ungated one
+    for d in (0, 1, 2, 3):
+        assert all(starts[d][ck] >= starts[-1][ck] for ck in starts[-1])
