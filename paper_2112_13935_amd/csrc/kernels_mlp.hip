@@ -263,25 +263,27 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         }
         // ---- prefetch the rows of the NEXT recursion into registers ----------------------
         // (Algorithm 2: "sample xi from D_c"; the indices are a counter hash, so they are
-        // known ahead of time).  Loads of one wave return in order, so the waves that poll
-        // the exchange records issue their prefetch only after the poll; the other waves
-        // have nothing to poll and issue theirs at once.
+        // known ahead of time).  Loads of one wave return in order, so nothing is issued
+        // before the exchange poll.
         f4 xpre[NI];
         int labn = 0;
+        uint32_t rowv = 0;
         const bool more = u + 1 < p.m;
-        auto prefetch = [&]() {
+        // the rows' indices and the labels now; the row loads themselves are issued a few at
+        // a time between the first tiles of the backward product, so that a wave that has to
+        // wait for room in the memory pipeline leaves the matrix core to the SIMD's other wave
+        auto prefetch_rows = [&]() {
             if (!more) return;
-            uint32_t rowv = 0;
             if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)(u + 1) * B + lane), p.n_samples);
             if (wave == 0 && lane < B) labn = yg[rowv];
-            const int subo = opaque(sub);
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                const uint32_t row = __shfl(rowv, min(i * RPI + subo, B - 1));
-                xpre[i] = f4{0.f, 0.f, 0.f, 0.f};
-                if (my_vec && i * RPI + sub < B) {
-                    if constexpr (FAST) xpre[i] = load_row_fast(row); else xpre[i] = load_row_slow(row);
-                }
+        };
+        constexpr int PFT = TPW > 4 ? 4 : TPW;   // tiles of the backward product that carry loads
+        auto prefetch_load = [&](int i) {
+            xpre[i] = f4{0.f, 0.f, 0.f, 0.f};
+            if (!more) return;
+            const uint32_t row = __shfl(rowv, min(i * RPI + opaque(sub), B - 1));
+            if (my_vec && i * RPI + sub < B) {
+                if constexpr (FAST) xpre[i] = load_row_fast(row); else xpre[i] = load_row_slow(row);
             }
         };
         // ---- logits, softmax, d logits: thread (b, o) = (tid / 16, tid % 16) ------------
@@ -352,7 +354,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         }
         __syncthreads();
         // ---- small products on the matrix cores -----------------------------------------
-        if (wave >= NBT) prefetch();
+        prefetch_rows();
         f4 dW2acc = {0.f, 0.f, 0.f, 0.f};
         if (wave < NBT) {
             // dh = (dz W2) * 1[h > 0] for samples 16*wave .. 16*wave+15
@@ -366,7 +368,6 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                 const int i = (16 * bt + 4 * lg + r) * 16 + li;
                 dhs[i] = hs[i] > 0.f ? acc[r] : 0.f;
             }
-            prefetch();
         } else if (wave == 2) {
             // dW2[o][j] = sum_b dz[b][o] h[b][j]; applied after the barrier (W2 is still read)
 #pragma unroll
@@ -434,6 +435,9 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                     W1r[tt][r] -= eb * gsum;
                     U1r[tt][r] += invB * gsum;
                 }
+                // this tile's share of the next recursion's row loads
+#pragma unroll
+                for (int i = tt * NI / PFT; i < (tt + 1) * NI / PFT && i < NI; ++i) prefetch_load(i);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
