@@ -329,8 +329,7 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
     if (e == hipSuccess) e = hipMemcpyAsync(ctx->W0(), w0, (size_t)ctx->P * 4, hipMemcpyHostToDevice, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // w0 is the caller's; do not keep reading it
     if (e == hipSuccess) e = hipMemcpyAsync(ctx->Wg(), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream);
-    for (int c = 0; c < n_clients && e == hipSuccess; ++c)
-        e = hipMemcpyAsync(ctx->Wc(c), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream);
+    if (e == hipSuccess) e = launch_broadcast_model(ctx->stream, ctx->Wc(0), ctx->Ps, n_clients, ctx->W0());
     if (e != hipSuccess) {
         const aet_status st = fail(nullptr, AET_EHIP, "aet_init: %s", hipGetErrorString(e));
         aet_destroy(ctx);
@@ -740,9 +739,7 @@ aet_status aet_reset(aet_ctx *ctx) {
     if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
     // server form: the replicas need no copy, every round starts by adopting the global model
     AET_HIP(ctx, hipMemcpyAsync(ctx->Wg(), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream));
-    if (ctx->p2p)
-        for (int c = 0; c < ctx->n; ++c)
-            AET_HIP(ctx, hipMemcpyAsync(ctx->Wc(c), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream));
+    if (ctx->p2p) AET_HIP(ctx, launch_broadcast_model(ctx->stream, ctx->Wc(0), ctx->Ps, ctx->n, ctx->W0()));
     std::fill(ctx->i_c.begin(), ctx->i_c.end(), 0);
     std::fill(ctx->t_c.begin(), ctx->t_c.end(), 0);
     std::fill(ctx->q_c.begin(), ctx->q_c.end(), 0);

@@ -98,6 +98,8 @@ hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, c
 hipError_t launch_apply_neighbour_U(hipStream_t s, Profiler *prof, float *W, int64_t Ps, int64_t P,
                                     int n_clients, const int32_t *nbr_off, const int32_t *nbr,
                                     const ArrivalPack *pack, const Arrival *darr, int n_arr);
+// every replica (Ps floats apart, Ps a multiple of 4) <- src (Ps floats readable)
+hipError_t launch_broadcast_model(hipStream_t s, float *W, int64_t Ps, int n_clients, const float *src);
 hipError_t launch_debug_indices(hipStream_t s, uint64_t key, int64_t q0, int count,
                                 uint32_t n_samples, int32_t *dst);
 // convolution on the matrix cores (kernels_conv_mfma.hip); bwd = backward-data

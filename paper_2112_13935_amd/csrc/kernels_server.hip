@@ -198,6 +198,20 @@ hipError_t launch_apply_neighbour_U(hipStream_t s, Profiler *prof, float *W, int
     return hipGetLastError();
 }
 
+// every replica <- src (Setup: all nodes start from the same model)
+__global__ void __launch_bounds__(256)
+k_broadcast_model(float *__restrict__ W, int64_t Ps, const float *__restrict__ src) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;   // float4 index
+    if (4 * i >= Ps) return;
+    reinterpret_cast<sf4 *>(W + (int64_t)blockIdx.y * Ps)[i] = reinterpret_cast<const sf4 *>(src)[i];
+}
+
+hipError_t launch_broadcast_model(hipStream_t s, float *W, int64_t Ps, int n_clients, const float *src) {
+    dim3 grid((unsigned)((Ps / 4 + 255) / 256), (unsigned)n_clients);
+    k_broadcast_model<<<grid, 256, 0, s>>>(W, Ps, src);
+    return hipGetLastError();
+}
+
 int server_reduce_chunks(int n_arr, int64_t P) {
     (void)P;
     return n_arr <= 2 * kChunk ? 1 : (n_arr + kChunk - 1) / kChunk;
