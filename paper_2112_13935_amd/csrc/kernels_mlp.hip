@@ -97,16 +97,12 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
     const int KT = (D + 15) >> 4;             // real K tiles (of 16 columns)
     constexpr int ld = 16 * kMlpWaves * TPW + 4;  // LDS row stride: all tiles + 4 floats of skew
-    constexpr int LPR = 4 * TPW;              // lanes that move one row of the wave's columns
-    constexpr int RPI = 64 / LPR;             // rows moved by one load instruction
-    constexpr int NI = (B + RPI - 1) / RPI;   // load instructions per mini-batch
+    constexpr int NI = NBT * TPW;             // float4 loads per lane and mini-batch
     // wave w steps through tiles [TPW*w, TPW*w + TPW); the first nt of them are real, the
     // rest lie in the zero-filled tail of the LDS rows and meet zero weights
     const int t0 = TPW * wave;
     const int nt = min(max(KT - t0, 0), TPW);
     const int col0 = 16 * t0;                 // first column of the wave
-    const int sub = lane / LPR, cl = lane - sub * LPR;  // row slot and float4 slot of this lane
-    const bool my_vec = sub < RPI && cl < 4 * nt;       // this lane moves float4s of real columns
 
     extern __shared__ float smem[];
     // the small arrays come first so that their addresses fit the 16-bit offset field of
@@ -129,20 +125,24 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     const int64_t b1_off = (int64_t)H * D, w2_off = b1_off + H, b2_off = w2_off + (int64_t)C * H;
     const float invB = 1.0f / (float)B;
 
-    // one row of the wave's columns: global -> registers.  `fast`: every lane's float4 is
-    // inside the row and 16-byte aligned (D a multiple of 16), so a row is one load.
-    constexpr bool fast = FAST;
-    const gcf_ptr lane_src = Xg + col0 + 4 * cl;
-    auto load_row_fast = [&](uint32_t row) -> f4 {
-        return *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(lane_src + (int64_t)row * D);
-    };
-    auto load_row_slow = [&](uint32_t row) -> f4 {
+    // The mini-batch travels global -> registers -> matrix core / LDS in the A-operand layout
+    // of the forward product: lane (li, lg) holds, for batch tile bt and K tile tt, the four
+    // values x[16*bt + li][col0 + 16*tt + 4*lg .. +3] (one 16-byte load when FAST: D a
+    // multiple of 16, so every piece is inside the row and aligned).
+    const gcf_ptr lane_src = Xg + col0 + 4 * lg;
+    auto load_piece = [&](uint32_t row, int tt) -> f4 {
         f4 x = {0.f, 0.f, 0.f, 0.f};
-        const int col = col0 + 4 * cl;
-        const gcf_ptr src = lane_src + (int64_t)row * D;
+        if (tt < nt) {
+            const gcf_ptr src = lane_src + (int64_t)row * D + 16 * tt;
+            if constexpr (FAST) {
+                x = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(src);
+            } else {
+                const int col = col0 + 16 * tt + 4 * lg;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if (col + r < D) x[r] = src[r];
+                for (int r = 0; r < 4; ++r)
+                    if (col + r < D) x[r] = src[r];
+            }
+        }
         return x;
     };
 
@@ -182,23 +182,22 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     // the tail of every LDS row (columns the model does not have) stays zero for the round
     for (int i = tid; i < B * ld; i += kMlpThreads) Xs[i] = 0.f;
     __syncthreads();
-    // rows and labels of recursion 0 go straight to LDS
+    // rows of recursion 0 into registers, labels into LDS
+    f4 xreg[NBT][TPW];
+#pragma unroll
+    for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+        for (int tt = 0; tt < TPW; ++tt) xreg[bt][tt] = f4{0.f, 0.f, 0.f, 0.f};
     if (p.m > 0) {
         uint32_t rowv = 0;
         if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + lane), p.n_samples);
         if (wave == 0 && lane < B) labs[lane] = yg[rowv];
-        f4 x0[NI];
 #pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const uint32_t row = __shfl(rowv, min(i * RPI + sub, B - 1));
-            x0[i] = f4{0.f, 0.f, 0.f, 0.f};
-            if (my_vec && i * RPI + sub < B) {
-                if constexpr (FAST) x0[i] = load_row_fast(row); else x0[i] = load_row_slow(row);
-            }
+        for (int bt = 0; bt < NBT; ++bt) {
+            const uint32_t row = __shfl(rowv, 16 * bt + li);
+#pragma unroll
+            for (int tt = 0; tt < TPW; ++tt) xreg[bt][tt] = load_piece(row, tt);
         }
-#pragma unroll
-        for (int i = 0; i < NI; ++i)
-            if (my_vec && i * RPI + sub < B) *reinterpret_cast<f4 *>(Xs + (i * RPI + sub) * ld + col0 + 4 * cl) = x0[i];
     }
     unsigned long long *rec_base = xrec + (int64_t)(rec0 + a) * 2 * kMlpMaxG * kMlpRec;
     bool dead = false;  // the poll expired: keep going, the host will see the flag
@@ -210,24 +209,21 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             f4 acc[NBT];
 #pragma unroll
             for (int bt = 0; bt < NBT; ++bt) acc[bt] = f4{0.f, 0.f, 0.f, 0.f};
-            // operands of the next tile are fetched from LDS while this tile multiplies
-            f4 xa[2][NBT];
-#pragma unroll
-            for (int bt = 0; bt < NBT; ++bt)
-                xa[0][bt] = *reinterpret_cast<const f4 *>(Xs + (16 * bt + li) * ld + col0 + 4 * lg);
+            // the A operand comes straight from the registers the rows were loaded into
 #pragma unroll
             for (int tt = 0; tt < TPW; ++tt) {
-                if (tt + 1 < TPW) {
-#pragma unroll
-                    for (int bt = 0; bt < NBT; ++bt)
-                        xa[(tt + 1) & 1][bt] = *reinterpret_cast<const f4 *>(Xs + (16 * bt + li) * ld + col0 + 16 * (tt + 1) + 4 * lg);
-                }
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
 #pragma unroll
-                    for (int bt = 0; bt < NBT; ++bt) acc[bt] = mfma16(xa[tt & 1][bt][r], W1r[tt][r], acc[bt]);
-                __builtin_amdgcn_sched_barrier(0);
+                    for (int bt = 0; bt < NBT; ++bt) acc[bt] = mfma16(xreg[bt][tt][r], W1r[tt][r], acc[bt]);
             }
+            // the backward product needs the rows transposed: park them in LDS (this wave's
+            // columns only, so no barrier; the writes drain while the logits are exchanged)
+#pragma unroll
+            for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+                for (int tt = 0; tt < TPW; ++tt)
+                    *reinterpret_cast<f4 *>(Xs + (16 * bt + li) * ld + col0 + 16 * tt + 4 * lg) = xreg[bt][tt];
 #pragma unroll
             for (int bt = 0; bt < NBT; ++bt)
 #pragma unroll
@@ -265,26 +261,25 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         // (Algorithm 2: "sample xi from D_c"; the indices are a counter hash, so they are
         // known ahead of time).  Loads of one wave return in order, so nothing is issued
         // before the exchange poll.
-        f4 xpre[NI];
         int labn = 0;
         uint32_t rowv = 0;
         const bool more = u + 1 < p.m;
         // the rows' indices and the labels now; the row loads themselves are issued a few at
         // a time between the first tiles of the backward product, so that a wave that has to
-        // wait for room in the memory pipeline leaves the matrix core to the SIMD's other wave
+        // wait for room in the memory pipeline leaves the matrix core to the SIMD's other
+        // wave.  They go into the registers the forward product has finished with.
+        uint32_t myrow[NBT];
         auto prefetch_rows = [&]() {
             if (!more) return;
             if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)(u + 1) * B + lane), p.n_samples);
             if (wave == 0 && lane < B) labn = yg[rowv];
+#pragma unroll
+            for (int bt = 0; bt < NBT; ++bt) myrow[bt] = __shfl(rowv, 16 * bt + li);
         };
         constexpr int PFT = TPW > 4 ? 4 : TPW;   // tiles of the backward product that carry loads
-        auto prefetch_load = [&](int i) {
-            xpre[i] = f4{0.f, 0.f, 0.f, 0.f};
+        auto prefetch_load = [&](int i) {        // i = tt * NBT + bt: in the order the forward product uses them
             if (!more) return;
-            const uint32_t row = __shfl(rowv, min(i * RPI + opaque(sub), B - 1));
-            if (my_vec && i * RPI + sub < B) {
-                if constexpr (FAST) xpre[i] = load_row_fast(row); else xpre[i] = load_row_slow(row);
-            }
+            xreg[i % NBT][i / NBT] = load_piece(myrow[i % NBT], i / NBT);
         };
         // ---- logits, softmax, d logits: thread (b, o) = (tid / 16, tid % 16) ------------
         // Every thread with o < C fetches its own logit: the G tagged words of element
@@ -441,16 +436,8 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        // ---- the prefetched rows replace this wave's columns ----------------------------
-        if (more) {
-            int dst = opaque(sub * ld + col0 + 4 * cl);
-#pragma unroll
-            for (int i = 0; i < NI; ++i) {
-                if (my_vec && i * RPI + sub < B) *reinterpret_cast<f4 *>(Xs + dst) = xpre[i];
-                dst = opaque(dst + RPI * ld);
-            }
-            if (wave == 0 && lane < B) labs[lane] = labn;
-        }
+        // ---- the next recursion's labels ----------------------------------------------------
+        if (more && wave == 0 && lane < B) labs[lane] = labn;
     }
 
     // ---- end of round: the replica and the message payload go to HBM ---------------------
