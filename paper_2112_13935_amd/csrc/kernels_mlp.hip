@@ -8,12 +8,13 @@
 // mini-batch rows plus one small exchange.
 //
 // Per recursion:
-//   - each of the 8 waves owns a contiguous eighth of the input columns: it has
-//     prefetched its part of the B sampled rows into registers during the previous
-//     recursion and now drops them into LDS (no workgroup barrier: nobody else touches
-//     those columns);
-//   - z1 = X W1^T on the matrix cores (fp32 MFMA 16x16x4), partial over the wave's columns,
-//     summed over the waves through LDS; h = relu(z1 + b1);
+//   - each of the 8 waves owns a contiguous eighth of the input columns: it has loaded its
+//     part of the B sampled rows into registers during the previous recursion, in the
+//     A-operand layout of the forward product;
+//   - z1 = X W1^T on the matrix cores (fp32 MFMA 16x16x4) straight from those registers,
+//     partial over the wave's columns, summed over the waves through LDS; h = relu(z1 + b1);
+//     the rows are then parked in LDS for the backward product (no workgroup barrier:
+//     nobody else touches those columns);
 //   - the partial logits of the 16 own units are written to the client's exchange record
 //     as 64-bit {step tag, value} words; every workgroup polls the G records until all
 //     tags show the current step, which gives the logits without a separate barrier or
