@@ -30,7 +30,7 @@ __device__ __forceinline__ f4 mfma16x16x4(float a, float b, f4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
-constexpr int kCch = 8;    // source channels per K chunk
+constexpr int kCch = 8;    // source channels per K chunk, at most (layers with fewer use 1, 2 or 4)
 constexpr int kStage = 8;  // global loads in flight per thread while a tile is staged
 
 struct ConvDir {
@@ -40,6 +40,7 @@ struct ConvDir {
     int R;               // dst rows per workgroup
     int MPR;             // M tiles (16 columns) per dst row
     int NT;              // N tiles (16 dst channels) per workgroup
+    int CCH;             // source channels per K chunk: 1, 2, 4 or 8
     int rowsT, SWP;      // rows and padded width of the staged source tile
     int64_t src_size, dst_size;  // floats per sample
     int64_t w_off, b_off;
@@ -47,14 +48,17 @@ struct ConvDir {
     int relu;
 };
 
-template <int KS, bool BWD>
+// CCH: source channels per K chunk (1, 2, 4 or 8: the smallest that holds the layer's source
+// channels, so that a 1- or 3-channel input does not multiply seven or five channels of zeros)
+template <int KS, bool BWD, int CCH>
 __global__ void __launch_bounds__(256)
 k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const float *__restrict__ src,
             float *__restrict__ dst, const float *__restrict__ mask_src) {
     const RoundParams p = rp[blockIdx.z];
     if (u >= p.m) return;
-    constexpr int KCH = kCch * KS * KS;  // K elements per chunk
-    constexpr int KCHP = KCH + 4;        // padded weight row in LDS
+    constexpr int KCHR = CCH * KS * KS;      // K elements per chunk
+    constexpr int KCH = (KCHR + 3) / 4 * 4;  // ... rounded up to whole contraction steps (zero weights)
+    constexpr int KCHP = KCH + 4;            // padded weight row in LDS
     constexpr int STEPS = KCH / 4;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
     const int nblk = blockIdx.x % ((g.DC + 16 * g.NT - 1) / (16 * g.NT));
@@ -67,13 +71,13 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
 
     extern __shared__ float smem[];
     const int tile_plane = g.rowsT * g.SWP;
-    float *Ssm = smem;                          // [kCch][rowsT][SWP]
-    float *Wsm = Ssm + kCch * tile_plane;       // [16*NT][KCHP]
+    float *Ssm = smem;                          // [CCH][rowsT][SWP]
+    float *Wsm = Ssm + CCH * tile_plane;        // [16*NT][KCHP]
     int *koff = reinterpret_cast<int *>(Wsm + 16 * g.NT * KCHP);  // [KCH]
 
     for (int k = tid; k < KCH; k += 256) {
         const int c = k / (KS * KS), r = k - c * KS * KS;
-        koff[k] = c * tile_plane + (r / KS) * g.SWP + (r % KS);
+        koff[k] = k < KCHR ? c * tile_plane + (r / KS) * g.SWP + (r % KS) : 0;  // padding: weight 0
     }
 
     // the wave's two M tiles: (row, column chunk) inside the workgroup's block
@@ -97,6 +101,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     const int wk = tid % KCH, wd0 = tid / KCH;           // this thread's k and first dst channel
     const int wc = wk / (KS * KS), wr = wk - wc * (KS * KS);
     const bool wactive = wd0 < WG_;
+    const bool wreal = wk < KCHR;                        // not one of the padding columns
     const int64_t shw = (int64_t)g.SH * g.SW;
     // element (d, wk) of chunk c0 sits at wbase + c0 * wcstep + d * wdstep
     const int64_t wdstep = BWD ? (int64_t)(KS * KS) : (int64_t)g.ic * (KS * KS);
@@ -105,7 +110,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
                               : ((int64_t)dc0 * g.ic + wc) * (KS * KS) + wr;
     const int nd = 16 * g.NT;
 
-    for (int c0 = 0; c0 < g.SC; c0 += kCch) {
+    for (int c0 = 0; c0 < g.SC; c0 += CCH) {
         __syncthreads();
         // source tile (zero outside the image and beyond the last channel); the loads of
         // the chunk's channels are in flight together
@@ -114,16 +119,16 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
             const int sy = y0 + ty - g.P, sx = tx - g.P;
             const bool ok = (unsigned)sy < (unsigned)g.SH && (unsigned)sx < (unsigned)g.SW;
             const gcf_ptr q = sg + ((int64_t)c0 * g.SH + sy) * g.SW + sx;
-            float v[kCch];
+            float v[CCH];
 #pragma unroll
-            for (int c = 0; c < kCch; ++c) v[c] = (ok && c0 + c < g.SC) ? q[c * shw] : 0.f;
+            for (int c = 0; c < CCH; ++c) v[c] = (ok && c0 + c < g.SC) ? q[c * shw] : 0.f;
 #pragma unroll
-            for (int c = 0; c < kCch; ++c) Ssm[c * tile_plane + pos] = v[c];
+            for (int c = 0; c < CCH; ++c) Ssm[c * tile_plane + pos] = v[c];
         }
         // weights of this chunk: Wsm[d][k]; forward Wt = W[dc][sc][ky][kx], backward-data
         // Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]
         if (wactive) {
-            const bool cok = c0 + wc < g.SC;
+            const bool cok = wreal && c0 + wc < g.SC;
             const gcf_ptr q = wg + wbase + c0 * wcstep;
             for (int d0 = wd0; d0 < nd; d0 += WG_ * kStage) {
                 float v[kStage];
@@ -208,6 +213,7 @@ static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d) {
     // the 4 waves own 8 M tiles; with MPR in {3, 5, 6, 7} some tiles stay unused
     d->NT = (d->DC + 15) / 16;
     if (d->NT > 4) d->NT = 4;
+    d->CCH = d->SC <= 1 ? 1 : d->SC <= 2 ? 2 : d->SC <= 4 ? 4 : kCch;
     d->rowsT = d->R + KS - 1;
     d->SWP = 16 * d->MPR + KS - 1;
     d->SWP += (d->SWP & 1) ? 0 : 1;  // odd row stride: fewer LDS bank conflicts
@@ -215,8 +221,8 @@ static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d) {
 }
 
 static size_t conv_lds_bytes(const ConvDir &d, int KS) {
-    const int KCH = kCch * KS * KS;
-    return sizeof(float) * ((size_t)kCch * d.rowsT * d.SWP + (size_t)16 * d.NT * (KCH + 4)) + sizeof(int) * KCH;
+    const int KCH = (d.CCH * KS * KS + 3) / 4 * 4;
+    return sizeof(float) * ((size_t)d.CCH * d.rowsT * d.SWP + (size_t)16 * d.NT * (KCH + 4)) + sizeof(int) * KCH;
 }
 
 bool conv_mfma_supported(const LayerGeom &L, bool bwd) {
@@ -237,13 +243,14 @@ hipError_t launch_conv_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp
     const int fam = bwd ? F_CONV_BWD_DATA : F_CONV_FWD;
     const bool timed = prof && prof->on[fam];
     if (timed) prof->before(fam, s);
-    if (L.k == 3) {
-        if (bwd) k_conv_mfma<3, true><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);
-        else k_conv_mfma<3, false><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);
-    } else {
-        if (bwd) k_conv_mfma<5, true><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);
-        else k_conv_mfma<5, false><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);
+#define AET_CONV(KSv, CCHv)                                                                        \
+    if (L.k == KSv && d.CCH == CCHv) {                                                            \
+        if (bwd) k_conv_mfma<KSv, true, CCHv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);  \
+        else k_conv_mfma<KSv, false, CCHv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);     \
     }
+    AET_CONV(3, 1) AET_CONV(3, 2) AET_CONV(3, 4) AET_CONV(3, 8)
+    AET_CONV(5, 1) AET_CONV(5, 2) AET_CONV(5, 4) AET_CONV(5, 8)
+#undef AET_CONV
     if (timed) prof->after(fam, s);
     return hipGetLastError();
 }
