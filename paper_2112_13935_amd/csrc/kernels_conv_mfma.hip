@@ -417,7 +417,13 @@ k_conv_wgrad_finish(const RoundParams *__restrict__ rp, int u, int B, WgradGeom 
     as_global(p.U)[wi] += s;
 }
 
-constexpr int kWgradTarget = 512;  // workgroups the partial sums are spread over
+// Workgroups the partial sums of one launch are spread over, at most: layers with a small
+// gradient (partial result up to 16 KB) can afford many short slices, which hides the
+// latency of their short work items; large ones pay for every slice with a partial result.
+static int wgrad_target(const LayerGeom &L) {
+    const int64_t floats = (int64_t)((L.oc + 15) / 16 * 16) * ((L.ic * L.k * L.k + 1 + 15) / 16 * 16);
+    return floats <= 4096 ? 2048 : 512;
+}
 
 // accumulator tiling of the wave: WM = 2 (2 x 2 waves) when there are at most 2 N tiles
 static int wgrad_wm(const WgradGeom &g) { return g.NTT <= 2 ? 2 : 1; }
@@ -473,8 +479,8 @@ bool conv_wgrad_mfma_supported(const LayerGeom &L, int B) {
 size_t conv_wgrad_partial_floats(const LayerGeom &L, int B, int n_clients) {
     WgradGeom g;
     if (!wgrad_geom(L, B, 1, &g)) return 0;
-    // nact * S <= kWgradTarget + nact
-    return (size_t)(kWgradTarget + n_clients) * 16 * g.MTT * 16 * g.NTT;
+    // nact * S <= wgrad_target + nact
+    return (size_t)(wgrad_target(L) + n_clients) * 16 * g.MTT * 16 * g.NTT;
 }
 
 // resident workgroups per compute unit of one instantiation (cached); 0 = no such instantiation
@@ -535,10 +541,10 @@ hipError_t launch_conv_wgrad_mfma(hipStream_t s, Profiler *prof, const RoundPara
     if (per_cu < 1) return hipErrorInvalidValue;
     // Slices per client: all workgroups of the launch resident at once (a few workgroups more
     // than fit would cost a whole second pass), never more than the partial-sum scratch holds
-    // (kWgradTarget + n_clients slices), and the work items spread evenly.
+    // (wgrad_target + n_clients slices), and the work items spread evenly.
     const int items = B * g.items_per_sample;
     int cap = per_cu * device_cus();
-    if (cap > kWgradTarget) cap = kWgradTarget;
+    if (cap > wgrad_target(L)) cap = wgrad_target(L);
     int S = cap / nact;
     if (S < 1) S = 1;
     if (S > items) S = items;
