@@ -26,7 +26,7 @@
  *     eta0 / (1 + beta * t^power), constant inside a round             : Section 3.1, Experiments
  *                                                                        ("Objective function"), Table 5
  *
- * Readings taken where the paper is silent (all listed in the design notes):
+ * Readings taken where the paper is silent:
  * thresholds are per client and count samples; a mini-batch step uses the mean of the
  * per-sample gradients; sampling is i.i.d. with replacement from a counter hash
  * (SplitMix64, Steele/Lea/Flood 2014); clients adopt the global model only at the start

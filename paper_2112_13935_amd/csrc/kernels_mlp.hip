@@ -100,7 +100,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     constexpr int ld = 16 * kMlpWaves * TPW + 4;  // LDS row stride: all tiles + 4 floats of skew
     constexpr int NI = NBT * TPW;             // float4 loads per lane and mini-batch
     // wave w steps through tiles [TPW*w, TPW*w + TPW); the first nt of them are real, the
-    // rest lie in the zero-filled tail of the LDS rows and meet zero weights
+    // rest are loaded as zeros and meet zero weights
     const int t0 = TPW * wave;
     const int nt = min(max(KT - t0, 0), TPW);
     const int col0 = 16 * t0;                 // first column of the wave
@@ -155,11 +155,13 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     for (int tt = 0; tt < TPW; ++tt) {
         f4 w = {0.f, 0.f, 0.f, 0.f};
         if (tt < nt) {
-            const float *src = Wg + (int64_t)(16 * g + li) * D;
+            const float *src = Wg + (int64_t)(16 * g + li) * D + 16 * (t0 + tt) + 4 * lg;
+            if constexpr (FAST) {   // D a multiple of 16: the four values are one aligned piece
+                w = *reinterpret_cast<const f4 *>(src);
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int k = 16 * (t0 + tt) + 4 * lg + r;
-                if (k < D) w[r] = src[k];
+                for (int r = 0; r < 4; ++r)
+                    if (16 * (t0 + tt) + 4 * lg + r < D) w[r] = src[r];
             }
         }
         W1r[tt] = w;
@@ -180,8 +182,6 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             lossacc[tid] = 0.f;
         }
     }
-    // the tail of every LDS row (columns the model does not have) stays zero for the round
-    for (int i = tid; i < B * ld; i += kMlpThreads) Xs[i] = 0.f;
     __syncthreads();
     // rows of recursion 0 into registers, labels into LDS
     f4 xreg[NBT][TPW];
@@ -445,14 +445,17 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
 #pragma unroll
     for (int tt = 0; tt < TPW; ++tt) {
         if (tt < nt) {
-            const int64_t base = (int64_t)(16 * g + li) * D;
+            const int64_t base = (int64_t)(16 * g + li) * D + 16 * (t0 + tt) + 4 * lg;
+            if constexpr (FAST) {
+                *reinterpret_cast<f4 __attribute__((address_space(1))) *>(Wc + base) = W1r[tt];
+                *reinterpret_cast<f4 __attribute__((address_space(1))) *>(Uc + base) = U1r[tt];
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int k = 16 * (t0 + tt) + 4 * lg + r;
-                if (k < D) {
-                    Wc[base + k] = W1r[tt][r];
-                    Uc[base + k] = U1r[tt][r];
-                }
+                for (int r = 0; r < 4; ++r)
+                    if (16 * (t0 + tt) + 4 * lg + r < D) {
+                        Wc[base + r] = W1r[tt][r];
+                        Uc[base + r] = U1r[tt][r];
+                    }
             }
         }
     }
