@@ -95,7 +95,10 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     const gci_ptr yg = as_global(p.y);
     const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    // the wave index as a scalar, so that everything derived from it (tile counts, column
+    // offsets, branches on them) stays in scalar registers and scalar branches
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int KT = (D + 15) >> 4;             // real K tiles (of 16 columns)
     constexpr int ld = 16 * kMlpWaves * TPW + 4;  // LDS row stride: all tiles + 4 floats of skew
     constexpr int NI = NBT * TPW;             // float4 loads per lane and mini-batch
@@ -131,10 +134,11 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     // values x[16*bt + li][col0 + 16*tt + 4*lg .. +3] (one 16-byte load when FAST: D a
     // multiple of 16, so every piece is inside the row and aligned).
     const gcf_ptr lane_src = Xg + col0 + 4 * lg;
-    auto load_piece = [&](uint32_t row, int tt) -> f4 {
+    // rowp: the lane's piece of tile 0 of its row, lane_src + row * D
+    auto load_piece = [&](gcf_ptr rowp, int tt) -> f4 {
         f4 x = {0.f, 0.f, 0.f, 0.f};
         if (tt < nt) {
-            const gcf_ptr src = lane_src + (int64_t)row * D + 16 * tt;
+            const gcf_ptr src = rowp + 16 * tt;
             if constexpr (FAST) {
                 x = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(src);
             } else {
@@ -195,9 +199,9 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         if (wave == 0 && lane < B) labs[lane] = yg[rowv];
 #pragma unroll
         for (int bt = 0; bt < NBT; ++bt) {
-            const uint32_t row = __shfl(rowv, 16 * bt + li);
+            const gcf_ptr rowp = lane_src + (int64_t)__shfl(rowv, 16 * bt + li) * D;
 #pragma unroll
-            for (int tt = 0; tt < TPW; ++tt) xreg[bt][tt] = load_piece(row, tt);
+            for (int tt = 0; tt < TPW; ++tt) xreg[bt][tt] = load_piece(rowp, tt);
         }
     }
     unsigned long long *rec_base = xrec + (int64_t)(rec0 + a) * 2 * kMlpMaxG * kMlpRec;
@@ -269,13 +273,13 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         // a time between the first tiles of the backward product, so that a wave that has to
         // wait for room in the memory pipeline leaves the matrix core to the SIMD's other
         // wave.  They go into the registers the forward product has finished with.
-        uint32_t myrow[NBT];
+        gcf_ptr myrow[NBT];
         auto prefetch_rows = [&]() {
             if (!more) return;
             if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)(u + 1) * B + lane), p.n_samples);
             if (wave == 0 && lane < B) labn = yg[rowv];
 #pragma unroll
-            for (int bt = 0; bt < NBT; ++bt) myrow[bt] = __shfl(rowv, 16 * bt + li);
+            for (int bt = 0; bt < NBT; ++bt) myrow[bt] = lane_src + (int64_t)__shfl(rowv, 16 * bt + li) * D;
         };
         constexpr int PFT = TPW > 4 ? 4 : TPW;   // tiles of the backward product that carry loads
         auto prefetch_load = [&](int i) {        // i = tt * NBT + bt: in the order the forward product uses them
@@ -424,10 +428,11 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                     acc0 = mfma16(xb[tt & 1][s], dhb[s], acc0);
                     acc1 = mfma16(xb[tt & 1][s + 1], dhb[s + 1], acc1);
                 }
-                const bool real = tt < nt;  // pad tiles keep their zero weights
+                // (pad tiles: their rows are zeros, so the product is zero and the zero
+                // weights stay zero)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
-                    const float gsum = real ? acc0[r] + acc1[r] : 0.f;
+                    const float gsum = acc0[r] + acc1[r];
                     W1r[tt][r] -= eb * gsum;
                     U1r[tt][r] += invB * gsum;
                 }
