@@ -53,6 +53,42 @@ __device__ __forceinline__ void wave_sum_dpp_many(float (&v)[N]) {
 }
 #undef AET_DPP_ADD
 
+// Sums of N values over the 64 lanes of a wave, several values per instruction.  The lane
+// swaps of gfx950 exchange half-waves (rows of 16 lanes) between two registers, so that one
+// addition folds two (then four) different values at once:
+//   swap32(a, b) -> [a.lo, b.lo], [a.hi, b.hi]; their sum holds a folded to 32 lanes in the
+//                   lower half and b in the upper half;
+//   swap16(p, q) -> rows [p0, q0, p2, q2], [p1, q1, p3, q3]; their sum holds four values, one
+//                   per row of 16 lanes;
+// four shuffle-and-add stages inside the rows finish.  Register k of the result holds, in all
+// 16 lanes of row r, the total of value 4k + rowmap(r), rowmap = {0, 2, 1, 3}.
+template <int N>
+__device__ __forceinline__ void wave_sum_rows(const float (&v)[N], float (&out)[(N + 3) / 4]) {
+    static_assert(N % 2 == 0, "values come in pairs");
+    constexpr int NP = N / 2, NQ = (N + 3) / 4;
+    float p[NP];
+#pragma unroll
+    for (int k = 0; k < NP; ++k) {
+        const auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(int, v[2 * k]),
+                                                        __builtin_bit_cast(int, v[2 * k + 1]), false, false);
+        p[k] = __builtin_bit_cast(float, (int)r[0]) + __builtin_bit_cast(float, (int)r[1]);
+    }
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) {
+        const float a = p[2 * k], b = 2 * k + 1 < NP ? p[2 * k + 1] : 0.f;
+        const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(int, a), __builtin_bit_cast(int, b), false, false);
+        out[k] = __builtin_bit_cast(float, (int)r[0]) + __builtin_bit_cast(float, (int)r[1]);
+    }
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) out[k] += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, out[k]), 0xB1, 0xF, 0xF, true));
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) out[k] += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, out[k]), 0x4E, 0xF, 0xF, true));
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) out[k] += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, out[k]), 0x141, 0xF, 0xF, true));
+#pragma unroll
+    for (int k = 0; k < NQ; ++k) out[k] += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, out[k]), 0x140, 0xF, 0xF, true));
+}
+
 // sum / max over each row of 16 lanes (every lane of the row gets the result)
 __device__ __forceinline__ float row_sum_dpp(float v) {
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
@@ -119,12 +155,15 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
 #pragma unroll
             for (int j = 0; j < NC; ++j) s[o] += W[o][j] * x[j];
         }
-        // the C wave reductions advance stage by stage, so that consecutive DPP operations
-        // are independent of each other
-        wave_sum_dpp_many<C>(s);
-        if (lane == 63) {
+        // the C sums over the wave, four classes per register at the end; the first lane of
+        // every row posts its classes
+        float t[(C + 3) / 4];
+        wave_sum_rows<C>(s, t);
+        if (cls == 0) {
+            const int row = lane >> 4, o0 = ((row & 1) << 1) | (row >> 1);
 #pragma unroll
-            for (int o = 0; o < C; ++o) zp[wave][o] = s[o];
+            for (int k = 0; k < (C + 3) / 4; ++k)
+                if (4 * k + o0 < C) zp[wave][4 * k + o0] = t[k];
         }
         __syncthreads();
         // lane cls of every row: logit of class cls, then the softmax inside the row
