@@ -87,6 +87,18 @@ def small_cases():
     wl = W.config2(n_clients=3, n_total=3 * 200, d=784, hidden=128, batch=32, rounds=3, a=32, b=32)
     wl.compute_factor = np.array([1, 2, 1], dtype=np.int32)
     cases["mlp_fused_full_width"] = wl
+    # the limits of the fused kernels: widest input and most unit groups of the
+    # dense-ReLU-dense kernel (896 columns, 256 hidden units = 16 workgroups per client) ...
+    wl = W.config2(n_clients=2, n_total=2 * 120, d=896, hidden=256, batch=16, rounds=3, a=16, b=16)
+    cases["mlp_fused_widest"] = wl
+    # ... and of the softmax-regression kernel: 6 columns per thread with a ragged tail,
+    # exactly 2 columns per thread, one column more than 1 per thread
+    wl = W.config1(n_clients=3, n_per=40, d=3000, rounds=3, a=2, b=2)
+    cases["softmax_3000_columns"] = wl
+    wl = W.config1(n_clients=2, n_per=40, d=1024, rounds=3, a=2, b=2)
+    cases["softmax_1024_columns"] = wl
+    wl = W.config1(n_clients=2, n_per=40, d=513, rounds=3, a=2, b=2)
+    cases["softmax_513_columns"] = wl
     return cases
 
 
