@@ -54,17 +54,27 @@ __device__ __forceinline__ int opaque(int x) {
 __device__ __forceinline__ f4 mfma16(float a, float b, f4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
-// sum / max over the 16 lanes of one sample (lanes 16k .. 16k+15 of the wave)
+// sum / max over the 16 lanes of one sample (lanes 16k .. 16k+15 of the wave), with the
+// data-parallel-primitive lane permutations inside a row: neighbours in a quad, the other
+// pair of the quad, the mirrored half row, the mirrored row
+#define AET_ROW_STEP(op, v, ctrl) \
+    v = op(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, 0xF, 0xF, true)))
+__device__ __forceinline__ float row16_add(float a, float b) { return a + b; }
 __device__ __forceinline__ float row16_sum(float v) {
-#pragma unroll
-    for (int off = 8; off > 0; off >>= 1) v += __shfl_xor(v, off, 16);
+    AET_ROW_STEP(row16_add, v, 0xB1);
+    AET_ROW_STEP(row16_add, v, 0x4E);
+    AET_ROW_STEP(row16_add, v, 0x141);
+    AET_ROW_STEP(row16_add, v, 0x140);
     return v;
 }
 __device__ __forceinline__ float row16_max(float v) {
-#pragma unroll
-    for (int off = 8; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 16));
+    AET_ROW_STEP(fmaxf, v, 0xB1);
+    AET_ROW_STEP(fmaxf, v, 0x4E);
+    AET_ROW_STEP(fmaxf, v, 0x141);
+    AET_ROW_STEP(fmaxf, v, 0x140);
     return v;
 }
+#undef AET_ROW_STEP
 
 // FAST: D is a multiple of 16, so every row piece is one aligned 16-byte load.
 // NBT: batch tiles of 16 samples; TPW: K tiles every wave steps through (waves that own
