@@ -76,6 +76,24 @@ __device__ __forceinline__ float row16_max(float v) {
 }
 #undef AET_ROW_STEP
 
+// sum over the 64 lanes, every lane gets it (gfx950 lane swaps: halves, then rows, then the
+// in-row steps)
+__device__ __forceinline__ float fold_rows(float v) {   // sum of the 4 rows, lane by lane
+    const auto a = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v), false, false);
+    v = __builtin_bit_cast(float, (int)a[0]) + __builtin_bit_cast(float, (int)a[1]);
+    const auto b = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(int, v), __builtin_bit_cast(int, v), false, false);
+    return __builtin_bit_cast(float, (int)b[0]) + __builtin_bit_cast(float, (int)b[1]);
+}
+// column sums of a [B][16] LDS array: lane (c = lane % 16, q = lane / 16) adds the rows
+// q, q + 4, ... of column c, then the four row groups are folded
+template <int B>
+__device__ __forceinline__ float col_sum16(const float *a, int lane) {
+    float s = 0.f;
+#pragma unroll
+    for (int b = lane >> 4; b < B; b += 4) s += a[b * 16 + (lane & 15)];
+    return fold_rows(s);
+}
+
 // FAST: D is a multiple of 16, so every row piece is one aligned 16-byte load.
 // NBT: batch tiles of 16 samples; TPW: K tiles every wave steps through (waves that own
 // fewer real tiles run the remaining ones as no-ops on zero weights, so that the tile loops
@@ -87,7 +105,8 @@ struct MlpPack {
     RoundParams p[kMlpPack];
 };
 
-template <int NBT, int TPW, bool FAST>
+// FULL: every wave owns TPW real tiles (D = 16 * 8 * TPW): no pad tiles, loads unguarded.
+template <int NBT, int TPW, bool FAST, bool FULL>
 __global__ void __launch_bounds__(kMlpThreads, 1)
 k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             int D, int H, int C, int G, unsigned long long *__restrict__ xrec, uint32_t tag0,
@@ -147,7 +166,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     // rowp: the lane's piece of tile 0 of its row, lane_src + row * D
     auto load_piece = [&](gcf_ptr rowp, int tt) -> f4 {
         f4 x = {0.f, 0.f, 0.f, 0.f};
-        if (tt < nt) {
+        if (FULL || tt < nt) {
             const gcf_ptr src = rowp + 16 * tt;
             if constexpr (FAST) {
                 x = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(src);
@@ -331,17 +350,29 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                 for (;;) {
                     bool ok = true;
                     z = b2s[o];
-                    for (int g0 = 0; g0 < G; g0 += GC) {
+                    if (G == GC) {   // the common cluster size: one unguarded batch
                         unsigned long long v[GC];
 #pragma unroll
                         for (int gg = 0; gg < GC; ++gg)
-                            if (g0 + gg < G) v[gg] = __hip_atomic_load(src + (g0 + gg) * kMlpRec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            v[gg] = __hip_atomic_load(src + gg * kMlpRec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
-                        for (int gg = 0; gg < GC; ++gg)
-                            if (g0 + gg < G) {
-                                ok = ok && (uint32_t)(v[gg] >> 32) == tag;
-                                z += __uint_as_float((uint32_t)v[gg]);
-                            }
+                        for (int gg = 0; gg < GC; ++gg) {
+                            ok = ok && (uint32_t)(v[gg] >> 32) == tag;
+                            z += __uint_as_float((uint32_t)v[gg]);
+                        }
+                    } else {
+                        for (int g0 = 0; g0 < G; g0 += GC) {
+                            unsigned long long v[GC];
+#pragma unroll
+                            for (int gg = 0; gg < GC; ++gg)
+                                if (g0 + gg < G) v[gg] = __hip_atomic_load(src + (g0 + gg) * kMlpRec, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                            for (int gg = 0; gg < GC; ++gg)
+                                if (g0 + gg < G) {
+                                    ok = ok && (uint32_t)(v[gg] >> 32) == tag;
+                                    z += __uint_as_float((uint32_t)v[gg]);
+                                }
+                        }
                     }
                     if (ok || dead) break;
                     __builtin_amdgcn_s_sleep(2);
@@ -355,11 +386,11 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             }
             if (b < B) {
                 const float zmax = row16_max(o < C ? z : -3.0e38f);
-                const float ex = o < C ? expf(z - zmax) : 0.f;
-                const float lse = zmax + logf(row16_sum(ex));
+                const float ex = o < C ? __expf(z - zmax) : 0.f;
+                const float lse = zmax + __logf(row16_sum(ex));
                 const int lab = labs[b];
                 if (o == lab) lossb[b] = lse - z;
-                zs[b * 16 + o] = o < C ? expf(z - lse) - (o == lab ? 1.f : 0.f) : 0.f;
+                zs[b * 16 + o] = o < C ? __expf(z - lse) - (o == lab ? 1.f : 0.f) : 0.f;
             }
         }
         __syncthreads();
@@ -384,17 +415,16 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             for (int s = 0; s < 4 * NBT; ++s)
                 dW2acc = mfma16(zs[(4 * s + lg) * 16 + li], hs[(4 * s + lg) * 16 + li], dW2acc);
         } else if (wave == 3) {
+            // second-layer bias: column sums of dz
+            const float s = col_sum16<B>(zs, lane) * invB;
             if (lane < C) {
-                float s = 0.f;
-                for (int b = 0; b < B; ++b) s += zs[b * 16 + lane];
-                s *= invB;
                 b2s[lane] -= p.eta * s;
                 Ub2s[lane] += s;
-            } else if (lane == 32) {
-                float s = 0.f;
-                for (int b = 0; b < B; ++b) s += lossb[b];
-                lossacc[0] += s * invB;
             }
+        } else if (wave == 4) {
+            // the recursion's mean loss
+            const float s = row16_sum(fold_rows(lane < B ? lossb[lane] : 0.f));
+            if (lane == 0) lossacc[0] += s * invB;
         }
         __syncthreads();
         // ---- second layer and first-layer bias: w <- w - eta g, U <- U + g ---------------
@@ -406,12 +436,13 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                 W2s[i] -= p.eta * gv;
                 U2s[i] += gv;
             }
-        } else if (wave == 3 && lane < 16) {
-            float s = 0.f;
-            for (int b = 0; b < B; ++b) s += dhs[b * 16 + lane];
-            s *= invB;
-            b1s[lane] -= p.eta * s;
-            Ub1s[lane] += s;
+        } else if (wave == 3) {
+            // first-layer bias: column sums of dh
+            const float s = col_sum16<B>(dhs, lane) * invB;
+            if (lane < 16) {
+                b1s[lane] -= p.eta * s;
+                Ub1s[lane] += s;
+            }
         }
         // ---- first layer: dW1^T = X^T dh on the matrix cores, update in registers -------
         {
@@ -490,8 +521,8 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             }
         }
     }
-    // the loss was accumulated by wave 3, lane 32 of unit group 0
-    if (g == 0 && wave == 3 && lane == 32) *as_global(p.loss) = lossacc[0];
+    // the loss was accumulated by wave 4, lane 0 of unit group 0
+    if (g == 0 && wave == 4 && lane == 0) *as_global(p.loss) = lossacc[0];
 }
 
 __global__ void k_zero_words(unsigned long long *p, size_t n) {
@@ -521,13 +552,13 @@ size_t mlp_round_scratch_bytes(int n_clients, int B) {
     return mlp_rec_words(n_clients) * 8 + 256;
 }
 
-static int g_mlp_capacity[2][2][2] = {};  // resident workgroups, per instantiation
+static int g_mlp_capacity[2][2][3] = {};  // resident workgroups, per instantiation
 
-template <int NBT, int TPW, bool FAST>
+template <int NBT, int TPW, bool FAST, bool FULL>
 static hipError_t mlp_capacity(size_t lds, int *cap) {
-    int &cached = g_mlp_capacity[NBT - 1][TPW == kMlpMaxTPW ? 1 : 0][FAST ? 1 : 0];
+    int &cached = g_mlp_capacity[NBT - 1][TPW == kMlpMaxTPW ? 1 : 0][FAST ? (FULL ? 2 : 1) : 0];
     if (cached > 0) { *cap = cached; return hipSuccess; }
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mlp_round<NBT, TPW, FAST>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mlp_round<NBT, TPW, FAST, FULL>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     int dev = 0, cus = 0, per_cu = 0;
@@ -535,14 +566,14 @@ static hipError_t mlp_capacity(size_t lds, int *cap) {
     if (e != hipSuccess) return e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_mlp_round<NBT, TPW, FAST>, kMlpThreads, lds);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_mlp_round<NBT, TPW, FAST, FULL>, kMlpThreads, lds);
     if (e != hipSuccess) return e;
     *cap = cus * per_cu;
     cached = *cap;
     return hipSuccess;
 }
 
-template <int NBT, int TPW, bool FAST>
+template <int NBT, int TPW, bool FAST, bool FULL>
 static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *hp, int nact, int max_m,
                              const float *Wg, int D, int H, int C, void *scratch, int n_clients,
                              uint32_t *epoch) {
@@ -550,7 +581,7 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *h
     const int G = H / 16;
     const size_t lds = mlp_lds_bytes(D, B);
     int cap = 0;
-    hipError_t e = mlp_capacity<NBT, TPW, FAST>(lds, &cap);
+    hipError_t e = mlp_capacity<NBT, TPW, FAST, FULL>(lds, &cap);
     if (e != hipSuccess) return e;
     // Clusters per launch: every workgroup that polls must be resident together with its
     // peers.  Workgroups of unused slots exit at once and free their compute unit, so only
@@ -576,7 +607,7 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *h
         MlpPack pack;
         for (int j = 0; j < here; ++j) pack.p[j] = hp[a0 + j];
         if (prof && prof->on[F_MLP_ROUND]) prof->before(F_MLP_ROUND, s);
-        k_mlp_round<NBT, TPW, FAST><<<grid, kMlpThreads, lds, s>>>(pack, here, a0, Wg, D, H, C, G, xrec, tag0, errflag);
+        k_mlp_round<NBT, TPW, FAST, FULL><<<grid, kMlpThreads, lds, s>>>(pack, here, a0, Wg, D, H, C, G, xrec, tag0, errflag);
         if (prof && prof->on[F_MLP_ROUND]) prof->after(F_MLP_ROUND, s);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -590,14 +621,19 @@ hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *hp
     if (nact <= 0) return hipSuccess;
     const bool small = mlp_tpw(D) == 2;  // at most 2 K tiles per wave
     const bool fast = (D & 15) == 0;
-#define AET_MLP_CASE(nbt, tpw, f) \
-    return mlp_launch<nbt, tpw, f>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch)
+    const bool full = D == 16 * kMlpWaves * mlp_tpw(D);   // no pad tiles
+#define AET_MLP_CASE(nbt, tpw)                                                                        \
+    do {                                                                                              \
+        if (full) return mlp_launch<nbt, tpw, true, true>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);   \
+        if (fast) return mlp_launch<nbt, tpw, true, false>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);  \
+        return mlp_launch<nbt, tpw, false, false>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);           \
+    } while (0)
     if (B == 16) {
-        if (small) { if (fast) AET_MLP_CASE(1, 2, true); else AET_MLP_CASE(1, 2, false); }
-        if (fast) AET_MLP_CASE(1, kMlpMaxTPW, true); else AET_MLP_CASE(1, kMlpMaxTPW, false);
+        if (small) AET_MLP_CASE(1, 2);
+        AET_MLP_CASE(1, kMlpMaxTPW);
     }
-    if (small) { if (fast) AET_MLP_CASE(2, 2, true); else AET_MLP_CASE(2, 2, false); }
-    if (fast) AET_MLP_CASE(2, kMlpMaxTPW, true); else AET_MLP_CASE(2, kMlpMaxTPW, false);
+    if (small) AET_MLP_CASE(2, 2);
+    AET_MLP_CASE(2, kMlpMaxTPW);
 #undef AET_MLP_CASE
 }
 
