@@ -463,9 +463,11 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                     for (int s = 0; s < 4 * NBT; ++s) xb[(tt + 1) & 1][s] = xcol[(16 * (s >> 2) + (s & 3)) * ld + 16 * (tt + 1)];
                 }
                 // two independent accumulation chains per tile
-                f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+                // (the first product of each chain takes the constant zero as its addend)
+                f4 acc0 = mfma16(xb[tt & 1][0], dhb[0], f4{0.f, 0.f, 0.f, 0.f});
+                f4 acc1 = mfma16(xb[tt & 1][1], dhb[1], f4{0.f, 0.f, 0.f, 0.f});
 #pragma unroll
-                for (int s = 0; s < 4 * NBT; s += 2) {
+                for (int s = 2; s < 4 * NBT; s += 2) {
                     acc0 = mfma16(xb[tt & 1][s], dhb[s], acc0);
                     acc1 = mfma16(xb[tt & 1][s + 1], dhb[s + 1], acc1);
                 }
