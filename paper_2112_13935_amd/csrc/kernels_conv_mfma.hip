@@ -269,6 +269,8 @@ struct WgradGeom {
     int DPL;          // floats per channel of the staged d(output) tile: R*OWP padded to 4 mod 32,
                       // so that the 16 channels x 4 pixels of an A operand fall into distinct banks
     int items_per_sample, S;
+    int gin, gd;      // channel groups of 256 threads walking the input tile / the d(output) tile
+    int nq_in_all, nq_d_all;  // the longest walks: channels per input group, rows per d(output) group
     int64_t in_size, out_size, w_off, b_off;
 };
 
@@ -280,8 +282,8 @@ constexpr int kPreD = 16;   // the same for the d(output) tile
 // w/2, w/2+2, ... and N tiles w%2, w%2+2, ...
 //
 // Staging: a thread is tied to one position of the tile (row, column) and walks the channels,
-// so the loop has no index arithmetic; the next work item's elements are fetched into
-// registers before the products of the current one start and go to LDS after them.
+// so the loop has no index arithmetic and no branches; the next work item's elements are
+// fetched into registers before the products of the current one start and go to LDS after them.
 template <int KS, int MT, int NTW, int WM>
 __global__ void __launch_bounds__(256)
 k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
@@ -297,8 +299,8 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
 
     extern __shared__ float smem[];
     const int plane = g.rowsT * g.SWP;
-    float *Ism = smem;                       // [IC + 2][rowsT][SWP]; plane IC = ones, IC+1 = zeros
-    float *Dsm = Ism + (g.IC + 2) * plane;   // [16*MTS][DPL]
+    float *Ism = smem;                       // [IC + 3][rowsT][SWP]; plane IC = ones, IC+1 = zeros, IC+2 = dump
+    float *Dsm = Ism + (g.IC + 3) * plane;   // [16*MTS + 1][DPL]; the last row is a dump
     const int dplane = g.R * g.OWP;
 
     for (int e = tid; e < 2 * plane; e += 256) Ism[g.IC * plane + e] = e < plane ? 1.f : 0.f;
@@ -317,41 +319,70 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
         }
         kb[j] = off + lg;
     }
+    // A operand: lane li of M tile mt holds output channel 16*mt + li
+    int ab[MT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m) ab[m] = (16 * (m0 + WM * m) + li) * g.DPL + lg;
     f4 acc[MT][NTW];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
         for (int j = 0; j < NTW; ++j) acc[m][j] = f4{0.f, 0.f, 0.f, 0.f};
 
-    // this thread's position in the input tile and in the d(output) tile
-    const int gin = 256 / plane;                 // channel groups walking the input tile
+    // This thread's position in the input tile and in the d(output) tile.  Threads beyond
+    // the last whole channel group, and a thread's turns beyond the last channel, load a
+    // valid dummy element and store to the dump areas: the staging code has no branches.
+    const int gin = g.gin;                       // channel groups walking the input tile
     const int ipos = tid % plane, igrp = tid / plane;
     const int ity = ipos / g.SWP, itx = ipos - ity * g.SWP;
     const bool ixok = igrp < gin && (unsigned)(itx - g.pad) < (unsigned)g.IW;
     const int nq_in = igrp < gin ? (g.IC - igrp + gin - 1) / gin : 0;
-    const int gd = 256 / dplane;
+    const int gd = g.gd;
     const int dpos = tid % dplane, dgrp = tid / dplane;
     const int dr = dpos / g.OWP, dx = dpos - dr * g.OWP;
     const bool dxok = dgrp < gd && dx < g.OW;
     const int nq_d = dgrp < gd ? (16 * g.MTS - dgrp + gd - 1) / gd : 0;
-    const int64_t ihw = (int64_t)g.IH * g.IW, ohw = (int64_t)g.OH * g.OW;
+    const int nq_d_real = dgrp < gd && dgrp < g.OC ? (g.OC - dgrp + gd - 1) / gd : 0;  // rows below OC
+    const uint32_t ihw = (uint32_t)(g.IH * g.IW), ohw = (uint32_t)(g.OH * g.OW);
 
+    // the fetched elements stay untouched in registers until they go to LDS (nothing waits
+    // for a load before the products start); ilim / dlim say how many of them are real
     float pin[kPreIn], pd[kPreD];
+    int ilim = 0, dlim = 0;
     const int items = B * g.items_per_sample;
     auto fetch = [&](int it) {
         const int b = it / g.items_per_sample, rb = it - b * g.items_per_sample;
         const int y0 = rb * g.R;
         const int64_t sample = (int64_t)blockIdx.z * B + b;
+        const gcf_ptr sin = as_global(in) + sample * g.in_size;       // uniform bases,
+        const gcf_ptr sd = as_global(dout) + sample * g.out_size;     // 32-bit offsets per thread
         const int sy = y0 + ity - g.pad;
         const bool iok = ixok && (unsigned)sy < (unsigned)g.IH;
-        const gcf_ptr src = as_global(in) + sample * g.in_size + igrp * ihw + (int64_t)sy * g.IW + (itx - g.pad);
+        const uint32_t ioff = iok ? (uint32_t)igrp * ihw + (uint32_t)(sy * g.IW + (itx - g.pad)) : 0u;
+        ilim = iok ? nq_in : 0;
 #pragma unroll
-        for (int q = 0; q < kPreIn; ++q) pin[q] = (iok && q < nq_in) ? src[(int64_t)q * gin * ihw] : 0.f;
+        for (int q = 0; q < kPreIn; ++q)
+            if (q < g.nq_in_all) pin[q] = sin[q < ilim ? ioff + (uint32_t)(q * gin) * ihw : 0u];
         const bool dok = dxok && y0 + dr < g.OH;
-        const gcf_ptr dsrc = as_global(dout) + sample * g.out_size + dgrp * ohw + (int64_t)(y0 + dr) * g.OW + dx;
+        const uint32_t doff = dok ? (uint32_t)dgrp * ohw + (uint32_t)((y0 + dr) * g.OW + dx) : 0u;
+        dlim = dok ? nq_d_real : 0;
 #pragma unroll
         for (int q = 0; q < kPreD; ++q)
-            pd[q] = (dok && q < nq_d && dgrp + gd * q < g.OC) ? dsrc[(int64_t)q * gd * ohw] : 0.f;
+            if (q < g.nq_d_all) pd[q] = sd[q < dlim ? doff + (uint32_t)(q * gd) * ohw : 0u];
+    };
+
+    const int xsteps = g.OWP >> 2, nsteps = g.R * xsteps;
+    auto operands = [&](float (&a)[MT], float (&bv)[NTW], int doff, int po) {
+#pragma unroll
+        for (int m = 0; m < MT; ++m) a[m] = Dsm[ab[m] + doff];
+#pragma unroll
+        for (int j = 0; j < NTW; ++j) bv[j] = Ism[kb[j] + po];
+    };
+    auto products = [&](const float (&a)[MT], const float (&bv)[NTW]) {
+#pragma unroll
+        for (int j = 0; j < NTW; ++j)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[m][j] = mfma16x16x4(a[m], bv[j], acc[m][j]);
     };
 
     int it = sl;
@@ -360,25 +391,35 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
         __syncthreads();   // the products of the previous item are done with the tiles
 #pragma unroll
         for (int q = 0; q < kPreIn; ++q)
-            if (q < nq_in) Ism[(igrp + gin * q) * plane + ipos] = pin[q];
+            if (q < g.nq_in_all)
+                Ism[(q < nq_in ? igrp + gin * q : g.IC + 2) * plane + ipos] = q < ilim ? pin[q] : 0.f;
 #pragma unroll
         for (int q = 0; q < kPreD; ++q)
-            if (q < nq_d) Dsm[(dgrp + gd * q) * g.DPL + dpos] = pd[q];
+            if (q < g.nq_d_all)
+                Dsm[(q < nq_d ? dgrp + gd * q : 16 * g.MTS) * g.DPL + dpos] = q < dlim ? pd[q] : 0.f;
         __syncthreads();
         if (it + g.S < items) fetch(it + g.S);   // in flight while the products run
-        for (int r = 0; r < g.R; ++r) {
-            for (int x4 = 0; x4 < g.OWP; x4 += 4) {
-                float a[MT];
-#pragma unroll
-                for (int m = 0; m < MT; ++m) a[m] = Dsm[(16 * (m0 + WM * m) + li) * g.DPL + r * g.OWP + x4 + lg];
-                const int po = r * g.SWP + x4;
-#pragma unroll
-                for (int j = 0; j < NTW; ++j) {
-                    const float bv = Ism[kb[j] + po];
-#pragma unroll
-                    for (int m = 0; m < MT; ++m) acc[m][j] = mfma16x16x4(a[m], bv, acc[m][j]);
-                }
+        // One step = 4 consecutive pixels of a row.  Two operand sets take turns: the set of
+        // the step after is read from LDS before the products of a step are issued.
+        float a0[MT], b0[NTW], a1[MT], b1[NTW];
+        int xs = 0, po = 0;
+        auto advance = [&]() {
+            po += 4;
+            if (++xs == xsteps) { xs = 0; po += g.SWP - g.OWP; }
+        };
+        operands(a0, b0, 0, 0);
+        for (int t = 0; t < nsteps; t += 2) {
+            const bool odd = t + 1 < nsteps;
+            if (odd) {
+                advance();
+                operands(a1, b1, 4 * (t + 1), po);
             }
+            products(a0, b0);
+            if (t + 2 < nsteps) {
+                advance();
+                operands(a0, b0, 4 * (t + 2), po);
+            }
+            if (odd) products(a1, b1);
         }
     }
     // partial[a][slice][co][k]: lane holds k = 16*nt + li, co = 16*mt + 4*lg + r
@@ -451,6 +492,11 @@ static bool wgrad_geom(const LayerGeom &L, int B, int nact, WgradGeom *g) {
     g->S = 1;  // set by the launcher from the number of resident workgroups
     g->MTS = wgrad_wm(*g) * wgrad_mt(*g);
     g->DPL = g->R * g->OWP + ((4 - (g->R * g->OWP) % 32 + 32) % 32);
+    const int plane = g->rowsT * g->SWP, dplane = g->R * g->OWP;
+    g->gin = plane <= 256 ? 256 / plane : 0;
+    g->gd = dplane <= 256 ? 256 / dplane : 0;
+    g->nq_in_all = g->gin ? (g->IC + g->gin - 1) / g->gin : 0;
+    g->nq_d_all = g->gd ? (16 * g->MTS + g->gd - 1) / g->gd : 0;
     return true;
 }
 
@@ -460,7 +506,7 @@ static int wgrad_ntw(const WgradGeom &g) {
     return n <= 2 ? 2 : n <= 5 ? 5 : 10;
 }
 static size_t wgrad_lds_bytes(const WgradGeom &g) {
-    return sizeof(float) * ((size_t)(g.IC + 2) * g.rowsT * g.SWP + (size_t)16 * g.MTS * g.DPL);
+    return sizeof(float) * ((size_t)(g.IC + 3) * g.rowsT * g.SWP + (size_t)(16 * g.MTS + 1) * g.DPL);
 }
 
 bool conv_wgrad_mfma_supported(const LayerGeom &L, int B) {
@@ -468,10 +514,8 @@ bool conv_wgrad_mfma_supported(const LayerGeom &L, int B) {
     if (!wgrad_geom(L, B, 1, &g)) return false;
     // a thread is tied to one tile position: both tiles must fit the 256 threads, and the
     // channels one thread walks must fit its prefetch registers
-    const int plane = g.rowsT * g.SWP, dplane = g.R * g.OWP;
-    if (plane > 256 || dplane > 256) return false;
-    const int gin = 256 / plane, gd = 256 / dplane;
-    if ((g.IC + gin - 1) / gin > kPreIn || (16 * g.MTS + gd - 1) / gd > kPreD) return false;
+    if (g.gin < 1 || g.gd < 1) return false;
+    if (g.nq_in_all > kPreIn || g.nq_d_all > kPreD) return false;
     return wgrad_lds_bytes(g) <= 64 * 1024;
 }
 
