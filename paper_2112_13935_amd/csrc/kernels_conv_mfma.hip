@@ -42,6 +42,8 @@ struct ConvDir {
     int NT;              // N tiles (16 dst channels) per workgroup
     int CCH;             // source channels per K chunk: 1, 2, 4 or 8
     int rowsT, SWP;      // rows and padded width of the staged source tile
+    int PL;              // floats between the tile's channel planes in LDS (16 mod 32)
+    int npos;            // tile positions one thread stages: 1, 2 or 3
     int64_t src_size, dst_size;  // floats per sample
     int64_t w_off, b_off;
     int ic, oc;          // the layer's own channel counts (weight layout W[oc][ic][K][K])
@@ -49,36 +51,41 @@ struct ConvDir {
 };
 
 // CCH: source channels per K chunk (1, 2, 4 or 8: the smallest that holds the layer's source
-// channels, so that a 1- or 3-channel input does not multiply seven or five channels of zeros)
-template <int KS, bool BWD, int CCH>
+// channels, so that a 1- or 3-channel input does not multiply seven or five channels of zeros).
+// NT: N tiles (16 destination channels each) per workgroup: 1, 2 or 4.
+//
+// Order of the chunk's K elements.  CCH >= 4: k = ((cq*KS + ky)*KS + kx)*4 + c4, channel
+// 4*cq + c4: the four K elements of one matrix instruction are four channels at one filter
+// tap, so a lane's source address is its base plus a number that is the same for the whole
+// wave.  CCH < 4: k = c*KS*KS + ky*KS + kx, each lane keeps the tile offsets of its K
+// elements in registers.  In both cases the operands of the next step are read from LDS
+// before the products of the current step are issued.
+template <int KS, bool BWD, int CCH, int NT>
 __global__ void __launch_bounds__(256)
 k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const float *__restrict__ src,
             float *__restrict__ dst, const float *__restrict__ mask_src) {
     const RoundParams p = rp[blockIdx.z];
     if (u >= p.m) return;
-    constexpr int KCHR = CCH * KS * KS;      // K elements per chunk
+    constexpr int KSQ = KS * KS;
+    constexpr int KCHR = CCH * KSQ;          // K elements per chunk
     constexpr int KCH = (KCHR + 3) / 4 * 4;  // ... rounded up to whole contraction steps (zero weights)
-    constexpr int KCHP = KCH + 4;            // padded weight row in LDS
+    constexpr int KCHP = KCH + 2;            // weight row in LDS: KCHP / 2 odd, no bank conflicts among 16 rows
     constexpr int STEPS = KCH / 4;
+    constexpr bool CF = CCH >= 4;            // channels fastest
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
-    const int nblk = blockIdx.x % ((g.DC + 16 * g.NT - 1) / (16 * g.NT));
-    const int rblk = blockIdx.x / ((g.DC + 16 * g.NT - 1) / (16 * g.NT));
+    const int nblocks = (g.DC + 16 * NT - 1) / (16 * NT);
+    const int nblk = blockIdx.x % nblocks, rblk = blockIdx.x / nblocks;
     const int y0 = rblk * g.R;
-    const int dc0 = nblk * 16 * g.NT;
+    const int dc0 = nblk * 16 * NT;
     const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
-    const gcf_ptr sg = as_global(src) + sample * g.src_size;
+    const gcf_ptr sg = as_global(src) + sample * g.src_size;   // uniform base, 32-bit offsets per thread
     const gcf_ptr wg = as_global(p.W) + g.w_off;
 
     extern __shared__ float smem[];
     const int tile_plane = g.rowsT * g.SWP;
-    float *Ssm = smem;                          // [CCH][rowsT][SWP]
-    float *Wsm = Ssm + CCH * tile_plane;        // [16*NT][KCHP]
-    int *koff = reinterpret_cast<int *>(Wsm + 16 * g.NT * KCHP);  // [KCH]
-
-    for (int k = tid; k < KCH; k += 256) {
-        const int c = k / (KS * KS), r = k - c * KS * KS;
-        koff[k] = k < KCHR ? c * tile_plane + (r / KS) * g.SWP + (r % KS) : 0;  // padding: weight 0
-    }
+    const int PL = g.PL;                        // plane stride: 16 mod 32, so that the four lane
+    float *Ssm = smem;                          // groups of an A operand fall into distinct banks
+    float *Wsm = Ssm + CCH * PL;                // [16*NT][KCHP]
 
     // the wave's two M tiles: (row, column chunk) inside the workgroup's block
     int abase[2];
@@ -86,77 +93,123 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     for (int m = 0; m < 2; ++m) {
         const int mt = 2 * wave + m;
         const int row = mt / g.MPR, cch = mt - row * g.MPR;
-        abase[m] = row * g.SWP + 16 * cch + li;
+        abase[m] = row * g.SWP + 16 * cch + li + (CF ? lg * PL : 0);
     }
-    f4 acc[2][4];
+    int ko[CF ? 1 : STEPS];
+    if (!CF) {
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+            const int k = 4 * st + lg;
+            const int c = k / KSQ, r = k - c * KSQ;
+            ko[CF ? 0 : st] = k < KCHR ? c * PL + (r / KS) * g.SWP + (r % KS) : 0;  // padding: weight 0
+        }
+    }
+    const int bbase = li * KCHP + lg;
+    f4 acc[2][NT];
 #pragma unroll
     for (int m = 0; m < 2; ++m)
 #pragma unroll
-        for (int n = 0; n < 4; ++n) acc[m][n] = f4{0.f, 0.f, 0.f, 0.f};
+        for (int n = 0; n < NT; ++n) acc[m][n] = f4{0.f, 0.f, 0.f, 0.f};
 
-    // Staging without per-element index arithmetic: a thread is tied to positions of the
-    // source tile and walks the chunk's channels, and to one k = (c, ky, kx) of the weight
-    // chunk and walks the destination channels.
+    // Staging without per-element index arithmetic and without branches: a thread is tied to
+    // up to 3 positions of the source tile and walks the chunk's channels, and to one K
+    // element of the weight chunk and walks the destination channels; what lies outside is
+    // loaded from a valid dummy address and replaced by zero when it goes to LDS.
+    const uint32_t shw = (uint32_t)(g.SH * g.SW);
+    uint32_t soff[3];
+    bool sok[3];
+#pragma unroll
+    for (int i = 0; i < 3; ++i) {
+        const int pos = tid + 256 * i;
+        const int ty = pos / g.SWP, tx = pos - ty * g.SWP;
+        const int sy = y0 + ty - g.P, sx = tx - g.P;
+        sok[i] = pos < tile_plane && (unsigned)sy < (unsigned)g.SH && (unsigned)sx < (unsigned)g.SW;
+        soff[i] = sok[i] ? (uint32_t)(sy * g.SW + sx) : 0u;
+    }
     constexpr int WG_ = 256 / KCH > 0 ? 256 / KCH : 1;   // dst-channel groups staging the weights
-    const int wk = tid % KCH, wd0 = tid / KCH;           // this thread's k and first dst channel
-    const int wc = wk / (KS * KS), wr = wk - wc * (KS * KS);
+    const int wk = tid % KCH, wd0 = tid / KCH;           // this thread's K element and first dst channel
+    int wc, wr;
+    if (CF) {
+        const int st = wk >> 2, t = st / KS;
+        wc = 4 * (t / KS) + (wk & 3);
+        wr = (t % KS) * KS + st % KS;
+    } else {
+        wc = wk / KSQ;
+        wr = wk - wc * KSQ;
+    }
     const bool wactive = wd0 < WG_;
     const bool wreal = wk < KCHR;                        // not one of the padding columns
-    const int64_t shw = (int64_t)g.SH * g.SW;
     // element (d, wk) of chunk c0 sits at wbase + c0 * wcstep + d * wdstep
-    const int64_t wdstep = BWD ? (int64_t)(KS * KS) : (int64_t)g.ic * (KS * KS);
-    const int64_t wcstep = BWD ? (int64_t)g.ic * (KS * KS) : (int64_t)(KS * KS);
-    const int64_t wbase = BWD ? ((int64_t)wc * g.ic + dc0) * (KS * KS) + (KS * KS - 1 - wr)
-                              : ((int64_t)dc0 * g.ic + wc) * (KS * KS) + wr;
-    const int nd = 16 * g.NT;
+    const uint32_t wdstep = BWD ? (uint32_t)KSQ : (uint32_t)(g.ic * KSQ);
+    const uint32_t wcstep = BWD ? (uint32_t)(g.ic * KSQ) : (uint32_t)KSQ;
+    const uint32_t wbase = BWD ? (uint32_t)((wc * g.ic + dc0) * KSQ + (KSQ - 1 - wr))
+                               : (uint32_t)((dc0 * g.ic + wc) * KSQ + wr);
+    constexpr int nd = 16 * NT;
+    // destination channels this thread stages: d = wd0 + WG_ * j, real while d < dlim
+    const int dlim = min(nd, g.DC - dc0);
 
     for (int c0 = 0; c0 < g.SC; c0 += CCH) {
         __syncthreads();
-        // source tile (zero outside the image and beyond the last channel); the loads of
-        // the chunk's channels are in flight together
-        for (int pos = tid; pos < tile_plane; pos += 256) {
-            const int ty = pos / g.SWP, tx = pos - ty * g.SWP;
-            const int sy = y0 + ty - g.P, sx = tx - g.P;
-            const bool ok = (unsigned)sy < (unsigned)g.SH && (unsigned)sx < (unsigned)g.SW;
-            const gcf_ptr q = sg + ((int64_t)c0 * g.SH + sy) * g.SW + sx;
-            float v[CCH];
+        {
+            float v[3][CCH];
 #pragma unroll
-            for (int c = 0; c < CCH; ++c) v[c] = (ok && c0 + c < g.SC) ? q[c * shw] : 0.f;
+            for (int i = 0; i < 3; ++i)
+                if (i < g.npos) {
 #pragma unroll
-            for (int c = 0; c < CCH; ++c) Ssm[c * tile_plane + pos] = v[c];
+                    for (int c = 0; c < CCH; ++c)
+                        v[i][c] = sg[(sok[i] && c0 + c < g.SC) ? soff[i] + (uint32_t)(c0 + c) * shw : 0u];
+                }
+#pragma unroll
+            for (int i = 0; i < 3; ++i)
+                if (i < g.npos && tid + 256 * i < tile_plane) {
+#pragma unroll
+                    for (int c = 0; c < CCH; ++c)
+                        Ssm[c * PL + tid + 256 * i] = (sok[i] && c0 + c < g.SC) ? v[i][c] : 0.f;
+                }
         }
         // weights of this chunk: Wsm[d][k]; forward Wt = W[dc][sc][ky][kx], backward-data
         // Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]
         if (wactive) {
             const bool cok = wreal && c0 + wc < g.SC;
-            const gcf_ptr q = wg + wbase + c0 * wcstep;
+            const int lim = cok ? dlim : 0;
+            const uint32_t q = wbase + (uint32_t)c0 * wcstep;
             for (int d0 = wd0; d0 < nd; d0 += WG_ * kStage) {
                 float v[kStage];
 #pragma unroll
                 for (int j = 0; j < kStage; ++j) {
                     const int d = d0 + WG_ * j;
-                    v[j] = (cok && d < nd && dc0 + d < g.DC) ? q[d * wdstep] : 0.f;
+                    v[j] = wg[d < lim ? q + (uint32_t)d * wdstep : 0u];
                 }
 #pragma unroll
                 for (int j = 0; j < kStage; ++j) {
                     const int d = d0 + WG_ * j;
-                    if (d < nd) Wsm[d * KCHP + wk] = v[j];
+                    if (d < nd) Wsm[d * KCHP + wk] = d < lim ? v[j] : 0.f;
                 }
             }
         }
         __syncthreads();
-        for (int s = 0; s < STEPS; ++s) {
-            const int k = 4 * s + lg;
-            const int ko = koff[k];
-            const float a0 = Ssm[abase[0] + ko];
-            const float a1 = Ssm[abase[1] + ko];
+        float a[2][2], bv[2][NT];
+        auto operands = [&](int st, int set) {
+            int off;
+            if (CF) {
+                const int t = st / KS;
+                off = (t / KS) * 4 * PL + (t % KS) * g.SWP + st % KS;
+            } else {
+                off = ko[CF ? 0 : st];
+            }
+            a[set][0] = Ssm[abase[0] + off];
+            a[set][1] = Ssm[abase[1] + off];
 #pragma unroll
-            for (int n = 0; n < 4; ++n) {
-                if (n < g.NT) {
-                    const float b = Wsm[(16 * n + li) * KCHP + k];
-                    acc[0][n] = mfma16x16x4(a0, b, acc[0][n]);
-                    acc[1][n] = mfma16x16x4(a1, b, acc[1][n]);
-                }
+            for (int n = 0; n < NT; ++n) bv[set][n] = Wsm[bbase + 16 * n * KCHP + 4 * st];
+        };
+        operands(0, 0);
+#pragma unroll
+        for (int st = 0; st < STEPS; ++st) {
+            if (st + 1 < STEPS) operands(st + 1, (st + 1) & 1);
+#pragma unroll
+            for (int n = 0; n < NT; ++n) {
+                acc[0][n] = mfma16x16x4(a[st & 1][0], bv[st & 1][n], acc[0][n]);
+                acc[1][n] = mfma16x16x4(a[st & 1][1], bv[st & 1][n], acc[1][n]);
             }
         }
     }
@@ -164,6 +217,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     // epilogue: lane holds dst channel dc0+16n+li, 4 consecutive x
     const gf_ptr dg = as_global(dst) + sample * g.dst_size;
     const gcf_ptr mg = mask_src ? as_global(mask_src) + sample * g.dst_size : nullptr;
+    const bool vec = (g.DW & 3) == 0;   // whole groups of 4 pixels, 16-byte aligned
 #pragma unroll
     for (int m = 0; m < 2; ++m) {
         const int mt = 2 * wave + m;
@@ -171,23 +225,40 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
         const int y = y0 + row;
         if (row >= g.R || y >= g.DH) continue;
 #pragma unroll
-        for (int n = 0; n < 4; ++n) {
-            if (n >= g.NT) continue;
+        for (int n = 0; n < NT; ++n) {
             const int dc = dc0 + 16 * n + li;
             if (dc >= g.DC) continue;
             const float bias = BWD ? 0.f : as_global(p.W)[g.b_off + dc];
+            const int x0 = 16 * cch + 4 * lg;
+            const int64_t i0 = ((int64_t)dc * g.DH + y) * g.DW + x0;
+            if (vec) {
+                if (x0 >= g.DW) continue;
+                f4 v = acc[m][n] + bias;
+                if (BWD) {
+                    if (mg) {
+                        const f4 k = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(mg + i0);
+#pragma unroll
+                        for (int r = 0; r < 4; ++r)
+                            if (!(k[r] > 0.f)) v[r] = 0.f;
+                    }
+                } else if (g.relu) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (!(v[r] > 0.f)) v[r] = 0.f;
+                }
+                *reinterpret_cast<f4 __attribute__((address_space(1))) *>(dg + i0) = v;
+                continue;
+            }
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int x = 16 * cch + 4 * lg + r;
-                if (x >= g.DW) continue;
-                const int64_t i = ((int64_t)dc * g.DH + y) * g.DW + x;
+                if (x0 + r >= g.DW) continue;
                 float v = acc[m][n][r] + bias;
                 if (BWD) {
-                    if (mg && !(mg[i] > 0.f)) v = 0.f;
+                    if (mg && !(mg[i0 + r] > 0.f)) v = 0.f;
                 } else if (g.relu && !(v > 0.f)) {
                     v = 0.f;
                 }
-                dg[i] = v;
+                dg[i0 + r] = v;
             }
         }
     }
@@ -212,17 +283,22 @@ static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d) {
     if (d->R < 1) d->R = 1;
     // the 4 waves own 8 M tiles; with MPR in {3, 5, 6, 7} some tiles stay unused
     d->NT = (d->DC + 15) / 16;
-    if (d->NT > 4) d->NT = 4;
+    d->NT = d->NT <= 1 ? 1 : d->NT <= 2 ? 2 : 4;
     d->CCH = d->SC <= 1 ? 1 : d->SC <= 2 ? 2 : d->SC <= 4 ? 4 : kCch;
     d->rowsT = d->R + KS - 1;
     d->SWP = 16 * d->MPR + KS - 1;
     d->SWP += (d->SWP & 1) ? 0 : 1;  // odd row stride: fewer LDS bank conflicts
+    const int tile_plane = d->rowsT * d->SWP;
+    d->PL = tile_plane + ((16 - tile_plane % 32 + 32) % 32);
+    d->npos = (tile_plane + 255) / 256;
+    if (d->npos > 3) return false;
+    if (d->src_size >= (int64_t)1 << 31 || (int64_t)L.oc * L.ic * KS * KS >= (int64_t)1 << 31) return false;
     return true;
 }
 
 static size_t conv_lds_bytes(const ConvDir &d, int KS) {
     const int KCH = (d.CCH * KS * KS + 3) / 4 * 4;
-    return sizeof(float) * ((size_t)d.CCH * d.rowsT * d.SWP + (size_t)16 * d.NT * (KCH + 4)) + sizeof(int) * KCH;
+    return sizeof(float) * ((size_t)d.CCH * d.PL + (size_t)16 * d.NT * (KCH + 2));
 }
 
 bool conv_mfma_supported(const LayerGeom &L, bool bwd) {
@@ -243,13 +319,15 @@ hipError_t launch_conv_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp
     const int fam = bwd ? F_CONV_BWD_DATA : F_CONV_FWD;
     const bool timed = prof && prof->on[fam];
     if (timed) prof->before(fam, s);
-#define AET_CONV(KSv, CCHv)                                                                        \
-    if (L.k == KSv && d.CCH == CCHv) {                                                            \
-        if (bwd) k_conv_mfma<KSv, true, CCHv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);  \
-        else k_conv_mfma<KSv, false, CCHv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);     \
+#define AET_CONV(KSv, CCHv, NTv)                                                                          \
+    if (L.k == KSv && d.CCH == CCHv && d.NT == NTv) {                                                   \
+        if (bwd) k_conv_mfma<KSv, true, CCHv, NTv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);  \
+        else k_conv_mfma<KSv, false, CCHv, NTv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);     \
     }
-    AET_CONV(3, 1) AET_CONV(3, 2) AET_CONV(3, 4) AET_CONV(3, 8)
-    AET_CONV(5, 1) AET_CONV(5, 2) AET_CONV(5, 4) AET_CONV(5, 8)
+#define AET_CONV_NT(KSv, CCHv) AET_CONV(KSv, CCHv, 1) AET_CONV(KSv, CCHv, 2) AET_CONV(KSv, CCHv, 4)
+    AET_CONV_NT(3, 1) AET_CONV_NT(3, 2) AET_CONV_NT(3, 4) AET_CONV_NT(3, 8)
+    AET_CONV_NT(5, 1) AET_CONV_NT(5, 2) AET_CONV_NT(5, 4) AET_CONV_NT(5, 8)
+#undef AET_CONV_NT
 #undef AET_CONV
     if (timed) prof->after(fam, s);
     return hipGetLastError();
