@@ -126,27 +126,41 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
         sok[i] = pos < tile_plane && (unsigned)sy < (unsigned)g.SH && (unsigned)sx < (unsigned)g.SW;
         soff[i] = sok[i] ? (uint32_t)(sy * g.SW + sx) : 0u;
     }
-    constexpr int WG_ = 256 / KCH > 0 ? 256 / KCH : 1;   // dst-channel groups staging the weights
-    const int wk = tid % KCH, wd0 = tid / KCH;           // this thread's K element and first dst channel
-    int wc, wr;
-    if (CF) {
-        const int st = wk >> 2, t = st / KS;
-        wc = 4 * (t / KS) + (wk & 3);
-        wr = (t % KS) * KS + st % KS;
-    } else {
-        wc = wk / KSQ;
-        wr = wk - wc * KSQ;
-    }
-    const bool wactive = wd0 < WG_;
-    const bool wreal = wk < KCHR;                        // not one of the padding columns
-    // element (d, wk) of chunk c0 sits at wbase + c0 * wcstep + d * wdstep
-    const uint32_t wdstep = BWD ? (uint32_t)KSQ : (uint32_t)(g.ic * KSQ);
-    const uint32_t wcstep = BWD ? (uint32_t)(g.ic * KSQ) : (uint32_t)KSQ;
-    const uint32_t wbase = BWD ? (uint32_t)((wc * g.ic + dc0) * KSQ + (KSQ - 1 - wr))
-                               : (uint32_t)((dc0 * g.ic + wc) * KSQ + wr);
+    // Weights of a chunk, Wsm[d][k].  Threads follow the memory order, so that a wave's loads
+    // are consecutive addresses, and scatter into the K order of the chunk in LDS.
+    //   forward, Wt = W[dc][sc][ky][kx]: for one dc the chunk is a run of CCH*KS*KS floats;
+    //     a thread is tied to one element of the run and walks the destination channels.
+    //   backward-data, Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]: for one sc the
+    //     workgroup's destination channels are a run of 16*NT*KS*KS floats; a thread is tied
+    //     to up to NPB elements of the run and walks the chunk's source channels.
     constexpr int nd = 16 * NT;
-    // destination channels this thread stages: d = wd0 + WG_ * j, real while d < dlim
-    const int dlim = min(nd, g.DC - dc0);
+    const int dlim = min(nd, g.DC - dc0);                // destination channels that exist
+    auto kcol = [](int c, int tap) { return CF ? ((c >> 2) * KSQ + tap) * 4 + (c & 3) : c * KSQ + tap; };
+    constexpr int WG_ = 256 / KCH > 0 ? 256 / KCH : 1;   // forward: dst-channel groups
+    const int wm = tid % KCH, wd0 = tid / KCH;           // forward: element of the run, first dst channel
+    const int wc = wm / KSQ, wr = wm - wc * KSQ;
+    const bool wactive = wd0 < WG_;
+    const bool wreal = wm < KCHR;                        // not one of the padding columns
+    const int wcol = wreal ? kcol(wc, wr) : wm;
+    const uint32_t wdstep = (uint32_t)(g.ic * KSQ);
+    const uint32_t wbase = (uint32_t)(dc0 * g.ic * KSQ + wm);
+    constexpr int NPB = (nd * KSQ + 255) / 256;          // backward-data: elements of the run per thread
+    uint32_t boff[BWD ? NPB : 1];
+    int blds[BWD ? NPB : 1];
+    if (BWD) {
+#pragma unroll
+        for (int i = 0; i < NPB; ++i) {
+            const int j = tid + 256 * i;
+            const int d = j / KSQ, tm = j - d * KSQ;
+            const bool ok = j < nd * KSQ && d < dlim;
+            boff[BWD ? i : 0] = ok ? (uint32_t)(dc0 * KSQ + j) : 0xffffffffu;
+            blds[BWD ? i : 0] = j < nd * KSQ ? d * KCHP + kcol(0, KSQ - 1 - tm) : -1;
+        }
+        if (KCH > KCHR)   // padding columns: zero weights, written once
+            for (int e = tid; e < nd * (KCH - KCHR); e += 256)
+                Wsm[(e / (KCH - KCHR)) * KCHP + KCHR + e % (KCH - KCHR)] = 0.f;
+    }
+    const uint32_t bcstep = (uint32_t)(g.ic * KSQ);
 
     for (int c0 = 0; c0 < g.SC; c0 += CCH) {
         __syncthreads();
@@ -167,12 +181,31 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
                         Ssm[c * PL + tid + 256 * i] = (sok[i] && c0 + c < g.SC) ? v[i][c] : 0.f;
                 }
         }
-        // weights of this chunk: Wsm[d][k]; forward Wt = W[dc][sc][ky][kx], backward-data
-        // Wt[dc][sc][ky][kx] = W[sc][dc][K-1-ky][K-1-kx]
-        if (wactive) {
+        if (BWD) {
+#pragma unroll
+            for (int i0 = 0; i0 < NPB; i0 += 3) {
+                float v[3][CCH];
+#pragma unroll
+                for (int i = i0; i < i0 + 3 && i < NPB; ++i)
+#pragma unroll
+                    for (int c = 0; c < CCH; ++c) {
+                        const bool ok = boff[BWD ? i : 0] != 0xffffffffu && c0 + c < g.SC;
+                        v[i - i0][c] = wg[ok ? boff[BWD ? i : 0] + (uint32_t)(c0 + c) * bcstep : 0u];
+                    }
+#pragma unroll
+                for (int i = i0; i < i0 + 3 && i < NPB; ++i)
+                    if (blds[BWD ? i : 0] >= 0) {
+#pragma unroll
+                        for (int c = 0; c < CCH; ++c) {
+                            const bool ok = boff[BWD ? i : 0] != 0xffffffffu && c0 + c < g.SC;
+                            Wsm[blds[BWD ? i : 0] + kcol(c, 0)] = ok ? v[i - i0][c] : 0.f;
+                        }
+                    }
+            }
+        } else if (wactive) {
             const bool cok = wreal && c0 + wc < g.SC;
             const int lim = cok ? dlim : 0;
-            const uint32_t q = wbase + (uint32_t)c0 * wcstep;
+            const uint32_t q = wbase + (uint32_t)c0 * KSQ;
             for (int d0 = wd0; d0 < nd; d0 += WG_ * kStage) {
                 float v[kStage];
 #pragma unroll
@@ -183,7 +216,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
 #pragma unroll
                 for (int j = 0; j < kStage; ++j) {
                     const int d = d0 + WG_ * j;
-                    if (d < nd) Wsm[d * KCHP + wk] = d < lim ? v[j] : 0.f;
+                    if (d < nd) Wsm[d * KCHP + wcol] = d < lim ? v[j] : 0.f;
                 }
             }
         }
