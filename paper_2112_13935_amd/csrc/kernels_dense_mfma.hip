@@ -151,6 +151,119 @@ k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int
     }
 }
 
+// Backward-weight with vector memory accesses, for layers whose rows are 16-byte aligned
+// (K and the parameter offset multiples of 4).  The GEMM is taken transposed,
+//   g^T[k][o] = (1/B) sum_b in[b][k] dout[b][o],        M = k, N = o, contraction over b,
+// so that the four accumulator elements of a lane are four consecutive k of one output
+// unit o: W and U are updated in place with float4 loads and stores.  A workgroup owns 64
+// k x 64 o; wave w owns the 16 output units 16w.. and all four k tiles.  Both operands are
+// staged as [b][k] / [b][o] rows (float4 loads without branches: what lies outside is read
+// from a valid dummy address and replaced by zero), row stride 80 floats = 16 mod 32 banks.
+// VO: dout rows are 16-byte aligned too (O a multiple of 4).
+constexpr int kWS = 80;   // LDS row stride of the staged operands
+
+template <bool VO>
+__global__ void __launch_bounds__(256)
+k_dense_wgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
+              int64_t b_off, const float *__restrict__ x, const float *__restrict__ y) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const int kbase = blockIdx.x * kDT, obase = blockIdx.y * kDT;
+    const int64_t cb = (int64_t)blockIdx.z * B;
+    typedef const f4 __attribute__((address_space(1))) *gv4;
+    typedef f4 __attribute__((address_space(1))) *gw4;
+    const gcf_ptr xin = as_global(x) + cb * K;    // in[b][k] of this client
+    const gcf_ptr yd = as_global(y) + cb * O;     // dout[b][o]
+
+    __shared__ __attribute__((aligned(16))) float As[kDK * kWS];   // As[b][k]
+    __shared__ __attribute__((aligned(16))) float Bs[kDK * kWS];   // Bs[b][o]
+
+    const int srow = tid >> 4, sc4 = 4 * (tid & 15);   // staging: rows srow, srow + 16; 4 columns from sc4
+    const bool kok = kbase + sc4 < K;
+    const bool ook = obase + sc4 < O;
+    const int orow = tid >> 6, ocol = tid & 63;        // scalar staging of dout: rows orow + 4 i
+
+    f4 acc[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) acc[m] = f4{0.f, 0.f, 0.f, 0.f};
+
+    for (int b0 = 0; b0 < B; b0 += kDK) {
+        __syncthreads();
+        f4 va[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int b = b0 + srow + 16 * i;
+            const bool ok = kok && b < B;
+            va[i] = *reinterpret_cast<gv4>(xin + (ok ? (int64_t)b * K + kbase + sc4 : 0));
+            if (!ok) va[i] = f4{0.f, 0.f, 0.f, 0.f};
+        }
+        if (VO) {
+            f4 vb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int b = b0 + srow + 16 * i;
+                const bool ok = ook && b < B;
+                vb[i] = *reinterpret_cast<gv4>(yd + (ok ? (int64_t)b * O + obase + sc4 : 0));
+                if (!ok) vb[i] = f4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int i = 0; i < 2; ++i) *reinterpret_cast<f4 *>(&Bs[(srow + 16 * i) * kWS + sc4]) = vb[i];
+        } else {
+            float vb[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int b = b0 + orow + 4 * i;
+                const bool ok = obase + ocol < O && b < B;
+                vb[i] = yd[ok ? (int64_t)b * O + obase + ocol : 0];
+                if (!ok) vb[i] = 0.f;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) Bs[(orow + 4 * i) * kWS + ocol] = vb[i];
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *reinterpret_cast<f4 *>(&As[(srow + 16 * i) * kWS + sc4]) = va[i];
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < kDK / 4; ++s) {
+            const float b = Bs[(4 * s + lg) * kWS + 16 * wave + li];
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+                acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(As[(4 * s + lg) * kWS + 16 * m + li], b, acc[m], 0, 0, 0);
+        }
+    }
+
+    // lane: output unit o = obase + 16 wave + li, k = kbase + 16 m + 4 lg .. + 3
+    const float invB = 1.0f / (float)B;
+    const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
+    const int o = obase + 16 * wave + li;
+    if (o < O) {
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const int k = kbase + 16 * m + 4 * lg;
+            if (k < K) {
+                const int64_t wi = w_off + (int64_t)o * K + k;
+                const f4 g = acc[m] * invB;
+                f4 w = *reinterpret_cast<gv4>(Wc + wi);
+                f4 uu = *reinterpret_cast<gv4>(Uc + wi);
+                w -= p.eta * g;
+                uu += g;
+                *reinterpret_cast<gw4>(Wc + wi) = w;
+                *reinterpret_cast<gw4>(Uc + wi) = uu;
+            }
+        }
+    }
+    // bias: the first k block sums dout over the mini-batch
+    if (blockIdx.x == 0 && tid < kDT && obase + tid < O) {
+        const int ob = obase + tid;
+        float sb = 0.f;
+        for (int b = 0; b < B; ++b) sb += yd[(int64_t)b * O + ob];
+        sb *= invB;
+        Wc[b_off + ob] -= p.eta * sb;
+        Uc[b_off + ob] += sb;
+    }
+}
+
 // Forward pass of a layer with few output tiles (small mini-batch, moderate width): one
 // workgroup per 16 x 16 output tile, its 4 waves split the contraction (wave w takes the
 // 16-wide chunks w, w+4, ...) and feed the matrix cores straight from global memory: lane
@@ -247,7 +360,11 @@ hipError_t launch_dense_mfma(hipStream_t s, Profiler *prof, int mode, const Roun
         k_dense_mfma<DENSE_FWD, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
     else if (mode == DENSE_BWD_DATA)
         k_dense_mfma<DENSE_BWD_DATA, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
-    else
+    else if ((K & 3) == 0 && (w_off & 3) == 0) {
+        dim3 wgrid((unsigned)((K + kDT - 1) / kDT), (unsigned)((O + kDT - 1) / kDT), (unsigned)nact);
+        if ((O & 3) == 0) k_dense_wgrad<true><<<wgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, x, y);
+        else k_dense_wgrad<false><<<wgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, x, y);
+    } else
         k_dense_mfma<DENSE_BWD_WEIGHT, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
     if (timed) prof->after(fam, s);
     return hipGetLastError();
