@@ -288,6 +288,79 @@ k_pool_bwd(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
     }
 }
 
+// The same two kernels for layers whose input rows are 16-byte aligned (input width a
+// multiple of 4): a thread owns two neighbouring windows, reads and writes float4 rows.
+typedef float pf4 __attribute__((ext_vector_type(4)));
+typedef float pf2 __attribute__((ext_vector_type(2)));
+
+__global__ void __launch_bounds__(256)
+k_pool_fwd_pair(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
+                const float *__restrict__ in, float *__restrict__ out, uint8_t *__restrict__ amax) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;   // pair of outputs 2 idx, 2 idx + 1
+    const int owh = g.ow >> 1;
+    if (idx >= g.oc * g.oh * owh) return;
+    const int oxp = idx % owh, oy = (idx / owh) % g.oh, c = idx / (owh * g.oh);
+    const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
+    const float *x = in + sample * g.in_size + ((int64_t)c * g.ih + 2 * oy) * g.iw + 4 * oxp;
+    const pf4 r0 = *reinterpret_cast<const pf4 *>(x), r1 = *reinterpret_cast<const pf4 *>(x + g.iw);
+    pf2 best;
+    unsigned which2 = 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        float b = r0[2 * h];
+        unsigned w = 0;
+        if (r0[2 * h + 1] > b) { b = r0[2 * h + 1]; w = 1; }
+        if (r1[2 * h] > b) { b = r1[2 * h]; w = 2; }
+        if (r1[2 * h + 1] > b) { b = r1[2 * h + 1]; w = 3; }
+        best[h] = b;
+        which2 |= w << (8 * h);
+    }
+    const int64_t o = sample * g.out_size + 2 * (int64_t)idx;
+    *reinterpret_cast<pf2 *>(out + o) = best;
+    *reinterpret_cast<uint16_t *>(amax + o) = (uint16_t)which2;
+}
+
+__global__ void __launch_bounds__(256)
+k_pool_bwd_pair(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
+                const float *__restrict__ dout, const uint8_t *__restrict__ amax,
+                float *__restrict__ din, const float *__restrict__ mask_src) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    const int owh = g.ow >> 1;
+    if (idx >= g.oc * g.oh * owh) return;
+    const int oxp = idx % owh, oy = (idx / owh) % g.oh, c = idx / (owh * g.oh);
+    const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
+    const int64_t o = sample * g.out_size + 2 * (int64_t)idx;
+    const pf2 d = *reinterpret_cast<const pf2 *>(dout + o);
+    const unsigned which2 = *reinterpret_cast<const uint16_t *>(amax + o);
+    const int64_t base = sample * g.in_size + ((int64_t)c * g.ih + 2 * oy) * g.iw + 4 * oxp;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        pf4 v;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int h = e >> 1, j = 2 * r + (e & 1);
+            v[e] = ((which2 >> (8 * h)) & 0xffu) == (unsigned)j ? d[h] : 0.f;
+        }
+        const int64_t i = base + (int64_t)r * g.iw;
+        if (mask_src) {
+            const pf4 k = *reinterpret_cast<const pf4 *>(mask_src + i);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if (!(k[e] > 0.f)) v[e] = 0.f;
+        }
+        *reinterpret_cast<pf4 *>(din + i) = v;
+    }
+}
+
+// rows of the pooling input are 16-byte aligned and the windows come in pairs
+static bool pool_pairs(const LayerGeom &g) {
+    return (g.iw & 3) == 0 && (g.ow & 1) == 0 && 2 * g.ow == g.iw && 2 * g.oh <= g.ih;
+}
+
 // loss and d loss / d logits of the mini-batch; one block per client
 __global__ void __launch_bounds__(256)
 k_softmax_ce(const RoundParams *__restrict__ rp, int u, int B, int C,
@@ -375,8 +448,13 @@ hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *d
             AET_RETURN_IF(conv_dispatch(g.k, s, prof, dp, nact, u, B, g, 0, sc.act[l], nullptr,
                                         sc.act[l + 1], nullptr, !sc.plain));
         } else if (g.type == 1) {
-            dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
-            AET_TIMED(F_POOL_FWD, k_pool_fwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.act[l], sc.act[l + 1], sc.amax[l]));
+            if (pool_pairs(g)) {
+                dim3 grid((unsigned)((g.out_size / 2 + 255) / 256), B, nact);
+                AET_TIMED(F_POOL_FWD, k_pool_fwd_pair<<<grid, 256, 0, s>>>(dp, u, B, g, sc.act[l], sc.act[l + 1], sc.amax[l]));
+            } else {
+                dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
+                AET_TIMED(F_POOL_FWD, k_pool_fwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.act[l], sc.act[l + 1], sc.amax[l]));
+            }
             AET_RETURN_IF(hipGetLastError());
         } else if (!sc.plain) {
             AET_RETURN_IF(launch_dense_mfma(s, prof, 0, dp, nact, u, B, (int)g.in_size, g.oc, g.w_off, g.b_off,
@@ -402,8 +480,13 @@ hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *d
                                         sc.wgrad, nullptr, !sc.plain));
         } else if (g.type == 1) {
             if (l > 0) {
-                dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
-                AET_TIMED(F_POOL_BWD, k_pool_bwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.del[l + 1], sc.amax[l], sc.del[l], mask));
+                if (pool_pairs(g)) {
+                    dim3 grid((unsigned)((g.out_size / 2 + 255) / 256), B, nact);
+                    AET_TIMED(F_POOL_BWD, k_pool_bwd_pair<<<grid, 256, 0, s>>>(dp, u, B, g, sc.del[l + 1], sc.amax[l], sc.del[l], mask));
+                } else {
+                    dim3 grid((unsigned)((g.out_size + 255) / 256), B, nact);
+                    AET_TIMED(F_POOL_BWD, k_pool_bwd<<<grid, 256, 0, s>>>(dp, u, B, g, sc.del[l + 1], sc.amax[l], sc.del[l], mask));
+                }
                 AET_RETURN_IF(hipGetLastError());
             }
         } else if (!sc.plain) {
