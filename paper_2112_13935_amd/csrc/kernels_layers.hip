@@ -417,11 +417,182 @@ static hipError_t conv_step(hipStream_t s, Profiler *prof, const RoundParams *dp
     return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------
+// Backward-weight of a convolution with very few channels (LeNet's first layer: 1 -> 6),
+// where 16 x 16 matrix tiles would be mostly padding: plain FMAs, one workgroup per
+// (client, output channel, input channel).  A thread owns one filter row ky and one output
+// row y of one of the samples in flight; it slides along the row with the KS input values
+// of the window in registers (one new input value and one d(output) value per pixel feed KS
+// FMAs).  The per-row sums are added in fixed order (sample slot, then y), scaled by 1/B and
+// applied:  w <- w - eta g,  U <- U + g.  Stride 1, zero padding.
+// ---------------------------------------------------------------------------------------
+constexpr int kDirectPos = 4;   // tile positions one thread stages, at most
+constexpr int kDirectSlots = 4; // samples in flight, at most
+
+template <int KS>
+__global__ void __launch_bounds__(256)
+k_conv_wgrad_direct(const RoundParams *__restrict__ rp, int u, int B, LayerGeom g,
+                    const float *__restrict__ in, const float *__restrict__ dout) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    const int oc = blockIdx.x, ic = blockIdx.y, tid = threadIdx.x;
+    const int IWP = (g.iw + 2 * g.pad) | 1, IHP = g.ih + 2 * g.pad;   // padded plane, odd row stride
+    const int OWS = g.ow | 1;
+    const int rows = KS * g.oh;              // threads per sample in flight
+    const int SPW = 256 / rows < kDirectSlots ? 256 / rows : kDirectSlots;   // samples in flight
+    const int iplane = IHP * IWP, dplane = g.oh * OWS;
+    const int ihw = g.ih * g.iw, ohw = g.oh * g.ow;
+    extern __shared__ float sm[];
+    float *Ism = sm;                         // [SPW][IHP][IWP], borders zero
+    float *Dsm = Ism + SPW * iplane;         // [SPW][oh][OWS]
+    float *red = Dsm + SPW * dplane;         // [SPW * rows][KS + 1]: row sums per kx, and of d(output)
+    const int slot = tid / rows, rem = tid - slot * rows;
+    const int ky = rem / g.oh, y = rem - ky * g.oh;
+    const bool active = slot < SPW;
+    const int64_t cb = (int64_t)blockIdx.z * B;
+
+    // staging: a thread is tied to up to kDirectPos positions of each plane
+    int igo[kDirectPos], ilo[kDirectPos], dgo[kDirectPos], dlo[kDirectPos];
+#pragma unroll
+    for (int i = 0; i < kDirectPos; ++i) {
+        const int e = tid + 256 * i;
+        const int yi = e / g.iw, xi = e - yi * g.iw;
+        igo[i] = e < ihw ? e : -1;
+        ilo[i] = (yi + g.pad) * IWP + xi + g.pad;
+        const int yo = e / g.ow, xo = e - yo * g.ow;
+        dgo[i] = e < ohw ? e : -1;
+        dlo[i] = yo * OWS + xo;
+    }
+    for (int e = tid; e < SPW * iplane; e += 256) Ism[e] = 0.f;
+
+    float acc[KS], dsum = 0.f;
+#pragma unroll
+    for (int k = 0; k < KS; ++k) acc[k] = 0.f;
+
+    // the planes of the next samples are fetched into registers before the products of the
+    // current ones start and go to LDS after them
+    float vi[kDirectSlots][kDirectPos], vd[kDirectSlots][kDirectPos];
+    auto fetch = [&](int b0) {
+#pragma unroll
+        for (int sl = 0; sl < kDirectSlots; ++sl) {
+            if (sl < SPW) {
+                const int b = b0 + sl < B ? b0 + sl : 0;
+                const float *ib = in + (cb + b) * g.in_size + (int64_t)ic * ihw;
+                const float *db = dout + (cb + b) * g.out_size + (int64_t)oc * ohw;
+#pragma unroll
+                for (int i = 0; i < kDirectPos; ++i) {
+                    vi[sl][i] = ib[igo[i] >= 0 ? igo[i] : 0];
+                    vd[sl][i] = db[dgo[i] >= 0 ? dgo[i] : 0];
+                }
+            }
+        }
+    };
+    constexpr int CH = 2 * KS;   // pixels per step of the row walk (a multiple of KS: the window's
+                                 // registers keep their places)
+    fetch(0);
+    for (int b0 = 0; b0 < B; b0 += SPW) {
+        __syncthreads();   // the products of the previous samples are done (first pass: borders are zero)
+#pragma unroll
+        for (int sl = 0; sl < kDirectSlots; ++sl) {
+            if (sl < SPW) {
+                const bool bok = b0 + sl < B;
+#pragma unroll
+                for (int i = 0; i < kDirectPos; ++i) {
+                    if (igo[i] >= 0) Ism[sl * iplane + ilo[i]] = bok ? vi[sl][i] : 0.f;
+                    if (dgo[i] >= 0) Dsm[sl * dplane + dlo[i]] = bok ? vd[sl][i] : 0.f;
+                }
+            }
+        }
+        __syncthreads();
+        if (b0 + SPW < B) fetch(b0 + SPW);
+        if (active) {
+            const float *Irow = Ism + slot * iplane + (y + ky) * IWP;
+            const float *Drow = Dsm + slot * dplane + y * OWS;
+            float w[KS];
+#pragma unroll
+            for (int j = 0; j < KS - 1; ++j) w[j] = Irow[j];
+            for (int x0 = 0; x0 < g.ow; x0 += CH) {
+                float dv[CH], nv[CH];
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const int x = x0 + j < g.ow ? x0 + j : g.ow - 1;   // beyond the row: d = 0
+                    nv[j] = Irow[x + KS - 1];
+                    dv[j] = Drow[x];
+                    if (x0 + j >= g.ow) dv[j] = 0.f;
+                }
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    w[(j + KS - 1) % KS] = nv[j];
+                    dsum += dv[j];
+#pragma unroll
+                    for (int kx = 0; kx < KS; ++kx) acc[kx] += dv[j] * w[(j + kx) % KS];
+                }
+            }
+        }
+    }
+    if (active) {
+#pragma unroll
+        for (int kx = 0; kx < KS; ++kx) red[tid * (KS + 1) + kx] = acc[kx];
+        red[tid * (KS + 1) + KS] = dsum;
+    }
+    __syncthreads();
+    const float invB = 1.0f / (float)B;
+    if (tid < KS * KS) {
+        const int fy = tid / KS, fx = tid - fy * KS;
+        float sum = 0.f;
+        for (int sl = 0; sl < SPW; ++sl)
+            for (int yy = 0; yy < g.oh; ++yy) sum += red[(sl * rows + fy * g.oh + yy) * (KS + 1) + fx];
+        sum *= invB;
+        const int64_t wi = g.w_off + ((int64_t)(oc * g.ic + ic) * KS + fy) * KS + fx;
+        p.W[wi] -= p.eta * sum;
+        p.U[wi] += sum;
+    } else if (tid == KS * KS && ic == 0) {
+        float sum = 0.f;
+        for (int sl = 0; sl < SPW; ++sl)
+            for (int yy = 0; yy < g.oh; ++yy) sum += red[(sl * rows + yy) * (KS + 1) + KS];
+        sum *= invB;
+        p.W[g.b_off + oc] -= p.eta * sum;
+        p.U[g.b_off + oc] += sum;
+    }
+}
+
+static size_t conv_wgrad_direct_lds(const LayerGeom &g) {
+    const int IWP = (g.iw + 2 * g.pad) | 1, IHP = g.ih + 2 * g.pad, OWS = g.ow | 1;
+    const int rows = g.k * g.oh;
+    if (rows > 256) return 0;
+    const int SPW = 256 / rows < kDirectSlots ? 256 / rows : kDirectSlots;
+    return sizeof(float) * ((size_t)SPW * (IHP * IWP + g.oh * OWS) + (size_t)SPW * rows * (g.k + 1));
+}
+
+// few channels (the matrix tiles of the MFMA kernel would be mostly padding), small planes
+static bool conv_wgrad_direct_ok(const LayerGeom &g) {
+    if (!(g.k == 3 || g.k == 5)) return false;
+    if (g.ic * g.k * g.k + 1 > 32 || g.oc > 16) return false;
+    if (g.ih * g.iw > 256 * kDirectPos || g.oh * g.ow > 256 * kDirectPos) return false;
+    if (g.ow != g.iw + 2 * g.pad - g.k + 1 || g.oh != g.ih + 2 * g.pad - g.k + 1) return false;
+    const size_t lds = conv_wgrad_direct_lds(g);
+    return lds > 0 && lds <= 64 * 1024;
+}
+
+static hipError_t launch_conv_wgrad_direct(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact,
+                                           int u, int B, const LayerGeom &g, const float *in,
+                                           const float *dout) {
+    dim3 grid((unsigned)g.oc, (unsigned)g.ic, (unsigned)nact);
+    const size_t lds = conv_wgrad_direct_lds(g);
+    if (g.k == 3)
+        AET_TIMED(F_CONV_BWD_WEIGHT, k_conv_wgrad_direct<3><<<grid, 256, lds, s>>>(dp, u, B, g, in, dout));
+    else
+        AET_TIMED(F_CONV_BWD_WEIGHT, k_conv_wgrad_direct<5><<<grid, 256, lds, s>>>(dp, u, B, g, in, dout));
+    return hipGetLastError();
+}
+
 static hipError_t conv_dispatch(int ks, hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                                 int B, const LayerGeom &g, int which, const float *a,
                                 const float *b, float *c, const float *mask, bool mfma) {
     if (which < 2 && mfma && conv_mfma_supported(g, which == 1))
         return launch_conv_mfma(s, prof, dp, nact, u, B, g, which == 1, a, c, mask);
+    if (which == 2 && mfma && conv_wgrad_direct_ok(g))
+        return launch_conv_wgrad_direct(s, prof, dp, nact, u, B, g, a, b);
     if (which == 2 && mfma && c && conv_wgrad_mfma_supported(g, B))
         return launch_conv_wgrad_mfma(s, prof, dp, nact, u, B, g, a, b, c);
     switch (ks) {
