@@ -264,6 +264,92 @@ k_dense_wgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, in
     }
 }
 
+// Backward-data with vector memory accesses, for layers whose rows are 16-byte aligned (K and
+// the parameter offset multiples of 4).  The GEMM is taken transposed,
+//   din^T[k][b] = sum_o W[o][k] dout[b][o],             M = k, N = b, contraction over o,
+// so that W is staged as it lies in memory (rows of consecutive k) and a lane ends up with
+// four consecutive k of one sample: float4 stores (and float4 loads of the ReLU mask).
+// A workgroup owns 64 k x 16*NBT samples; wave w owns the k tile 16w.. and all sample tiles.
+// dout is staged transposed ([o][b], odd row stride); chunks of 32 output units.
+template <int NBT>
+__global__ void __launch_bounds__(256)
+k_dense_dgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
+              const float *__restrict__ y, float *__restrict__ z, const float *__restrict__ mask_src) {
+    const RoundParams p = rp[blockIdx.z];
+    if (u >= p.m) return;
+    constexpr int BS = NBT == 4 ? 81 : 49;   // row stride of the transposed dout tile
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
+    const int kbase = blockIdx.x * kDT, bbase = blockIdx.y * 16 * NBT;
+    const int64_t cb = (int64_t)blockIdx.z * B;
+    typedef const f4 __attribute__((address_space(1))) *gv4;
+    typedef f4 __attribute__((address_space(1))) *gw4;
+    const gcf_ptr W = as_global(p.W) + w_off;
+    const gcf_ptr yd = as_global(y) + cb * O;     // dout[b][o] of this client
+
+    __shared__ __attribute__((aligned(16))) float As[kDK * kWS];   // As[o][k]
+    __shared__ float Bs[kDK * BS];                                 // Bs[o][b]
+
+    const int srow = tid >> 4, sc4 = 4 * (tid & 15);   // W: rows srow, srow + 16; 4 columns from sc4
+    const bool kok = kbase + sc4 < K;
+    const int oo = tid & 31, brow = tid >> 5;          // dout: unit oo of the chunk, samples brow + 8 i
+
+    f4 acc[NBT];
+#pragma unroll
+    for (int n = 0; n < NBT; ++n) acc[n] = f4{0.f, 0.f, 0.f, 0.f};
+
+    for (int o0 = 0; o0 < O; o0 += kDK) {
+        __syncthreads();
+        f4 va[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int o = o0 + srow + 16 * i;
+            const bool ok = kok && o < O;
+            va[i] = *reinterpret_cast<gv4>(W + (ok ? (int64_t)o * K + kbase + sc4 : 0));
+            if (!ok) va[i] = f4{0.f, 0.f, 0.f, 0.f};
+        }
+        float vb[2 * NBT];
+#pragma unroll
+        for (int i = 0; i < 2 * NBT; ++i) {
+            const int b = bbase + brow + 8 * i;
+            const bool ok = o0 + oo < O && b < B;
+            vb[i] = yd[ok ? (int64_t)b * O + o0 + oo : 0];
+            if (!ok) vb[i] = 0.f;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *reinterpret_cast<f4 *>(&As[(srow + 16 * i) * kWS + sc4]) = va[i];
+#pragma unroll
+        for (int i = 0; i < 2 * NBT; ++i) Bs[oo * BS + brow + 8 * i] = vb[i];
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < kDK / 4; ++s) {
+            const float a = As[(4 * s + lg) * kWS + 16 * wave + li];
+#pragma unroll
+            for (int n = 0; n < NBT; ++n)
+                acc[n] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, Bs[(4 * s + lg) * BS + 16 * n + li], acc[n], 0, 0, 0);
+        }
+    }
+
+    // lane: k = kbase + 16 wave + 4 lg .. + 3, sample b = bbase + 16 n + li
+    const int k = kbase + 16 * wave + 4 * lg;
+    if (k < K) {
+#pragma unroll
+        for (int n = 0; n < NBT; ++n) {
+            const int b = bbase + 16 * n + li;
+            if (b < B) {
+                const int64_t i = (cb + b) * K + k;
+                f4 v = acc[n];
+                if (mask_src) {
+                    const f4 mk = *reinterpret_cast<gv4>(as_global(mask_src) + i);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r)
+                        if (!(mk[r] > 0.f)) v[r] = 0.f;
+                }
+                *reinterpret_cast<gw4>(as_global(z) + i) = v;
+            }
+        }
+    }
+}
+
 // Forward pass of a layer with few output tiles (small mini-batch, moderate width): one
 // workgroup per 16 x 16 output tile, its 4 waves split the contraction (wave w takes the
 // 16-wide chunks w, w+4, ...) and feed the matrix cores straight from global memory: lane
@@ -358,7 +444,13 @@ hipError_t launch_dense_mfma(hipStream_t s, Profiler *prof, int mode, const Roun
             k_dense_fwd_direct<false><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
     } else if (mode == DENSE_FWD)
         k_dense_mfma<DENSE_FWD, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
-    else if (mode == DENSE_BWD_DATA)
+    else if (mode == DENSE_BWD_DATA && (K & 3) == 0 && (w_off & 3) == 0) {
+        const int nbt = B <= 16 ? 1 : B <= 32 ? 2 : 4;
+        dim3 dgrid((unsigned)((K + kDT - 1) / kDT), (unsigned)((B + 16 * nbt - 1) / (16 * nbt)), (unsigned)nact);
+        if (nbt == 1) k_dense_dgrad<1><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, x, z, mask_src);
+        else if (nbt == 2) k_dense_dgrad<2><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, x, z, mask_src);
+        else k_dense_dgrad<4><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, x, z, mask_src);
+    } else if (mode == DENSE_BWD_DATA)
         k_dense_mfma<DENSE_BWD_DATA, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
     else if ((K & 3) == 0 && (w_off & 3) == 0) {
         dim3 wgrid((unsigned)((K + kDT - 1) / kDT), (unsigned)((O + kDT - 1) / kDT), (unsigned)nact);
