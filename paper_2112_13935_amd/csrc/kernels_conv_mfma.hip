@@ -562,7 +562,8 @@ k_conv_wgrad_finish(const RoundParams *__restrict__ rp, int u, int B, WgradGeom 
     const int KP = 16 * g.NTT, OCP = 16 * g.MTT;
     const gcf_ptr pg = as_global(partial) + (int64_t)blockIdx.z * g.S * OCP * KP + (int64_t)co * KP + k;
     float s = 0.f;
-    for (int sl = 0; sl < g.S; ++sl) s += pg[(int64_t)sl * OCP * KP];
+#pragma unroll 8
+    for (int sl = 0; sl < g.S; ++sl) s += pg[(int64_t)sl * OCP * KP];   // loads in flight together, sum in order
     s *= 1.0f / (float)B;
     const int64_t wi = k < g.IC * KSQ ? g.w_off + (int64_t)co * g.IC * KSQ + k : g.b_off + co;
     as_global(p.W)[wi] -= p.eta * s;

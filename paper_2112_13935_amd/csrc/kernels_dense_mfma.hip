@@ -122,6 +122,7 @@ k_dense_mfma(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int
         if (blockIdx.x == 0 && tid < kDT && m0 + tid < O) {
             const int o = m0 + tid;
             float s = 0.f;
+#pragma unroll 8
             for (int b = 0; b < B; ++b) s += as_global(y)[(cb + b) * O + o];
             s *= invB;
             Wc[b_off + o] -= p.eta * s;
@@ -187,6 +188,7 @@ k_dense_wgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, in
     f4 acc[4];
 #pragma unroll
     for (int m = 0; m < 4; ++m) acc[m] = f4{0.f, 0.f, 0.f, 0.f};
+    float bsum = 0.f;
 
     for (int b0 = 0; b0 < B; b0 += kDK) {
         __syncthreads();
@@ -231,6 +233,12 @@ k_dense_wgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, in
             for (int m = 0; m < 4; ++m)
                 acc[m] = __builtin_amdgcn_mfma_f32_16x16x4f32(As[(4 * s + lg) * kWS + 16 * m + li], b, acc[m], 0, 0, 0);
         }
+        // bias gradient: the first k block sums the staged dout over the mini-batch (rows
+        // beyond the mini-batch are zero)
+        if (blockIdx.x == 0 && tid < kDT) {
+#pragma unroll
+            for (int b = 0; b < kDK; ++b) bsum += Bs[b * kWS + tid];
+        }
     }
 
     // lane: output unit o = obase + 16 wave + li, k = kbase + 16 m + 4 lg .. + 3
@@ -253,12 +261,9 @@ k_dense_wgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, in
             }
         }
     }
-    // bias: the first k block sums dout over the mini-batch
     if (blockIdx.x == 0 && tid < kDT && obase + tid < O) {
         const int ob = obase + tid;
-        float sb = 0.f;
-        for (int b = 0; b < B; ++b) sb += yd[(int64_t)b * O + ob];
-        sb *= invB;
+        const float sb = bsum * invB;
         Wc[b_off + ob] -= p.eta * sb;
         Uc[b_off + ob] += sb;
     }
