@@ -361,17 +361,24 @@ k_dense_dgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, in
 // (li, lg) loads the four consecutive k = 16c + 4lg .. 4lg+3 of row li of both operands, and
 // product r of the chunk contracts the r-th of them (the order of k inside a chunk is free
 // as long as both operands agree).  The four partial tiles are added in wave order in LDS.
-template <bool VEC>
+// MB: 16-sample tiles per workgroup (1 or 4); the tiles share the loads of the weight rows.
+template <bool VEC, int MB>
 __global__ void __launch_bounds__(256)
 k_dense_fwd_direct(const RoundParams *__restrict__ rp, int u, int B, int K, int O, int64_t w_off,
                    int64_t b_off, int relu, const float *__restrict__ x, float *__restrict__ z) {
     const RoundParams p = rp[blockIdx.z];
     if (u >= p.m) return;
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, li = lane & 15, lg = lane >> 4;
-    const int n0 = blockIdx.x * 16, m0 = blockIdx.y * 16;
+    const int n0 = blockIdx.x * 16, m0 = blockIdx.y * 16 * MB;
     const int64_t cb = (int64_t)blockIdx.z * B;
-    const bool arow = m0 + li < B, brow = n0 + li < O;
-    const gcf_ptr ap = as_global(x) + (cb + (arow ? m0 + li : 0)) * K + 4 * lg;
+    const bool brow = n0 + li < O;
+    bool arow[MB];
+    gcf_ptr ap[MB];
+#pragma unroll
+    for (int t = 0; t < MB; ++t) {
+        arow[t] = m0 + 16 * t + li < B;
+        ap[t] = as_global(x) + (cb + (arow[t] ? m0 + 16 * t + li : 0)) * K + 4 * lg;
+    }
     const gcf_ptr bp = as_global(p.W) + w_off + (int64_t)(brow ? n0 + li : 0) * K + 4 * lg;
     typedef const f4 __attribute__((address_space(1))) *gv4;
 
@@ -388,32 +395,42 @@ k_dense_fwd_direct(const RoundParams *__restrict__ rp, int u, int B, int K, int 
         return v;
     };
 
-    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    f4 acc[MB];
+#pragma unroll
+    for (int t = 0; t < MB; ++t) acc[t] = f4{0.f, 0.f, 0.f, 0.f};
     constexpr int UN = 4;   // chunks in flight per wave
     const int nchunk = (K + 15) / 16;
     for (int c0 = wave; c0 < nchunk; c0 += 4 * UN) {
-        f4 a[UN], b[UN];
+        f4 a[UN][MB], b[UN];
 #pragma unroll
         for (int j = 0; j < UN; ++j) {
             const int c = c0 + 4 * j;
-            a[j] = f4{0.f, 0.f, 0.f, 0.f};
-            b[j] = a[j];
+            b[j] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < MB; ++t) a[j][t] = b[j];
             if (c < nchunk) {
-                a[j] = load(ap + 16 * c, arow, 16 * c + 4 * lg);
+#pragma unroll
+                for (int t = 0; t < MB; ++t) a[j][t] = load(ap[t] + 16 * c, arow[t], 16 * c + 4 * lg);
                 b[j] = load(bp + 16 * c, brow, 16 * c + 4 * lg);
             }
         }
 #pragma unroll
         for (int j = 0; j < UN; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][r], b[j][r], acc, 0, 0, 0);
-    }
-    __shared__ float part[4][16][17];
+            for (int r = 0; r < 4; ++r)
 #pragma unroll
-    for (int r = 0; r < 4; ++r) part[wave][4 * lg + r][li] = acc[r];   // (sample, feature)
+                for (int t = 0; t < MB; ++t)
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[j][t][r], b[j][r], acc[t], 0, 0, 0);
+    }
+    __shared__ float part[4][16 * MB][17];
+#pragma unroll
+    for (int t = 0; t < MB; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[wave][16 * t + 4 * lg + r][li] = acc[t][r];   // (sample, feature)
     __syncthreads();
-    {
-        const int b = tid >> 4, o = tid & 15;   // 256 threads = the 16 x 16 tile
+#pragma unroll
+    for (int t = 0; t < MB; ++t) {
+        const int b = 16 * t + (tid >> 4), o = tid & 15;   // 256 threads = one 16 x 16 tile
         if (m0 + b < B && n0 + o < O) {
             float v = as_global(p.W)[b_off + n0 + o];
             v += part[0][b][o];
@@ -440,13 +457,18 @@ hipError_t launch_dense_mfma(hipStream_t s, Profiler *prof, int mode, const Roun
     const bool timed = prof && prof->on[fam];
     if (timed) prof->before(fam, s);
     if (mode == DENSE_FWD && narrow) {
-        dim3 dgrid((unsigned)((N + 15) / 16), (unsigned)((M + 15) / 16), (unsigned)nact);
         // float4 loads need 16-byte aligned rows: K a multiple of 4 (all offsets are multiples
         // of 64 floats otherwise) and the parameter offset a multiple of 4
-        if ((K & 3) == 0 && (w_off & 3) == 0)
-            k_dense_fwd_direct<true><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
-        else
-            k_dense_fwd_direct<false><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
+        const bool vec = (K & 3) == 0 && (w_off & 3) == 0;
+        if (M > 16) {
+            dim3 dgrid((unsigned)((N + 15) / 16), (unsigned)((M + 63) / 64), (unsigned)nact);
+            if (vec) k_dense_fwd_direct<true, 4><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
+            else k_dense_fwd_direct<false, 4><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
+        } else {
+            dim3 dgrid((unsigned)((N + 15) / 16), 1, (unsigned)nact);
+            if (vec) k_dense_fwd_direct<true, 1><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
+            else k_dense_fwd_direct<false, 1><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
+        }
     } else if (mode == DENSE_FWD)
         k_dense_mfma<DENSE_FWD, 4><<<grid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, y, z, mask_src);
     else if (mode == DENSE_BWD_DATA && (K & 3) == 0 && (w_off & 3) == 0) {
