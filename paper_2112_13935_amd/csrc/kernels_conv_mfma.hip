@@ -31,7 +31,6 @@ __device__ __forceinline__ f4 mfma16x16x4(float a, float b, f4 c) {
 }
 
 constexpr int kCch = 8;    // source channels per K chunk, at most (layers with fewer use 1, 2 or 4)
-constexpr int kStage = 8;  // global loads in flight per thread while a tile is staged
 
 struct ConvDir {
     int SC, DC;          // source / destination channels
@@ -162,62 +161,60 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     }
     const uint32_t bcstep = (uint32_t)(g.ic * KSQ);
 
+    // All loads of a chunk (source tile and weights) are issued before the first of them is
+    // stored to LDS: one memory round trip per chunk.
+    constexpr int NWL = (nd + WG_ - 1) / WG_;            // forward: destination channels per thread
+    constexpr int NWV = BWD ? NPB * CCH : NWL;
     for (int c0 = 0; c0 < g.SC; c0 += CCH) {
-        __syncthreads();
-        {
-            float v[3][CCH];
+        __syncthreads();   // the products of the previous chunk are done with the tiles
+        float sv[3][CCH], wv[NWV];
 #pragma unroll
-            for (int i = 0; i < 3; ++i)
-                if (i < g.npos) {
+        for (int i = 0; i < 3; ++i)
+            if (i < g.npos) {
 #pragma unroll
-                    for (int c = 0; c < CCH; ++c)
-                        v[i][c] = sg[(sok[i] && c0 + c < g.SC) ? soff[i] + (uint32_t)(c0 + c) * shw : 0u];
-                }
-#pragma unroll
-            for (int i = 0; i < 3; ++i)
-                if (i < g.npos && tid + 256 * i < tile_plane) {
-#pragma unroll
-                    for (int c = 0; c < CCH; ++c)
-                        Ssm[c * PL + tid + 256 * i] = (sok[i] && c0 + c < g.SC) ? v[i][c] : 0.f;
-                }
-        }
+                for (int c = 0; c < CCH; ++c)
+                    sv[i][c] = sg[(sok[i] && c0 + c < g.SC) ? soff[i] + (uint32_t)(c0 + c) * shw : 0u];
+            }
         if (BWD) {
 #pragma unroll
-            for (int i0 = 0; i0 < NPB; i0 += 3) {
-                float v[3][CCH];
+            for (int i = 0; i < NPB; ++i)
 #pragma unroll
-                for (int i = i0; i < i0 + 3 && i < NPB; ++i)
+                for (int c = 0; c < CCH; ++c) {
+                    const bool ok = boff[BWD ? i : 0] != 0xffffffffu && c0 + c < g.SC;
+                    wv[BWD ? i * CCH + c : 0] = wg[ok ? boff[BWD ? i : 0] + (uint32_t)(c0 + c) * bcstep : 0u];
+                }
+        } else {
+            const int lim = (wactive && wreal && c0 + wc < g.SC) ? dlim : 0;
+            const uint32_t q = wbase + (uint32_t)c0 * KSQ;
+#pragma unroll
+            for (int j = 0; j < NWL; ++j) {
+                const int d = wd0 + WG_ * j;
+                wv[BWD ? 0 : j] = wg[d < lim ? q + (uint32_t)d * wdstep : 0u];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 3; ++i)
+            if (i < g.npos && tid + 256 * i < tile_plane) {
+#pragma unroll
+                for (int c = 0; c < CCH; ++c)
+                    Ssm[c * PL + tid + 256 * i] = (sok[i] && c0 + c < g.SC) ? sv[i][c] : 0.f;
+            }
+        if (BWD) {
+#pragma unroll
+            for (int i = 0; i < NPB; ++i)
+                if (blds[BWD ? i : 0] >= 0) {
 #pragma unroll
                     for (int c = 0; c < CCH; ++c) {
                         const bool ok = boff[BWD ? i : 0] != 0xffffffffu && c0 + c < g.SC;
-                        v[i - i0][c] = wg[ok ? boff[BWD ? i : 0] + (uint32_t)(c0 + c) * bcstep : 0u];
+                        Wsm[blds[BWD ? i : 0] + kcol(c, 0)] = ok ? wv[BWD ? i * CCH + c : 0] : 0.f;
                     }
-#pragma unroll
-                for (int i = i0; i < i0 + 3 && i < NPB; ++i)
-                    if (blds[BWD ? i : 0] >= 0) {
-#pragma unroll
-                        for (int c = 0; c < CCH; ++c) {
-                            const bool ok = boff[BWD ? i : 0] != 0xffffffffu && c0 + c < g.SC;
-                            Wsm[blds[BWD ? i : 0] + kcol(c, 0)] = ok ? v[i - i0][c] : 0.f;
-                        }
-                    }
-            }
+                }
         } else if (wactive) {
-            const bool cok = wreal && c0 + wc < g.SC;
-            const int lim = cok ? dlim : 0;
-            const uint32_t q = wbase + (uint32_t)c0 * KSQ;
-            for (int d0 = wd0; d0 < nd; d0 += WG_ * kStage) {
-                float v[kStage];
+            const int lim = (wreal && c0 + wc < g.SC) ? dlim : 0;
 #pragma unroll
-                for (int j = 0; j < kStage; ++j) {
-                    const int d = d0 + WG_ * j;
-                    v[j] = wg[d < lim ? q + (uint32_t)d * wdstep : 0u];
-                }
-#pragma unroll
-                for (int j = 0; j < kStage; ++j) {
-                    const int d = d0 + WG_ * j;
-                    if (d < nd) Wsm[d * KCHP + wcol] = d < lim ? v[j] : 0.f;
-                }
+            for (int j = 0; j < NWL; ++j) {
+                const int d = wd0 + WG_ * j;
+                if (d < nd) Wsm[d * KCHP + wcol] = d < lim ? wv[BWD ? 0 : j] : 0.f;
             }
         }
         __syncthreads();
