@@ -382,6 +382,9 @@ struct WgradGeom {
     int64_t in_size, out_size, w_off, b_off;
 };
 
+// dword 3 of a raw buffer descriptor for 32-bit untyped accesses on this part
+constexpr int kBufferFlags = 0x00020000;
+
 constexpr int kPreIn = 32;  // input-tile elements one thread carries from one work item to the next
 constexpr int kPreD = 16;   // the same for the d(output) tile
 
@@ -407,23 +410,25 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
 
     extern __shared__ float smem[];
     const int plane = g.rowsT * g.SWP;
-    float *Ism = smem;                       // [IC + 3][rowsT][SWP]; plane IC = ones, IC+1 = zeros, IC+2 = dump
-    float *Dsm = Ism + (g.IC + 3) * plane;   // [16*MTS + 1][DPL]; the last row is a dump
+    const int CP = g.gin * g.nq_in_all;      // channel planes the staging threads write (>= IC)
+    const int DR = g.gd * g.nq_d_all;        // d(output) rows they write (>= 16*MTS)
+    float *Ism = smem;                       // [CP + 3][rowsT][SWP]; plane CP = ones, CP+1 = zeros, CP+2 = dump
+    float *Dsm = Ism + (CP + 3) * plane;     // [DR + 1][DPL]; the last row is a dump
     const int dplane = g.R * g.OWP;
 
-    for (int e = tid; e < 2 * plane; e += 256) Ism[g.IC * plane + e] = e < plane ? 1.f : 0.f;
+    for (int e = tid; e < 2 * plane; e += 256) Ism[CP * plane + e] = e < plane ? 1.f : 0.f;
 
     // B operand: lane li of N tile nt holds column k = 16*nt + li of the GEMM
     int kb[NTW];
 #pragma unroll
     for (int j = 0; j < NTW; ++j) {
         const int k = 16 * (n0 + NS * j) + li;
-        int off = (g.IC + 1) * plane;  // zeros
+        int off = (CP + 1) * plane;  // zeros
         if (k < g.IC * KS * KS) {
             const int c = k / (KS * KS), r = k - c * KS * KS;
             off = c * plane + (r / KS) * g.SWP + (r % KS);
         } else if (k == g.IC * KS * KS) {
-            off = g.IC * plane;        // ones
+            off = CP * plane;        // ones
         }
         kb[j] = off + lg;
     }
@@ -437,46 +442,53 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
 #pragma unroll
         for (int j = 0; j < NTW; ++j) acc[m][j] = f4{0.f, 0.f, 0.f, 0.f};
 
-    // This thread's position in the input tile and in the d(output) tile.  Threads beyond
-    // the last whole channel group, and a thread's turns beyond the last channel, load a
-    // valid dummy element and store to the dump areas: the staging code has no branches.
+    // This thread's position in the input tile and in the d(output) tile.  The tiles are
+    // fetched with range-checked buffer loads (one descriptor per sample): a lane outside
+    // the image asks for an offset beyond the sample and a turn beyond the last channel
+    // lands beyond it by itself; both read zero without touching memory, so the staging code
+    // has no branches and no selects.  Threads beyond the last whole channel group store to a
+    // dump area.
     const int gin = g.gin;                       // channel groups walking the input tile
     const int ipos = tid % plane, igrp = tid / plane;
     const int ity = ipos / g.SWP, itx = ipos - ity * g.SWP;
     const bool ixok = igrp < gin && (unsigned)(itx - g.pad) < (unsigned)g.IW;
-    const int nq_in = igrp < gin ? (g.IC - igrp + gin - 1) / gin : 0;
     const int gd = g.gd;
     const int dpos = tid % dplane, dgrp = tid / dplane;
     const int dr = dpos / g.OWP, dx = dpos - dr * g.OWP;
     const bool dxok = dgrp < gd && dx < g.OW;
-    const int nq_d = dgrp < gd ? (16 * g.MTS - dgrp + gd - 1) / gd : 0;
-    const int nq_d_real = dgrp < gd && dgrp < g.OC ? (g.OC - dgrp + gd - 1) / gd : 0;  // rows below OC
     const uint32_t ihw = (uint32_t)(g.IH * g.IW), ohw = (uint32_t)(g.OH * g.OW);
+    const uint32_t icstep = 4u * (uint32_t)gin * ihw, dcstep = 4u * (uint32_t)gd * ohw;   // bytes per turn
+    const int isbase = igrp < gin ? igrp * plane + ipos : (CP + 2) * plane + ipos;
+    const int isstep = igrp < gin ? gin * plane : 0;
+    const int dsbase = dgrp < gd ? dgrp * g.DPL + dpos : DR * g.DPL + dpos;
+    const int dsstep = dgrp < gd ? gd * g.DPL : 0;
+    constexpr uint32_t kNowhere = 0x80000000u;   // an offset no sample reaches
 
     // the fetched elements stay untouched in registers until they go to LDS (nothing waits
-    // for a load before the products start); ilim / dlim say how many of them are real
+    // for a load before the products start)
     float pin[kPreIn], pd[kPreD];
-    int ilim = 0, dlim = 0;
     const int items = B * g.items_per_sample;
     auto fetch = [&](int it) {
         const int b = it / g.items_per_sample, rb = it - b * g.items_per_sample;
         const int y0 = rb * g.R;
         const int64_t sample = (int64_t)blockIdx.z * B + b;
-        const gcf_ptr sin = as_global(in) + sample * g.in_size;       // uniform bases,
-        const gcf_ptr sd = as_global(dout) + sample * g.out_size;     // 32-bit offsets per thread
+        const __amdgpu_buffer_rsrc_t rin = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(in) + sample * g.in_size, 0, (int)(4 * g.in_size), kBufferFlags);
+        const __amdgpu_buffer_rsrc_t rd = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(dout) + sample * g.out_size, 0, (int)(4 * g.out_size), kBufferFlags);
         const int sy = y0 + ity - g.pad;
         const bool iok = ixok && (unsigned)sy < (unsigned)g.IH;
-        const uint32_t ioff = iok ? (uint32_t)igrp * ihw + (uint32_t)(sy * g.IW + (itx - g.pad)) : 0u;
-        ilim = iok ? nq_in : 0;
+        const uint32_t ivo = iok ? 4u * ((uint32_t)igrp * ihw + (uint32_t)(sy * g.IW + (itx - g.pad))) : kNowhere;
 #pragma unroll
         for (int q = 0; q < kPreIn; ++q)
-            if (q < g.nq_in_all) pin[q] = sin[q < ilim ? ioff + (uint32_t)(q * gin) * ihw : 0u];
+            if (q < g.nq_in_all)
+                pin[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rin, (int)(ivo + (uint32_t)q * icstep), 0, 0));
         const bool dok = dxok && y0 + dr < g.OH;
-        const uint32_t doff = dok ? (uint32_t)dgrp * ohw + (uint32_t)((y0 + dr) * g.OW + dx) : 0u;
-        dlim = dok ? nq_d_real : 0;
+        const uint32_t dvo = dok ? 4u * ((uint32_t)dgrp * ohw + (uint32_t)((y0 + dr) * g.OW + dx)) : kNowhere;
 #pragma unroll
         for (int q = 0; q < kPreD; ++q)
-            if (q < g.nq_d_all) pd[q] = sd[q < dlim ? doff + (uint32_t)(q * gd) * ohw : 0u];
+            if (q < g.nq_d_all)
+                pd[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rd, (int)(dvo + (uint32_t)q * dcstep), 0, 0));
     };
 
     const int xsteps = g.OWP >> 2, nsteps = g.R * xsteps;
@@ -499,12 +511,10 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
         __syncthreads();   // the products of the previous item are done with the tiles
 #pragma unroll
         for (int q = 0; q < kPreIn; ++q)
-            if (q < g.nq_in_all)
-                Ism[(q < nq_in ? igrp + gin * q : g.IC + 2) * plane + ipos] = q < ilim ? pin[q] : 0.f;
+            if (q < g.nq_in_all) Ism[isbase + q * isstep] = pin[q];
 #pragma unroll
         for (int q = 0; q < kPreD; ++q)
-            if (q < g.nq_d_all)
-                Dsm[(q < nq_d ? dgrp + gd * q : 16 * g.MTS) * g.DPL + dpos] = q < dlim ? pd[q] : 0.f;
+            if (q < g.nq_d_all) Dsm[dsbase + q * dsstep] = pd[q];
         __syncthreads();
         if (it + g.S < items) fetch(it + g.S);   // in flight while the products run
         // One step = 4 consecutive pixels of a row.  Two operand sets take turns: the set of
@@ -591,6 +601,7 @@ static bool wgrad_geom(const LayerGeom &L, int B, int nact, WgradGeom *g) {
     g->NTT = (g->KTOT + 15) / 16;
     g->MTT = (L.oc + 15) / 16;
     if (g->MTT > 4 || g->NTT > 40) return false;
+    if (L.in_size >= (int64_t)1 << 28 || L.out_size >= (int64_t)1 << 28) return false;   // 32-bit byte offsets
     g->R = L.oh < 4 ? L.oh : 4;
     g->rowsT = g->R + KS - 1;
     g->OWP = (L.ow + 3) / 4 * 4;
@@ -615,7 +626,7 @@ static int wgrad_ntw(const WgradGeom &g) {
     return n <= 2 ? 2 : n <= 5 ? 5 : 10;
 }
 static size_t wgrad_lds_bytes(const WgradGeom &g) {
-    return sizeof(float) * ((size_t)(g.IC + 3) * g.rowsT * g.SWP + (size_t)(16 * g.MTS + 1) * g.DPL);
+    return sizeof(float) * ((size_t)(g.gin * g.nq_in_all + 3) * g.rowsT * g.SWP + (size_t)(g.gd * g.nq_d_all + 1) * g.DPL);
 }
 
 bool conv_wgrad_mfma_supported(const LayerGeom &L, int B) {
