@@ -30,6 +30,10 @@ __device__ __forceinline__ f4 mfma16x16x4(float a, float b, f4 c) {
     return __builtin_amdgcn_mfma_f32_16x16x4f32(a, b, c, 0, 0, 0);
 }
 
+// dword 3 of a raw buffer descriptor for 32-bit untyped accesses on this part
+constexpr int kBufferFlags = 0x00020000;
+constexpr uint32_t kNowhere = 0x80000000u;   // a byte offset no buffer here reaches: reads as zero
+
 constexpr int kCch = 8;    // source channels per K chunk, at most (layers with fewer use 1, 2 or 4)
 
 struct ConvDir {
@@ -77,8 +81,15 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     const int y0 = rblk * g.R;
     const int dc0 = nblk * 16 * NT;
     const int64_t sample = (int64_t)blockIdx.z * B + blockIdx.y;
-    const gcf_ptr sg = as_global(src) + sample * g.src_size;   // uniform base, 32-bit offsets per thread
-    const gcf_ptr wg = as_global(p.W) + g.w_off;
+    // range-checked buffers: the sample's source planes and the layer's weights; an offset
+    // beyond them (kNowhere, or a channel beyond the last) reads zero without touching memory
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float *>(src) + sample * g.src_size, 0, (int)(4 * g.src_size), kBufferFlags);
+    const __amdgpu_buffer_rsrc_t rw = __builtin_amdgcn_make_buffer_rsrc(
+        p.W + g.w_off, 0, 4 * g.ic * g.oc * KS * KS, kBufferFlags);
+    auto bload = [](__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+        return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
+    };
 
     extern __shared__ float smem[];
     const int tile_plane = g.rowsT * g.SWP;
@@ -114,7 +125,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     // up to 3 positions of the source tile and walks the chunk's channels, and to one K
     // element of the weight chunk and walks the destination channels; what lies outside is
     // loaded from a valid dummy address and replaced by zero when it goes to LDS.
-    const uint32_t shw = (uint32_t)(g.SH * g.SW);
+    const uint32_t shw = 4u * (uint32_t)(g.SH * g.SW);   // bytes per source channel
     uint32_t soff[3];
     bool sok[3];
 #pragma unroll
@@ -123,7 +134,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
         const int ty = pos / g.SWP, tx = pos - ty * g.SWP;
         const int sy = y0 + ty - g.P, sx = tx - g.P;
         sok[i] = pos < tile_plane && (unsigned)sy < (unsigned)g.SH && (unsigned)sx < (unsigned)g.SW;
-        soff[i] = sok[i] ? (uint32_t)(sy * g.SW + sx) : 0u;
+        soff[i] = sok[i] ? 4u * (uint32_t)(sy * g.SW + sx) : kNowhere;   // byte offset in the sample
     }
     // Weights of a chunk, Wsm[d][k].  Threads follow the memory order, so that a wave's loads
     // are consecutive addresses, and scatter into the K order of the chunk in LDS.
@@ -173,7 +184,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
             if (i < g.npos) {
 #pragma unroll
                 for (int c = 0; c < CCH; ++c)
-                    sv[i][c] = sg[(sok[i] && c0 + c < g.SC) ? soff[i] + (uint32_t)(c0 + c) * shw : 0u];
+                    sv[i][c] = bload(rs, soff[i] + (uint32_t)(c0 + c) * shw);   // channels beyond SC lie beyond the sample
             }
         if (BWD) {
 #pragma unroll
@@ -181,7 +192,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
 #pragma unroll
                 for (int c = 0; c < CCH; ++c) {
                     const bool ok = boff[BWD ? i : 0] != 0xffffffffu && c0 + c < g.SC;
-                    wv[BWD ? i * CCH + c : 0] = wg[ok ? boff[BWD ? i : 0] + (uint32_t)(c0 + c) * bcstep : 0u];
+                    wv[BWD ? i * CCH + c : 0] = bload(rw, ok ? 4u * (boff[BWD ? i : 0] + (uint32_t)(c0 + c) * bcstep) : kNowhere);
                 }
         } else {
             const int lim = (wactive && wreal && c0 + wc < g.SC) ? dlim : 0;
@@ -189,7 +200,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
 #pragma unroll
             for (int j = 0; j < NWL; ++j) {
                 const int d = wd0 + WG_ * j;
-                wv[BWD ? 0 : j] = wg[d < lim ? q + (uint32_t)d * wdstep : 0u];
+                wv[BWD ? 0 : j] = bload(rw, d < lim ? 4u * (q + (uint32_t)d * wdstep) : kNowhere);
             }
         }
 #pragma unroll
@@ -197,24 +208,20 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
             if (i < g.npos && tid + 256 * i < tile_plane) {
 #pragma unroll
                 for (int c = 0; c < CCH; ++c)
-                    Ssm[c * PL + tid + 256 * i] = (sok[i] && c0 + c < g.SC) ? sv[i][c] : 0.f;
+                    Ssm[c * PL + tid + 256 * i] = sv[i][c];
             }
         if (BWD) {
 #pragma unroll
             for (int i = 0; i < NPB; ++i)
                 if (blds[BWD ? i : 0] >= 0) {
 #pragma unroll
-                    for (int c = 0; c < CCH; ++c) {
-                        const bool ok = boff[BWD ? i : 0] != 0xffffffffu && c0 + c < g.SC;
-                        Wsm[blds[BWD ? i : 0] + kcol(c, 0)] = ok ? wv[BWD ? i * CCH + c : 0] : 0.f;
-                    }
+                    for (int c = 0; c < CCH; ++c) Wsm[blds[BWD ? i : 0] + kcol(c, 0)] = wv[BWD ? i * CCH + c : 0];
                 }
         } else if (wactive) {
-            const int lim = (wreal && c0 + wc < g.SC) ? dlim : 0;
 #pragma unroll
             for (int j = 0; j < NWL; ++j) {
                 const int d = wd0 + WG_ * j;
-                if (d < nd) Wsm[d * KCHP + wcol] = d < lim ? wv[BWD ? 0 : j] : 0.f;
+                if (d < nd) Wsm[d * KCHP + wcol] = wv[BWD ? 0 : j];
             }
         }
         __syncthreads();
@@ -322,7 +329,7 @@ static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d) {
     d->PL = tile_plane + ((16 - tile_plane % 32 + 32) % 32);
     d->npos = (tile_plane + 255) / 256;
     if (d->npos > 3) return false;
-    if (d->src_size >= (int64_t)1 << 31 || (int64_t)L.oc * L.ic * KS * KS >= (int64_t)1 << 31) return false;
+    if (d->src_size >= (int64_t)1 << 28 || (int64_t)L.oc * L.ic * KS * KS >= (int64_t)1 << 28) return false;   // 32-bit byte offsets
     return true;
 }
 
@@ -381,9 +388,6 @@ struct WgradGeom {
     int nq_in_all, nq_d_all;  // the longest walks: channels per input group, rows per d(output) group
     int64_t in_size, out_size, w_off, b_off;
 };
-
-// dword 3 of a raw buffer descriptor for 32-bit untyped accesses on this part
-constexpr int kBufferFlags = 0x00020000;
 
 constexpr int kPreIn = 32;  // input-tile elements one thread carries from one work item to the next
 constexpr int kPreD = 16;   // the same for the d(output) tile
@@ -462,7 +466,6 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
     const int isstep = igrp < gin ? gin * plane : 0;
     const int dsbase = dgrp < gd ? dgrp * g.DPL + dpos : DR * g.DPL + dpos;
     const int dsstep = dgrp < gd ? gd * g.DPL : 0;
-    constexpr uint32_t kNowhere = 0x80000000u;   // an offset no sample reaches
 
     // the fetched elements stay untouched in registers until they go to LDS (nothing waits
     // for a load before the products start)
