@@ -99,6 +99,16 @@ def small_cases():
     cases["softmax_1024_columns"] = wl
     wl = W.config1(n_clients=2, n_per=40, d=513, rounds=3, a=2, b=2)
     cases["softmax_513_columns"] = wl
+    # layer engine, dense layers with 16-byte aligned rows (the float4 kernels) and mini-batches
+    # of 32 (two of four sample tiles real) and 64 (all four)
+    wl = W.config2(n_clients=3, n_total=3 * 90, d=52, hidden=24, batch=32, rounds=3, a=32, b=32)
+    cases["mlp_layers_aligned_b32"] = wl
+    wl = W.config2(n_clients=2, n_total=2 * 150, d=36, hidden=40, batch=64, rounds=3, a=64, b=64)
+    cases["mlp_layers_aligned_b64"] = wl
+    # convolutions with 6 and 12 channels on 12 x 12 images: ragged channel groups in the
+    # staging code, a pooling layer whose input rows are not 16-byte aligned (6 wide)
+    wl = W.config4(n_clients=2, n_per=30, hw=12, width=6, fc=16, batch=4, rounds=3, a=4, b=4)
+    cases["cnn12_six_channels"] = wl
     return cases
 
 
