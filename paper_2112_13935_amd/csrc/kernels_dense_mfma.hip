@@ -190,6 +190,21 @@ k_dense_wgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, in
     for (int m = 0; m < 4; ++m) acc[m] = f4{0.f, 0.f, 0.f, 0.f};
     float bsum = 0.f;
 
+    // lane: output unit o = obase + 16 wave + li, k = kbase + 16 m + 4 lg .. + 3.  Its weights
+    // and gradient sums are fetched now (nobody else touches them) and are there when the
+    // products are done: one memory round trip less at the end.
+    const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
+    const int o = obase + 16 * wave + li;
+    f4 wv[4], uv[4];
+#pragma unroll
+    for (int m = 0; m < 4; ++m) {
+        const int k = kbase + 16 * m + 4 * lg;
+        const bool ok = o < O && k < K;
+        const int64_t wi = ok ? w_off + (int64_t)o * K + k : w_off;
+        wv[m] = *reinterpret_cast<gv4>(Wc + wi);
+        uv[m] = *reinterpret_cast<gv4>(Uc + wi);
+    }
+
     for (int b0 = 0; b0 < B; b0 += kDK) {
         __syncthreads();
         f4 va[2];
@@ -241,10 +256,7 @@ k_dense_wgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, in
         }
     }
 
-    // lane: output unit o = obase + 16 wave + li, k = kbase + 16 m + 4 lg .. + 3
     const float invB = 1.0f / (float)B;
-    const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
-    const int o = obase + 16 * wave + li;
     if (o < O) {
 #pragma unroll
         for (int m = 0; m < 4; ++m) {
@@ -252,12 +264,8 @@ k_dense_wgrad(const RoundParams *__restrict__ rp, int u, int B, int K, int O, in
             if (k < K) {
                 const int64_t wi = w_off + (int64_t)o * K + k;
                 const f4 g = acc[m] * invB;
-                f4 w = *reinterpret_cast<gv4>(Wc + wi);
-                f4 uu = *reinterpret_cast<gv4>(Uc + wi);
-                w -= p.eta * g;
-                uu += g;
-                *reinterpret_cast<gw4>(Wc + wi) = w;
-                *reinterpret_cast<gw4>(Uc + wi) = uu;
+                *reinterpret_cast<gw4>(Wc + wi) = wv[m] - p.eta * g;
+                *reinterpret_cast<gw4>(Uc + wi) = uv[m] + g;
             }
         }
     }
