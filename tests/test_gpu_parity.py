@@ -105,6 +105,12 @@ def small_cases():
     cases["mlp_layers_aligned_b32"] = wl
     wl = W.config2(n_clients=2, n_total=2 * 150, d=36, hidden=40, batch=64, rounds=3, a=64, b=64)
     cases["mlp_layers_aligned_b64"] = wl
+    # dense layers with aligned rows and small mini-batches (one sample tile), narrow and wide
+    wl = W.config2(n_clients=5, n_total=5 * 60, d=36, hidden=20, batch=4, rounds=4, a=4, b=8)
+    wl.compute_factor = np.array([1, 2, 1, 1, 3], dtype=np.int32)
+    cases["mlp_layers_aligned_b4"] = wl
+    wl = W.config2(n_clients=3, n_total=3 * 80, d=256, hidden=120, batch=16, rounds=3, a=16, b=16)
+    cases["mlp_layers_256_120_b16"] = wl
     # convolutions with 6 and 12 channels on 12 x 12 images: ragged channel groups in the
     # staging code, a pooling layer whose input rows are not 16-byte aligned (6 wide)
     wl = W.config4(n_clients=2, n_per=30, hw=12, width=6, fc=16, batch=4, rounds=3, a=4, b=4)
