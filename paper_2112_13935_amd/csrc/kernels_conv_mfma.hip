@@ -123,8 +123,8 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
 
     // Staging without per-element index arithmetic and without branches: a thread is tied to
     // up to 3 positions of the source tile and walks the chunk's channels, and to one K
-    // element of the weight chunk and walks the destination channels; what lies outside is
-    // loaded from a valid dummy address and replaced by zero when it goes to LDS.
+    // element of the weight chunk and walks the destination channels; what lies outside asks
+    // the range-checked buffers for an offset beyond their end and comes back as zero.
     const uint32_t shw = 4u * (uint32_t)(g.SH * g.SW);   // bytes per source channel
     uint32_t soff[3];
     bool sok[3];
