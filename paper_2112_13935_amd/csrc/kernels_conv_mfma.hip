@@ -56,6 +56,8 @@ struct ConvDir {
 // CCH: source channels per K chunk (1, 2, 4 or 8: the smallest that holds the layer's source
 // channels, so that a 1- or 3-channel input does not multiply seven or five channels of zeros).
 // NT: N tiles (16 destination channels each) per workgroup: 1, 2 or 4.
+// NPOS: positions of the source tile one thread stages, at most: 1 (tiles of up to 256
+// positions, the common case: no loop, no spare registers) or 3.
 //
 // Order of the chunk's K elements.  CCH >= 4: k = ((cq*KS + ky)*KS + kx)*4 + c4, channel
 // 4*cq + c4: the four K elements of one matrix instruction are four channels at one filter
@@ -63,7 +65,7 @@ struct ConvDir {
 // wave.  CCH < 4: k = c*KS*KS + ky*KS + kx, each lane keeps the tile offsets of its K
 // elements in registers.  In both cases the operands of the next step are read from LDS
 // before the products of the current step are issued.
-template <int KS, bool BWD, int CCH, int NT>
+template <int KS, bool BWD, int CCH, int NT, int NPOS>
 __global__ void __launch_bounds__(256)
 k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const float *__restrict__ src,
             float *__restrict__ dst, const float *__restrict__ mask_src) {
@@ -126,10 +128,10 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     // element of the weight chunk and walks the destination channels; what lies outside asks
     // the range-checked buffers for an offset beyond their end and comes back as zero.
     const uint32_t shw = 4u * (uint32_t)(g.SH * g.SW);   // bytes per source channel
-    uint32_t soff[3];
-    bool sok[3];
+    uint32_t soff[NPOS];
+    bool sok[NPOS];
 #pragma unroll
-    for (int i = 0; i < 3; ++i) {
+    for (int i = 0; i < NPOS; ++i) {
         const int pos = tid + 256 * i;
         const int ty = pos / g.SWP, tx = pos - ty * g.SWP;
         const int sy = y0 + ty - g.P, sx = tx - g.P;
@@ -178,9 +180,9 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     constexpr int NWV = BWD ? NPB * CCH : NWL;
     for (int c0 = 0; c0 < g.SC; c0 += CCH) {
         __syncthreads();   // the products of the previous chunk are done with the tiles
-        float sv[3][CCH], wv[NWV];
+        float sv[NPOS][CCH], wv[NWV];
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
+        for (int i = 0; i < NPOS; ++i)
             if (i < g.npos) {
 #pragma unroll
                 for (int c = 0; c < CCH; ++c)
@@ -204,7 +206,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
             }
         }
 #pragma unroll
-        for (int i = 0; i < 3; ++i)
+        for (int i = 0; i < NPOS; ++i)
             if (i < g.npos && tid + 256 * i < tile_plane) {
 #pragma unroll
                 for (int c = 0; c < CCH; ++c)
@@ -356,14 +358,17 @@ hipError_t launch_conv_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp
     const int fam = bwd ? F_CONV_BWD_DATA : F_CONV_FWD;
     const bool timed = prof && prof->on[fam];
     if (timed) prof->before(fam, s);
-#define AET_CONV(KSv, CCHv, NTv)                                                                          \
-    if (L.k == KSv && d.CCH == CCHv && d.NT == NTv) {                                                   \
-        if (bwd) k_conv_mfma<KSv, true, CCHv, NTv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);  \
-        else k_conv_mfma<KSv, false, CCHv, NTv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);     \
+#define AET_CONV(KSv, CCHv, NTv, NPv)                                                                                \
+    if (L.k == KSv && d.CCH == CCHv && d.NT == NTv && np == NPv) {                                                  \
+        if (bwd) k_conv_mfma<KSv, true, CCHv, NTv, NPv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);  \
+        else k_conv_mfma<KSv, false, CCHv, NTv, NPv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);     \
     }
-#define AET_CONV_NT(KSv, CCHv) AET_CONV(KSv, CCHv, 1) AET_CONV(KSv, CCHv, 2) AET_CONV(KSv, CCHv, 4)
-    AET_CONV_NT(3, 1) AET_CONV_NT(3, 2) AET_CONV_NT(3, 4) AET_CONV_NT(3, 8)
-    AET_CONV_NT(5, 1) AET_CONV_NT(5, 2) AET_CONV_NT(5, 4) AET_CONV_NT(5, 8)
+#define AET_CONV_NT(KSv, CCHv, NPv) AET_CONV(KSv, CCHv, 1, NPv) AET_CONV(KSv, CCHv, 2, NPv) AET_CONV(KSv, CCHv, 4, NPv)
+    // tiles of up to 256 positions and at least 4 channels per chunk get the one-position kernel
+    const int np = (d.npos == 1 && d.CCH >= 4) ? 1 : 3;
+    AET_CONV_NT(3, 1, 3) AET_CONV_NT(3, 2, 3) AET_CONV_NT(3, 4, 3) AET_CONV_NT(3, 8, 3)
+    AET_CONV_NT(5, 1, 3) AET_CONV_NT(5, 2, 3) AET_CONV_NT(5, 4, 3) AET_CONV_NT(5, 8, 3)
+    AET_CONV_NT(3, 4, 1) AET_CONV_NT(3, 8, 1) AET_CONV_NT(5, 4, 1) AET_CONV_NT(5, 8, 1)
 #undef AET_CONV_NT
 #undef AET_CONV
     if (timed) prof->after(fam, s);
