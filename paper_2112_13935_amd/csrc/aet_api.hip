@@ -39,10 +39,9 @@ struct RoundRec {
 };
 
 struct Layout {
-    size_t w0, Wg, W, U, loss, params, arrivals, partial, debug, labels, fused, wgrad;
+    size_t w0, Wg, W, U, loss, params, arrivals, debug, labels, fused, wgrad;
     size_t act[AET_MAX_LAYERS + 1], del[AET_MAX_LAYERS + 1], amax[AET_MAX_LAYERS];
     size_t total;
-    int max_chunks;
 };
 
 std::string g_init_error;
@@ -118,8 +117,6 @@ bool make_layout(const LayerGeom *lay, int L, int64_t P, int B, int n, int infli
     lo->loss = take((size_t)n * rounds * 4);
     lo->params = take((size_t)n * sizeof(RoundParams));
     lo->arrivals = take((size_t)n * inflight * sizeof(Arrival));
-    lo->max_chunks = (n * inflight + 15) / 16;
-    lo->partial = take(Ps * 4 * (size_t)lo->max_chunks);
     lo->debug = take((size_t)kDebugIdx * 4);
     lo->labels = take((size_t)n * B * 4);
     lo->fused = take(mlp_round_scratch_bytes(n, B));
@@ -526,8 +523,7 @@ aet_status aet_server_aggregate(aet_ctx *ctx, float agg_scale, int32_t *n_applie
     if (by_value) {
         AET_HIP(ctx, launch_server_apply_small(ctx->stream, ctx->profp(), ctx->Wg(), *by_value, na, ctx->P));
     } else if (on_device) {
-        AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->profp(), ctx->Wg(), on_device, na, ctx->P,
-                                          reinterpret_cast<float *>(ctx->ws + ctx->lo.partial), ctx->lo.max_chunks));
+        AET_HIP(ctx, launch_server_reduce(ctx->stream, ctx->profp(), ctx->Wg(), on_device, na, ctx->P));
     }
     retire_arrivals(ctx, arr, n_applied, applied_client, applied_round);
     return AET_OK;

@@ -89,7 +89,7 @@ hipError_t launch_begin_round(hipStream_t s, Profiler *prof, const RoundParams *
 hipError_t launch_layer_step(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                              const LayerGeom *lay, int L, int B, const LayerScratch &sc);
 hipError_t launch_server_reduce(hipStream_t s, Profiler *prof, float *Wg, const Arrival *darr,
-                                int n_arr, int64_t P, float *partial, int max_chunks);
+                                int n_arr, int64_t P);
 hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, const ArrivalPack &pack,
                                      int n_arr, int64_t P);
 // Receive at the neighbours: replica r takes the arrivals whose sender is in nbr[nbr_off[r] ..
@@ -129,7 +129,5 @@ hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *hp
                             int n_clients, uint32_t *epoch);
 hipError_t mlp_clear_error_flag(hipStream_t s, void *scratch, int n_clients, int B);
 const int *mlp_error_flag_ptr(void *scratch, int n_clients, int B);
-// chunks of arrivals the two-stage server reduce uses for n_arr arrivals
-int server_reduce_chunks(int n_arr, int64_t P);
 
 }  // namespace aet

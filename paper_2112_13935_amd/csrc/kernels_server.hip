@@ -1,16 +1,16 @@
 // Receive (Algorithm 2), at the server and at the neighbours.
 // Server step (Receive in its client-server form):
 //   w_global <- w_global - sum over this tick's arrivals of (agg_scale * eta_k) * U_{k,c}.
-// The U's are streamed once from HBM.  With few arrivals a single pass applies them in
-// order; with many, the arrivals are cut into chunks that are summed in parallel
-// (each chunk in order) and the chunk sums are then applied in order, so the result does
-// not depend on how blocks are scheduled.
+// The U's are streamed once from HBM.  With few arrivals every thread applies them in order
+// to its own parameters; with many, a workgroup's thread groups each sum a contiguous part of
+// the list in order and the group sums are added in group order, so the result does not
+// depend on how blocks are scheduled.
 #include "aet_device.h"
 #include "aet_internal.h"
 
 namespace aet {
 
-constexpr int kChunk = 16;  // arrivals per chunk of the two-stage form
+constexpr int kFewArrivals = 32;  // up to here one thread walks the whole list
 
 typedef float sf4 __attribute__((ext_vector_type(4)));
 typedef const sf4 __attribute__((address_space(1))) *gcv4_ptr;
@@ -38,36 +38,47 @@ k_server_apply_small(float *__restrict__ Wg, ArrivalPack pack, int n_arr, int64_
     reinterpret_cast<sf4 *>(Wg)[i] = w;
 }
 
-__global__ void __launch_bounds__(256)
-k_server_partial(const Arrival *__restrict__ arr, int n_arr, int64_t nv, float *__restrict__ partial) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= nv) return;
-    const int j0 = blockIdx.y * kChunk;
-    sf4 u[kChunk];
-    float sc[kChunk];
-    // all loads of the chunk are in flight together; the sum keeps the list order
-#pragma unroll
-    for (int j = 0; j < kChunk; ++j) {
-        const bool in = j0 + j < n_arr;
-        const Arrival a = arr[in ? j0 + j : j0];
-        sc[j] = in ? a.scale : 0.f;
-        u[j] = reinterpret_cast<gcv4_ptr>(as_global(a.U))[i];
-    }
-    sf4 s = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int j = 0; j < kChunk; ++j)
-        if (j0 + j < n_arr) s += sc[j] * u[j];
-    reinterpret_cast<sf4 *>(partial)[(int64_t)blockIdx.y * nv + i] = s;
-}
+// Many arrivals in one pass: a workgroup owns 16 float4 columns of the model; its 16 thread
+// groups each sum a contiguous sixteenth of the arrival list in list order (8 loads in flight),
+// the group sums are added in group order in LDS and subtracted from the model.  No partial
+// sums in memory, no second kernel; the result does not depend on scheduling.
+constexpr int kOneCols = 16;   // float4 columns per workgroup
+constexpr int kOneGroups = 16; // arrival groups per workgroup
+constexpr int kOneFlight = 8;  // loads in flight per thread
 
 __global__ void __launch_bounds__(256)
-k_server_finish(float *__restrict__ Wg, const float *__restrict__ partial, int chunks, int64_t nv) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= nv) return;
-    sf4 w = reinterpret_cast<const sf4 *>(Wg)[i];
-#pragma unroll 8
-    for (int c = 0; c < chunks; ++c) w -= reinterpret_cast<const sf4 *>(partial)[(int64_t)c * nv + i];
-    reinterpret_cast<sf4 *>(Wg)[i] = w;
+k_server_reduce_one(float *__restrict__ Wg, const Arrival *__restrict__ arr, int n_arr, int64_t nv) {
+    const int tid = threadIdx.x, c = tid & (kOneCols - 1), grp = tid / kOneCols;
+    const int64_t i = (int64_t)blockIdx.x * kOneCols + c;
+    const bool valid = i < nv;
+    const int64_t ii = valid ? i : 0;
+    const int per = (n_arr + kOneGroups - 1) / kOneGroups;
+    const int j0 = grp * per, j1 = min(j0 + per, n_arr);
+    sf4 s = {0.f, 0.f, 0.f, 0.f};
+    for (int j = j0; j < j1; j += kOneFlight) {
+        sf4 u[kOneFlight];
+        float sc[kOneFlight];
+#pragma unroll
+        for (int q = 0; q < kOneFlight; ++q) {
+            const bool in = j + q < j1;
+            const Arrival a = arr[in ? j + q : j];
+            sc[q] = in ? a.scale : 0.f;
+            u[q] = reinterpret_cast<gcv4_ptr>(as_global(a.U))[ii];
+        }
+#pragma unroll
+        for (int q = 0; q < kOneFlight; ++q)
+            if (j + q < j1) s += sc[q] * u[q];
+    }
+    __shared__ sf4 red[kOneGroups][kOneCols];
+    red[grp][c] = s;
+    __syncthreads();
+    if (grp == 0 && valid) {
+        sf4 w = reinterpret_cast<const sf4 *>(Wg)[i];
+        sf4 t = red[0][c];
+#pragma unroll
+        for (int g = 1; g < kOneGroups; ++g) t += red[g][c];
+        reinterpret_cast<sf4 *>(Wg)[i] = w - t;
+    }
 }
 
 hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, const ArrivalPack &pack,
@@ -212,28 +223,16 @@ hipError_t launch_broadcast_model(hipStream_t s, float *W, int64_t Ps, int n_cli
     return hipGetLastError();
 }
 
-int server_reduce_chunks(int n_arr, int64_t P) {
-    (void)P;
-    return n_arr <= 2 * kChunk ? 1 : (n_arr + kChunk - 1) / kChunk;
-}
-
 hipError_t launch_server_reduce(hipStream_t s, Profiler *prof, float *Wg, const Arrival *darr,
-                                int n_arr, int64_t P, float *partial, int max_chunks) {
+                                int n_arr, int64_t P) {
     if (n_arr <= 0) return hipSuccess;
     const bool timed = prof && prof->on[F_SERVER_REDUCE];
     if (timed) prof->before(F_SERVER_REDUCE, s);
     const int64_t nv = (P + 63) / 64 * 16;   // float4s per padded model
-    const unsigned gx = (unsigned)((nv + 255) / 256);
-    const int chunks = server_reduce_chunks(n_arr, P);
-    if (chunks == 1 || chunks > max_chunks) {
-        k_server_apply<<<gx, 256, 0, s>>>(Wg, darr, n_arr, nv);
-        if (timed) prof->after(F_SERVER_REDUCE, s);
-        return hipGetLastError();
-    }
-    k_server_partial<<<dim3(gx, chunks), 256, 0, s>>>(darr, n_arr, nv, partial);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    k_server_finish<<<gx, 256, 0, s>>>(Wg, partial, chunks, nv);
+    if (n_arr <= kFewArrivals)
+        k_server_apply<<<(unsigned)((nv + 255) / 256), 256, 0, s>>>(Wg, darr, n_arr, nv);
+    else
+        k_server_reduce_one<<<(unsigned)((nv + kOneCols - 1) / kOneCols), 256, 0, s>>>(Wg, darr, n_arr, nv);
     if (timed) prof->after(F_SERVER_REDUCE, s);
     return hipGetLastError();
 }
