@@ -375,13 +375,37 @@ k_softmax_ce(const RoundParams *__restrict__ rp, int u, int B, int C,
         const float *z = logits + ((int64_t)blockIdx.x * B + b) * C;
         float *d = dz + ((int64_t)blockIdx.x * B + b) * C;
         const int lab = labels[(int64_t)blockIdx.x * B + b];
-        float zmax = z[0];
-        for (int j = 1; j < C; ++j) zmax = fmaxf(zmax, z[j]);
-        float sum = 0.f;
-        for (int j = 0; j < C; ++j) sum += expf(z[j] - zmax);
-        const float lse = zmax + logf(sum);
-        loss = lse - z[lab];
-        for (int j = 0; j < C; ++j) d[j] = expf(z[j] - lse) - (j == lab ? 1.f : 0.f);
+        if (C <= 16) {
+            // the row in registers: its loads travel together (one trip to memory, not C)
+            float zv[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j) zv[j] = z[j < C ? j : 0];
+            float zmax = zv[0];
+#pragma unroll
+            for (int j = 1; j < 16; ++j)
+                if (j < C) zmax = fmaxf(zmax, zv[j]);
+            float sum = 0.f;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (j < C) sum += expf(zv[j] - zmax);
+            const float lse = zmax + logf(sum);
+            float zl = zv[0];
+#pragma unroll
+            for (int j = 1; j < 16; ++j)
+                if (j == lab) zl = zv[j];
+            loss = lse - zl;
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                if (j < C) d[j] = expf(zv[j] - lse) - (j == lab ? 1.f : 0.f);
+        } else {
+            float zmax = z[0];
+            for (int j = 1; j < C; ++j) zmax = fmaxf(zmax, z[j]);
+            float sum = 0.f;
+            for (int j = 0; j < C; ++j) sum += expf(z[j] - zmax);
+            const float lse = zmax + logf(sum);
+            loss = lse - z[lab];
+            for (int j = 0; j < C; ++j) d[j] = expf(z[j] - lse) - (j == lab ? 1.f : 0.f);
+        }
     }
     sl[b] = loss;
     __syncthreads();
