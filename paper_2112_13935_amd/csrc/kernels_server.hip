@@ -167,17 +167,29 @@ k_apply_neighbour_U(float *__restrict__ W, int64_t Ps, const int32_t *__restrict
                 }
                 loaded = true;
             }
-            for (int s = 0; s < ns; ++s) {
-                const float *U = selU[s];
-                const float sc = selS[s];
+            // four arrivals at a time: their loads are in flight together (an element beyond
+            // the model reads the first one instead and is never stored), then they are applied
+            // in list order
+            for (int s0 = 0; s0 < ns; s0 += 4) {
+                nf4 u[4][kNbVec];
+                float sc[4];
 #pragma unroll
-                for (int v = 0; v < kNbVec; ++v) {
-                    const int64_t i = base + 1024 * v;
-                    if (i < Ps) {
-                        const nf4 u = *reinterpret_cast<const nf4 __attribute__((address_space(1))) *>(as_global(U) + i);
-                        w[v] -= sc * u;
+                for (int q = 0; q < 4; ++q) {
+                    const int s = s0 + q < ns ? s0 + q : s0;
+                    const float *U = selU[s];
+                    sc[q] = s0 + q < ns ? selS[s] : 0.f;
+#pragma unroll
+                    for (int v = 0; v < kNbVec; ++v) {
+                        const int64_t i = base + 1024 * v;
+                        u[q][v] = *reinterpret_cast<const nf4 __attribute__((address_space(1))) *>(as_global(U) + (i < Ps ? i : 0));
                     }
                 }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (s0 + q < ns) {
+#pragma unroll
+                        for (int v = 0; v < kNbVec; ++v) w[v] -= sc[q] * u[q][v];
+                    }
             }
         }
         __syncthreads();
