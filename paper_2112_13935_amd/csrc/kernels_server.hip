@@ -100,7 +100,8 @@ hipError_t launch_server_apply_small(hipStream_t s, Profiler *prof, float *Wg, c
 // ballot + prefix count); then every thread carries its parameters through them.
 // ---------------------------------------------------------------------------------------
 constexpr int kNbWin = 256;     // arrivals examined per window
-constexpr int kNbVec = 2;       // float4 per thread
+constexpr int kNbVec = 8;       // float4 per thread
+constexpr int kNbBatch = 2;     // arrivals whose loads are in flight together
 constexpr int kNbElems = 256 * 4 * kNbVec;
 
 typedef float nf4 __attribute__((ext_vector_type(4)));
@@ -167,14 +168,14 @@ k_apply_neighbour_U(float *__restrict__ W, int64_t Ps, const int32_t *__restrict
                 }
                 loaded = true;
             }
-            // four arrivals at a time: their loads are in flight together (an element beyond
+            // a few arrivals at a time: their loads are in flight together (an element beyond
             // the model reads the first one instead and is never stored), then they are applied
             // in list order
-            for (int s0 = 0; s0 < ns; s0 += 4) {
-                nf4 u[4][kNbVec];
-                float sc[4];
+            for (int s0 = 0; s0 < ns; s0 += kNbBatch) {
+                nf4 u[kNbBatch][kNbVec];
+                float sc[kNbBatch];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
+                for (int q = 0; q < kNbBatch; ++q) {
                     const int s = s0 + q < ns ? s0 + q : s0;
                     const float *U = selU[s];
                     sc[q] = s0 + q < ns ? selS[s] : 0.f;
@@ -185,7 +186,7 @@ k_apply_neighbour_U(float *__restrict__ W, int64_t Ps, const int32_t *__restrict
                     }
                 }
 #pragma unroll
-                for (int q = 0; q < 4; ++q)
+                for (int q = 0; q < kNbBatch; ++q)
                     if (s0 + q < ns) {
 #pragma unroll
                         for (int v = 0; v < kNbVec; ++v) w[v] -= sc[q] * u[q][v];
