@@ -19,6 +19,8 @@
 //   writes one partial result; a second kernel adds the partials in fixed order, scales by
 //   1/B and applies  w <- w - eta g,  U <- U + g  (the gradient itself is never stored
 //   in the canonical layout).
+#include <type_traits>
+
 #include "aet_device.h"
 #include "aet_internal.h"
 
@@ -391,9 +393,13 @@ struct WgradGeom {
     int items_per_sample, S;
     int gin, gd;      // channel groups of 256 threads walking the input tile / the d(output) tile
     int nq_in_all, nq_d_all;  // the longest walks: channels per input group, rows per d(output) group
+    int vec;          // rows are 16-byte aligned: the four-pixels-per-thread staging
+    int gin4, gd4, nq_in4, nq_d4;   // the same four numbers for that staging
     int64_t in_size, out_size, w_off, b_off;
 };
 
+constexpr int kPreIn4 = 8;  // the same for the four-pixel staging (float4 each)
+constexpr int kPreD4 = 8;
 constexpr int kPreIn = 32;  // input-tile elements one thread carries from one work item to the next
 constexpr int kPreD = 16;   // the same for the d(output) tile
 
@@ -404,7 +410,7 @@ constexpr int kPreD = 16;   // the same for the d(output) tile
 // Staging: a thread is tied to one position of the tile (row, column) and walks the channels,
 // so the loop has no index arithmetic and no branches; the next work item's elements are
 // fetched into registers before the products of the current one start and go to LDS after them.
-template <int KS, int MT, int NTW, int WM>
+template <int KS, int MT, int NTW, int WM, bool VEC>
 __global__ void __launch_bounds__(256)
 k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
                   const float *__restrict__ in, const float *__restrict__ dout,
@@ -419,12 +425,14 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
 
     extern __shared__ float smem[];
     const int plane = g.rowsT * g.SWP;
-    const int CP = g.gin * g.nq_in_all;      // channel planes the staging threads write (>= IC)
-    const int DR = g.gd * g.nq_d_all;        // d(output) rows they write (>= 16*MTS)
+    const int CP = VEC ? g.gin4 * g.nq_in4 : g.gin * g.nq_in_all;   // channel planes the staging threads write (>= IC)
+    const int DR = VEC ? g.gd4 * g.nq_d4 : g.gd * g.nq_d_all;       // d(output) rows they write (>= 16*MTS)
     float *Ism = smem;                       // [CP + 3][rowsT][SWP]; plane CP = ones, CP+1 = zeros, CP+2 = dump
-    float *Dsm = Ism + (CP + 3) * plane;     // [DR + 1][DPL]; the last row is a dump
+    float *Dsm = Ism + (((CP + 3) * plane + 3) & ~3);   // [DR + 1][DPL], 16-byte aligned; the last row is a dump
     const int dplane = g.R * g.OWP;
 
+    if (VEC)   // the halo columns of the channel planes are never written again: zero them once
+        for (int e = tid; e < CP * plane; e += 256) Ism[e] = 0.f;
     for (int e = tid; e < 2 * plane; e += 256) Ism[CP * plane + e] = e < plane ? 1.f : 0.f;
 
     // B operand: lane li of N tile nt holds column k = 16*nt + li of the GEMM
@@ -457,25 +465,41 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
     // lands beyond it by itself; both read zero without touching memory, so the staging code
     // has no branches and no selects.  Threads beyond the last whole channel group store to a
     // dump area.
-    const int gin = g.gin;                       // channel groups walking the input tile
-    const int ipos = tid % plane, igrp = tid / plane;
-    const int ity = ipos / g.SWP, itx = ipos - ity * g.SWP;
-    const bool ixok = igrp < gin && (unsigned)(itx - g.pad) < (unsigned)g.IW;
-    const int gd = g.gd;
-    const int dpos = tid % dplane, dgrp = tid / dplane;
-    const int dr = dpos / g.OWP, dx = dpos - dr * g.OWP;
-    const bool dxok = dgrp < gd && dx < g.OW;
+    // VEC (image rows and d(output) rows 16-byte aligned): a thread is tied to four
+    // consecutive pixels of a row, one 16-byte load and one turn per channel; the halo
+    // columns of the input planes stay zero from the start.
+    const int gin = VEC ? g.gin4 : g.gin;        // channel groups walking the input tile
+    const int islots = VEC ? g.rowsT * (g.IW >> 2) : plane;
+    const int ipos = tid % islots, igrp = tid / islots;
+    const int irow = VEC ? g.IW >> 2 : g.SWP;    // positions per tile row
+    const int ity = ipos / irow, itx = ipos - ity * irow;
+    const bool ixok = igrp < gin && (VEC || (unsigned)(itx - g.pad) < (unsigned)g.IW);
+    const int gd = VEC ? g.gd4 : g.gd;
+    const int dslots = VEC ? g.R * (g.OW >> 2) : dplane;
+    const int dpos = tid % dslots, dgrp = tid / dslots;
+    const int drow = VEC ? g.OW >> 2 : g.OWP;
+    const int dr = dpos / drow, dx = dpos - dr * drow;
+    const bool dxok = dgrp < gd && (VEC || dx < g.OW);
     const uint32_t ihw = (uint32_t)(g.IH * g.IW), ohw = (uint32_t)(g.OH * g.OW);
     const uint32_t icstep = 4u * (uint32_t)gin * ihw, dcstep = 4u * (uint32_t)gd * ohw;   // bytes per turn
-    const int isbase = igrp < gin ? igrp * plane + ipos : (CP + 2) * plane + ipos;
-    const int isstep = igrp < gin ? gin * plane : 0;
-    const int dsbase = dgrp < gd ? dgrp * g.DPL + dpos : DR * g.DPL + dpos;
-    const int dsstep = dgrp < gd ? gd * g.DPL : 0;
+    const int isbase = VEC ? igrp * plane + ity * g.SWP + g.pad + 4 * itx
+                           : (igrp < gin ? igrp * plane + ipos : (CP + 2) * plane + ipos);
+    const int isstep = (VEC || igrp < gin) ? gin * plane : 0;
+    const int dsbase = VEC ? dgrp * g.DPL + dr * g.OWP + 4 * dx
+                           : (dgrp < gd ? dgrp * g.DPL + dpos : DR * g.DPL + dpos);
+    const int dsstep = (VEC || dgrp < gd) ? gd * g.DPL : 0;
+    const int nq_in = VEC ? g.nq_in4 : g.nq_in_all, nq_d = VEC ? g.nq_d4 : g.nq_d_all;
 
     // the fetched elements stay untouched in registers until they go to LDS (nothing waits
     // for a load before the products start)
-    float pin[kPreIn], pd[kPreD];
+    constexpr int PI = VEC ? kPreIn4 : kPreIn, PD = VEC ? kPreD4 : kPreD;
+    typedef typename std::conditional<VEC, f4, float>::type stage_t;
+    stage_t pin[PI], pd[PD];
     const int items = B * g.items_per_sample;
+    auto bload = [](__amdgpu_buffer_rsrc_t r, uint32_t off) -> stage_t {
+        if constexpr (VEC) return __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)off, 0, 0));
+        else return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)off, 0, 0));
+    };
     auto fetch = [&](int it) {
         const int b = it / g.items_per_sample, rb = it - b * g.items_per_sample;
         const int y0 = rb * g.R;
@@ -486,17 +510,40 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
             const_cast<float *>(dout) + sample * g.out_size, 0, (int)(4 * g.out_size), kBufferFlags);
         const int sy = y0 + ity - g.pad;
         const bool iok = ixok && (unsigned)sy < (unsigned)g.IH;
-        const uint32_t ivo = iok ? 4u * ((uint32_t)igrp * ihw + (uint32_t)(sy * g.IW + (itx - g.pad))) : kNowhere;
+        const int sx = VEC ? 4 * itx : itx - g.pad;
+        const uint32_t ivo = iok ? 4u * ((uint32_t)igrp * ihw + (uint32_t)(sy * g.IW + sx)) : kNowhere;
 #pragma unroll
-        for (int q = 0; q < kPreIn; ++q)
-            if (q < g.nq_in_all)
-                pin[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rin, (int)(ivo + (uint32_t)q * icstep), 0, 0));
+        for (int q = 0; q < PI; ++q)
+            if (q < nq_in) pin[q] = bload(rin, ivo + (uint32_t)q * icstep);
         const bool dok = dxok && y0 + dr < g.OH;
-        const uint32_t dvo = dok ? 4u * ((uint32_t)dgrp * ohw + (uint32_t)((y0 + dr) * g.OW + dx)) : kNowhere;
+        const uint32_t dvo = dok ? 4u * ((uint32_t)dgrp * ohw + (uint32_t)((y0 + dr) * g.OW + (VEC ? 4 * dx : dx))) : kNowhere;
 #pragma unroll
-        for (int q = 0; q < kPreD; ++q)
-            if (q < g.nq_d_all)
-                pd[q] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(rd, (int)(dvo + (uint32_t)q * dcstep), 0, 0));
+        for (int q = 0; q < PD; ++q)
+            if (q < nq_d) pd[q] = bload(rd, dvo + (uint32_t)q * dcstep);
+    };
+    auto stash = [&]() {   // the fetched tiles go to LDS
+        if constexpr (VEC) {
+            if (igrp < gin) {
+#pragma unroll
+                for (int q = 0; q < PI; ++q)
+                    if (q < nq_in) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) Ism[isbase + q * isstep + e] = pin[q][e];
+                    }
+            }
+            if (dgrp < gd) {
+#pragma unroll
+                for (int q = 0; q < PD; ++q)
+                    if (q < nq_d) *reinterpret_cast<f4 *>(Dsm + dsbase + q * dsstep) = pd[q];
+            }
+        } else {
+#pragma unroll
+            for (int q = 0; q < PI; ++q)
+                if (q < nq_in) Ism[isbase + q * isstep] = pin[q];
+#pragma unroll
+            for (int q = 0; q < PD; ++q)
+                if (q < nq_d) Dsm[dsbase + q * dsstep] = pd[q];
+        }
     };
 
     const int xsteps = g.OWP >> 2, nsteps = g.R * xsteps;
@@ -517,12 +564,7 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
     if (it < items) fetch(it);
     for (; it < items; it += g.S) {
         __syncthreads();   // the products of the previous item are done with the tiles
-#pragma unroll
-        for (int q = 0; q < kPreIn; ++q)
-            if (q < g.nq_in_all) Ism[isbase + q * isstep] = pin[q];
-#pragma unroll
-        for (int q = 0; q < kPreD; ++q)
-            if (q < g.nq_d_all) Dsm[dsbase + q * dsstep] = pd[q];
+        stash();
         __syncthreads();
         if (it + g.S < items) fetch(it + g.S);   // in flight while the products run
         // One step = 4 consecutive pixels of a row.  Two operand sets take turns: the set of
@@ -625,6 +667,19 @@ static bool wgrad_geom(const LayerGeom &L, int B, int nact, WgradGeom *g) {
     g->gd = dplane <= 256 ? 256 / dplane : 0;
     g->nq_in_all = g->gin ? (g->IC + g->gin - 1) / g->gin : 0;
     g->nq_d_all = g->gd ? (16 * g->MTS + g->gd - 1) / g->gd : 0;
+    // four pixels per thread: whole aligned float4s per image row and per d(output) row
+    g->vec = 0;
+    g->gin4 = g->gd4 = g->nq_in4 = g->nq_d4 = 0;
+    if ((L.iw & 3) == 0 && (L.ow & 3) == 0) {
+        const int islots = g->rowsT * (L.iw >> 2), dslots = g->R * (L.ow >> 2);
+        if (islots <= 256 && dslots <= 256) {
+            g->gin4 = 256 / islots;
+            g->gd4 = 256 / dslots;
+            g->nq_in4 = (g->IC + g->gin4 - 1) / g->gin4;
+            g->nq_d4 = (16 * g->MTS + g->gd4 - 1) / g->gd4;
+            g->vec = g->nq_in4 <= kPreIn4 && g->nq_d4 <= kPreD4;
+        }
+    }
     return true;
 }
 
@@ -634,7 +689,8 @@ static int wgrad_ntw(const WgradGeom &g) {
     return n <= 2 ? 2 : n <= 5 ? 5 : 10;
 }
 static size_t wgrad_lds_bytes(const WgradGeom &g) {
-    return sizeof(float) * ((size_t)(g.gin * g.nq_in_all + 3) * g.rowsT * g.SWP + (size_t)(g.gd * g.nq_d_all + 1) * g.DPL);
+    const int CP = g.vec ? g.gin4 * g.nq_in4 : g.gin * g.nq_in_all, DR = g.vec ? g.gd4 * g.nq_d4 : g.gd * g.nq_d_all;
+    return sizeof(float) * ((((size_t)(CP + 3) * g.rowsT * g.SWP + 3) & ~(size_t)3) + (size_t)(DR + 1) * g.DPL);
 }
 
 bool conv_wgrad_mfma_supported(const LayerGeom &L, int B) {
@@ -656,13 +712,13 @@ size_t conv_wgrad_partial_floats(const LayerGeom &L, int B, int n_clients) {
 }
 
 // resident workgroups per compute unit of one instantiation (cached); 0 = no such instantiation
-template <int KS, int MT, int NTW, int WM>
+template <int KS, int MT, int NTW, int WM, bool VEC>
 static int wgrad_blocks_per_cu(size_t lds) {
     static int cached = -1;
     static size_t cached_lds = 0;
     if (cached < 0 || cached_lds != lds) {
         int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_wgrad_mfma<KS, MT, NTW, WM>, 256, lds) != hipSuccess || n < 1)
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_conv_wgrad_mfma<KS, MT, NTW, WM, VEC>, 256, lds) != hipSuccess || n < 1)
             n = 1;
         cached = n;
         cached_lds = lds;
@@ -675,11 +731,16 @@ template <int KS>
 static int wgrad_dispatch(int which, hipStream_t s, dim3 grid, size_t lds, int mt, int ntw, int wm,
                           const RoundParams *dp, int u, int B, const WgradGeom &g, const float *in,
                           const float *dout, float *partial) {
-#define AET_WG(MTv, NTWv, WMv)                                                                          \
-    if (mt == MTv && ntw == NTWv && wm == WMv) {                                                        \
-        if (which == 0) return wgrad_blocks_per_cu<KS, MTv, NTWv, WMv>(lds);                            \
-        k_conv_wgrad_mfma<KS, MTv, NTWv, WMv><<<grid, 256, lds, s>>>(dp, u, B, g, in, dout, partial); \
-        return 1;                                                                                       \
+#define AET_WG(MTv, NTWv, WMv)                                                                                  \
+    if (mt == MTv && ntw == NTWv && wm == WMv) {                                                                \
+        if (g.vec) {                                                                                            \
+            if (which == 0) return wgrad_blocks_per_cu<KS, MTv, NTWv, WMv, true>(lds);                          \
+            k_conv_wgrad_mfma<KS, MTv, NTWv, WMv, true><<<grid, 256, lds, s>>>(dp, u, B, g, in, dout, partial);  \
+        } else {                                                                                                \
+            if (which == 0) return wgrad_blocks_per_cu<KS, MTv, NTWv, WMv, false>(lds);                         \
+            k_conv_wgrad_mfma<KS, MTv, NTWv, WMv, false><<<grid, 256, lds, s>>>(dp, u, B, g, in, dout, partial); \
+        }                                                                                                       \
+        return 1;                                                                                               \
     }
     AET_WG(1, 1, 2) AET_WG(2, 1, 2)
     AET_WG(1, 2, 1) AET_WG(1, 5, 1) AET_WG(1, 10, 1)
