@@ -49,6 +49,8 @@ struct ConvDir {
     int rowsT, SWP;      // rows and padded width of the staged source tile
     int PL;              // floats between the tile's channel planes in LDS (16 mod 32)
     int npos;            // tile positions one thread stages: 1, 2 or 3
+    int vec;             // rows and weight runs are 16-byte aligned: the four-pixel staging
+    int nslot, sgrp;     // ... its groups of four pixels per channel plane; channel groups of threads
     int64_t src_size, dst_size;  // floats per sample
     int64_t w_off, b_off;
     int ic, oc;          // the layer's own channel counts (weight layout W[oc][ic][K][K])
@@ -67,8 +69,14 @@ struct ConvDir {
 // wave.  CCH < 4: k = c*KS*KS + ky*KS + kx, each lane keeps the tile offsets of its K
 // elements in registers.  In both cases the operands of the next step are read from LDS
 // before the products of the current step are issued.
-template <int KS, bool BWD, int CCH, int NT, int NPOS>
-__global__ void __launch_bounds__(256)
+//
+// VEC (chunks of 8 channels, source rows and weight runs 16-byte aligned, no partial chunk):
+// staging moves 16 bytes per load.  A thread is tied to four consecutive pixels of one tile
+// row and walks channels; for the weights to four consecutive elements of the memory run and
+// walks destination channels (forward) or source channels (backward-data).  The tile's halo
+// columns never change and are zeroed once.
+template <int KS, bool BWD, int CCH, int NT, int NPOS, bool VEC>
+__global__ void __launch_bounds__(256, VEC ? 4 : 1)   // VEC: at most 128 registers, 4 workgroups per CU
 k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const float *__restrict__ src,
             float *__restrict__ dst, const float *__restrict__ mask_src) {
     const RoundParams p = rp[blockIdx.z];
@@ -93,6 +101,9 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
         p.W + g.w_off, 0, 4 * g.ic * g.oc * KS * KS, kBufferFlags);
     auto bload = [](__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
         return __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(r, (int)byte_off, 0, 0));
+    };
+    auto bload4 = [](__amdgpu_buffer_rsrc_t r, uint32_t byte_off) {
+        return __builtin_bit_cast(f4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)byte_off, 0, 0));
     };
 
     extern __shared__ float smem[];
@@ -176,12 +187,105 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     }
     const uint32_t bcstep = (uint32_t)(g.ic * KSQ);
 
+    // The four-pixel staging.  Source tile: thread = (group of four pixels, channel group),
+    // channels vcg, vcg + sgrp.  Forward weights: thread = (four elements fq of the run of one
+    // destination channel, first destination channel fd0).  Backward-data weights: thread =
+    // (four elements gq of the run of one source channel, channel group gcg).
+    constexpr int kTurnsS = 2;
+    constexpr int QF = KCHR / 4, WGF = 256 / (QF > 0 ? QF : 1), NWF = (nd + WGF - 1) / WGF;
+    constexpr int QB = nd * KSQ / 4;
+    constexpr int NGB = 256 / QB < 1 ? 1 : (256 / QB > CCH ? CCH : 256 / QB);
+    constexpr int NBT = (CCH + NGB - 1) / NGB;
+    uint32_t voff[kTurnsS];
+    bool vst[kTurnsS];
+    int vlds = 0, vstep = 0, fcol[4], gl[4];
+    int fq = 0, fd0 = 0, gq = 0, gcg = 0;
+    if constexpr (VEC) {
+        const int sw4 = g.SW >> 2;
+        const int vslot = tid % g.nslot, vcg = tid / g.nslot;
+        const int vty = vslot / sw4, vxq = vslot - vty * sw4;
+        const int vsy = y0 + vty - g.P;
+#pragma unroll
+        for (int j = 0; j < kTurnsS; ++j) {
+            const int c = vcg + g.sgrp * j;
+            vst[j] = vcg < g.sgrp && c < CCH;
+            voff[j] = (vst[j] && (unsigned)vsy < (unsigned)g.SH)
+                          ? 4u * (uint32_t)(vsy * g.SW + 4 * vxq) + (uint32_t)c * shw : kNowhere;
+        }
+        vlds = vcg * PL + vty * g.SWP + g.P + 4 * vxq;
+        vstep = g.sgrp * PL;
+        fq = tid % QF; fd0 = tid / QF;
+        gq = tid % QB; gcg = tid / QB;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int m = 4 * fq + e;
+            fcol[e] = kcol(m / KSQ, m % KSQ);
+            const int j = 4 * gq + e;
+            gl[e] = (j / KSQ) * KCHP + kcol(0, KSQ - 1 - j % KSQ);
+        }
+        // halo columns: P on the left, the rest on the right of the image's columns
+        const int hw = g.SWP - g.SW, per = g.rowsT * hw;
+        for (int e = tid; e < CCH * per; e += 256) {
+            const int c = e / per, r = e - c * per;
+            const int ty = r / hw, h = r - ty * hw;
+            Ssm[c * PL + ty * g.SWP + (h < g.P ? h : g.SW + h)] = 0.f;
+        }
+    }
+    const uint32_t fbase = (uint32_t)(dc0 * g.ic * KSQ + 4 * fq);
+    const uint32_t gbase = (uint32_t)(dc0 * KSQ + 4 * gq);
+
     // All loads of a chunk (source tile and weights) are issued before the first of them is
     // stored to LDS: one memory round trip per chunk.
     constexpr int NWL = (nd + WG_ - 1) / WG_;            // forward: destination channels per thread
     constexpr int NWV = BWD ? NPB * CCH : NWL;
     for (int c0 = 0; c0 < g.SC; c0 += CCH) {
         __syncthreads();   // the products of the previous chunk are done with the tiles
+        if constexpr (VEC) {
+            f4 sv4[kTurnsS], wv4[BWD ? NBT : NWF];
+#pragma unroll
+            for (int j = 0; j < kTurnsS; ++j) sv4[j] = bload4(rs, voff[j] + (uint32_t)c0 * shw);
+            if (BWD) {
+#pragma unroll
+                for (int j = 0; j < NBT; ++j) {
+                    const int c = gcg + NGB * j;
+                    const bool ok = gcg < NGB && c < CCH;
+                    wv4[j] = bload4(rw, ok ? 4u * (gbase + (uint32_t)(c0 + c) * bcstep) : kNowhere);
+                }
+            } else {
+                const int lim = fd0 < WGF ? dlim : 0;
+                const uint32_t q = fbase + (uint32_t)c0 * KSQ;
+#pragma unroll
+                for (int j = 0; j < NWF; ++j) {
+                    const int d = fd0 + WGF * j;
+                    wv4[j] = bload4(rw, d < lim ? 4u * (q + (uint32_t)d * wdstep) : kNowhere);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < kTurnsS; ++j)
+                if (vst[j]) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) Ssm[vlds + j * vstep + e] = sv4[j][e];
+                }
+            if (BWD) {
+#pragma unroll
+                for (int j = 0; j < NBT; ++j) {
+                    const int c = gcg + NGB * j;
+                    if (gcg < NGB && c < CCH) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) Wsm[gl[e] + kcol(c, 0)] = wv4[j][e];
+                    }
+                }
+            } else if (fd0 < WGF) {
+#pragma unroll
+                for (int j = 0; j < NWF; ++j) {
+                    const int d = fd0 + WGF * j;
+                    if (d < nd) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) Wsm[d * KCHP + fcol[e]] = wv4[j][e];
+                    }
+                }
+            }
+        } else {
         float sv[NPOS][CCH], wv[NWV];
 #pragma unroll
         for (int i = 0; i < NPOS; ++i)
@@ -227,6 +331,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
                 const int d = wd0 + WG_ * j;
                 if (d < nd) Wsm[d * KCHP + wcol] = wv[BWD ? 0 : j];
             }
+        }
         }
         __syncthreads();
         float a[2][2], bv[2][NT];
@@ -334,6 +439,14 @@ static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d) {
     d->npos = (tile_plane + 255) / 256;
     if (d->npos > 3) return false;
     if (d->src_size >= (int64_t)1 << 28 || (int64_t)L.oc * L.ic * KS * KS >= (int64_t)1 << 28) return false;   // 32-bit byte offsets
+    // the four-pixel staging: whole chunks of 8 channels, rows and weight runs 16-byte aligned,
+    // whole blocks of destination channels, at most 64 groups of four pixels per plane (two
+    // turns of at least 4 channel groups of threads cover the chunk's 8 channels)
+    d->nslot = d->rowsT * (d->SW >> 2);
+    d->sgrp = d->nslot > 0 ? 256 / d->nslot : 0;
+    if (d->sgrp > kCch) d->sgrp = kCch;
+    d->vec = KS == 3 && d->CCH == kCch && d->SC % kCch == 0 && (d->SW & 3) == 0 && d->sgrp >= 4 &&
+             (L.ic & 3) == 0 && (L.w_off & 3) == 0 && d->DC % (16 * d->NT) == 0;
     return true;
 }
 
@@ -362,17 +475,24 @@ hipError_t launch_conv_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp
     if (timed) prof->before(fam, s);
 #define AET_CONV(KSv, CCHv, NTv, NPv)                                                                                \
     if (L.k == KSv && d.CCH == CCHv && d.NT == NTv && np == NPv) {                                                  \
-        if (bwd) k_conv_mfma<KSv, true, CCHv, NTv, NPv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);  \
-        else k_conv_mfma<KSv, false, CCHv, NTv, NPv><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);     \
+        if (bwd) k_conv_mfma<KSv, true, CCHv, NTv, NPv, false><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);  \
+        else k_conv_mfma<KSv, false, CCHv, NTv, NPv, false><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);     \
+    }
+#define AET_CONV_VEC(NTv)                                                                                            \
+    if (np == 0 && d.NT == NTv) {                                                                                    \
+        if (bwd) k_conv_mfma<3, true, 8, NTv, 1, true><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);    \
+        else k_conv_mfma<3, false, 8, NTv, 1, true><<<grid, 256, lds, s>>>(dp, u, B, d, src, dst, mask_src);       \
     }
 #define AET_CONV_NT(KSv, CCHv, NPv) AET_CONV(KSv, CCHv, 1, NPv) AET_CONV(KSv, CCHv, 2, NPv) AET_CONV(KSv, CCHv, 4, NPv)
     // tiles of up to 256 positions and at least 4 channels per chunk get the one-position kernel
-    const int np = (d.npos == 1 && d.CCH >= 4) ? 1 : 3;
+    const int np = d.vec ? 0 : (d.npos == 1 && d.CCH >= 4) ? 1 : 3;
+    AET_CONV_VEC(1) AET_CONV_VEC(2) AET_CONV_VEC(4)
     AET_CONV_NT(3, 1, 3) AET_CONV_NT(3, 2, 3) AET_CONV_NT(3, 4, 3) AET_CONV_NT(3, 8, 3)
     AET_CONV_NT(5, 1, 3) AET_CONV_NT(5, 2, 3) AET_CONV_NT(5, 4, 3) AET_CONV_NT(5, 8, 3)
     AET_CONV_NT(3, 4, 1) AET_CONV_NT(3, 8, 1) AET_CONV_NT(5, 4, 1) AET_CONV_NT(5, 8, 1)
 #undef AET_CONV_NT
 #undef AET_CONV
+#undef AET_CONV_VEC
     if (timed) prof->after(fam, s);
     return hipGetLastError();
 }
