@@ -468,12 +468,14 @@ hipError_t launch_dense_mfma(hipStream_t s, Profiler *prof, int mode, const Roun
         // float4 loads need 16-byte aligned rows: K a multiple of 4 (all offsets are multiples
         // of 64 floats otherwise) and the parameter offset a multiple of 4
         const bool vec = (K & 3) == 0 && (w_off & 3) == 0;
-        if (M > 16) {
+        // four sample tiles per workgroup share the weight rows, but only when that still
+        // gives every compute unit two workgroups; otherwise one tile each
+        if (M > 16 && (int64_t)((N + 15) / 16) * ((M + 63) / 64) * nact >= 512) {
             dim3 dgrid((unsigned)((N + 15) / 16), (unsigned)((M + 63) / 64), (unsigned)nact);
             if (vec) k_dense_fwd_direct<true, 4><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
             else k_dense_fwd_direct<false, 4><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
         } else {
-            dim3 dgrid((unsigned)((N + 15) / 16), 1, (unsigned)nact);
+            dim3 dgrid((unsigned)((N + 15) / 16), (unsigned)((M + 15) / 16), (unsigned)nact);
             if (vec) k_dense_fwd_direct<true, 1><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
             else k_dense_fwd_direct<false, 1><<<dgrid, 256, 0, s>>>(dp, u, B, K, O, w_off, b_off, relu, x, z);
         }
