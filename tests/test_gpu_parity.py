@@ -236,6 +236,72 @@ def test_config4_full_layer_shapes(gpu, oracle_libs):
     run.close()
 
 
+@pytest.mark.timeout(400)
+def test_config4_full_size_first_tick(gpu, oracle_libs):
+    """The CNN workload at full size in the launch configuration the benchmark times: all 32
+    clients in every launch, B = 64.  After the first tick (round 0 of every client: two
+    recursions from the common start) clients 0 and 1 are compared with an oracle run of
+    those two clients (rounds are independent of each other until the server aggregates),
+    client 31's round is recomputed from the oracle's index map and its mini-batch gradient
+    (Algorithm 2, inner loop: w <- w - eta g, U <- U + g), and for every client the round
+    bookkeeping is exact and w_start - w_end = eta U holds in the GPU's own numbers."""
+    from oracle import Oracle
+    from oracle.oracle import batch_loss_grad
+    from parity import TOL, TWIN_FACTOR, CEILING, tensor_relerrs, weight_unit_errs
+    wl = W.config4()
+    model, B = wl.model, wl.model.batch
+    run = gpu(wl)
+    orc, twin = Oracle(wl, "f64", n_clients=2), Oracle(wl, "f32", n_clients=2)
+    fin_g = run.run_round()
+    assert fin_g == [(c, 0) for c in range(wl.n_clients)]
+    assert orc.run_round() == twin.run_round() == [(0, 0), (1, 0)]
+    w0 = wl.w0.astype(np.float64)
+    m0 = wl.b // B
+    eta = float(np.float32(wl.eta0))          # t = 0: eta_0 itself
+    worst = {}
+
+    twin_worst = {}
+
+    def check(quantity, c, errs, twin_errs):
+        tw = twin_worst.setdefault(quantity, [0.0] * len(twin_errs))
+        for j, (e, t) in enumerate(zip(errs, twin_errs)):
+            tw[j] = max(tw[j], t)
+            bar = min(CEILING, max(TOL, TWIN_FACTOR * t))
+            assert e <= bar, f"{quantity}, client {c}, tensor {j}: {e:.3e} > {bar:.1e} (fp32 twin {t:.3e})"
+            worst[quantity] = max(worst.get(quantity, 0.0), e)
+
+    for c in range(wl.n_clients):
+        ig = run.lib.aet_get_round_info(c, 0)
+        assert (ig["s"], ig["m"], ig["q0"], ig["t0"], ig["start_tick"]) == (wl.b, m0, 0, 0, 0)
+        assert ig["arrival"] == int(wl.compute_factor[c]) - 1 and ig["eta"] == eta
+        U = run.lib.aet_get_U(c, 0).astype(np.float64)
+        w_end = run.lib.aet_get_weights(c).astype(np.float64)
+        err = np.abs((w0 - w_end) / eta - U).max()
+        assert err <= 1e-4 * max(1.0, np.abs(U).max()), (c, err)
+    for c in (0, 1):
+        io, ig = orc.round_info(c, 0), run.lib.aet_get_round_info(c, 0)
+        for key in ("s", "m", "q0", "t0", "start_tick", "arrival"):
+            assert ig[key] == io[key], (c, key)
+        wo, Uo = orc.get_weights(c), orc.get_U(c, 0)
+        check("w_c", c, tensor_relerrs(model, run.lib.aet_get_weights(c), wo),
+              tensor_relerrs(model, twin.get_weights(c), wo))
+        check("U_weight_units", c, weight_unit_errs(model, io["eta"], run.lib.aet_get_U(c, 0), Uo, wo),
+              weight_unit_errs(model, io["eta"], twin.get_U(c, 0), Uo, wo))
+        worst["loss"] = max(worst.get("loss", 0.0), abs(ig["loss"] - io["loss"]) / abs(io["loss"]))
+    c = wl.n_clients - 1          # yardstick: the twin's worst errors on clients 0 and 1
+    wo, Uo = w0.copy(), np.zeros(w0.size)
+    for u in range(m0):
+        idx = [orc.sample_index(c, u * B + j, wl.X[c].shape[0]) for j in range(B)]
+        _, g = batch_loss_grad(model, wo, wl.X[c][idx], wl.y[c][idx])
+        wo, Uo = wo - eta * g, Uo + g
+    check("w_c", c, tensor_relerrs(model, run.lib.aet_get_weights(c), wo), twin_worst["w_c"])
+    check("U_weight_units", c, weight_unit_errs(model, eta, run.lib.aet_get_U(c, 0), Uo, wo),
+          twin_worst["U_weight_units"])
+    report("config 4 at full size, first tick (clients 0, 1, 31 of 32)", worst)
+    assert worst["loss"] <= TOL
+    run.close()
+
+
 def test_config4_reduced_20_rounds(gpu, oracle_libs):
     """Same architecture at 16x16 images and half width, 8 clients with compute factors,
     20 rounds; all sides restart from the oracle's global model after every tick (a
