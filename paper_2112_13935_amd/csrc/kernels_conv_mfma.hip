@@ -181,7 +181,7 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
             boff[BWD ? i : 0] = ok ? (uint32_t)(dc0 * KSQ + j) : 0xffffffffu;
             blds[BWD ? i : 0] = j < nd * KSQ ? d * KCHP + kcol(0, KSQ - 1 - tm) : -1;
         }
-        if (KCH > KCHR)   // padding columns: zero weights, written once
+        if constexpr (KCH > KCHR)   // padding columns: zero weights, written once
             for (int e = tid; e < nd * (KCH - KCHR); e += 256)
                 Wsm[(e / (KCH - KCHR)) * KCHP + KCHR + e % (KCH - KCHR)] = 0.f;
     }
@@ -410,7 +410,18 @@ k_conv_mfma(const RoundParams *__restrict__ rp, int u, int B, ConvDir g, const f
     }
 }
 
-static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d) {
+static int device_cus() {
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+            cus = 256;
+    }
+    return cus;
+}
+
+static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d, int nt_max = 4) {
     const int KS = L.k;
     if (!(KS == 3 || KS == 5)) return false;
     d->ic = L.ic; d->oc = L.oc; d->relu = L.relu;
@@ -430,6 +441,7 @@ static bool conv_dir(const LayerGeom &L, bool bwd, ConvDir *d) {
     // the 4 waves own 8 M tiles; with MPR in {3, 5, 6, 7} some tiles stay unused
     d->NT = (d->DC + 15) / 16;
     d->NT = d->NT <= 1 ? 1 : d->NT <= 2 ? 2 : 4;
+    if (d->NT > nt_max) d->NT = nt_max;
     d->CCH = d->SC <= 1 ? 1 : d->SC <= 2 ? 2 : d->SC <= 4 ? 4 : kCch;
     d->rowsT = d->R + KS - 1;
     d->SWP = 16 * d->MPR + KS - 1;
@@ -466,6 +478,13 @@ hipError_t launch_conv_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp
                             const float *mask_src) {
     ConvDir d;
     if (!conv_dir(L, bwd, &d)) return hipErrorInvalidValue;
+    // A launch of the widest tiling (4 N tiles, 4 resident workgroups per compute unit) that
+    // has fewer than two full rounds of workgroups ends with compute units running a last
+    // workgroup alone; half as wide workgroups, twice as many, fill that tail (measured on
+    // launches of 10 and 12 clients: +2.5 % on the job; 1 N tile: +0.8 %).
+    if (d.NT == 4 && (int64_t)((d.DH + d.R - 1) / d.R) * ((d.DC + 63) / 64) * B * nact < (int64_t)8 * device_cus() &&
+        !conv_dir(L, bwd, &d, 2))
+        return hipErrorInvalidValue;
     const size_t lds = conv_lds_bytes(d, L.k);
     const int nblocks = (d.DC + 16 * d.NT - 1) / (16 * d.NT);
     const int rblocks = (d.DH + d.R - 1) / d.R;
@@ -870,16 +889,6 @@ static int wgrad_dispatch(int which, hipStream_t s, dim3 grid, size_t lds, int m
     return 0;
 }
 
-static int device_cus() {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess ||
-            hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-            cus = 256;
-    }
-    return cus;
-}
 
 hipError_t launch_conv_wgrad_mfma(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int u,
                                   int B, const LayerGeom &L, const float *in, const float *dout,
