@@ -530,6 +530,7 @@ struct WgradGeom {
     int DPL;          // floats per channel of the staged d(output) tile: R*OWP padded to 4 mod 32,
                       // so that the 16 channels x 4 pixels of an A operand fall into distinct banks
     int items_per_sample, S;
+    int U;            // output rows (of all work items, in order) per slice
     int gin, gd;      // channel groups of 256 threads walking the input tile / the d(output) tile
     int nq_in_all, nq_d_all;  // the longest walks: channels per input group, rows per d(output) group
     int vec;          // rows are 16-byte aligned: the four-pixels-per-thread staging
@@ -685,7 +686,7 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
         }
     };
 
-    const int xsteps = g.OWP >> 2, nsteps = g.R * xsteps;
+    const int xsteps = g.OWP >> 2;
     auto operands = [&](float (&a)[MT], float (&bv)[NTW], int doff, int po) {
 #pragma unroll
         for (int m = 0; m < MT; ++m) a[m] = Dsm[ab[m] + doff];
@@ -699,30 +700,37 @@ k_conv_wgrad_mfma(const RoundParams *__restrict__ rp, int u, int B, WgradGeom g,
             for (int m = 0; m < MT; ++m) acc[m][j] = mfma16x16x4(a[m], bv[j], acc[m][j]);
     };
 
-    int it = sl;
-    if (it < items) fetch(it);
-    for (; it < items; it += g.S) {
+    // The slice's share: output rows u0 .. u1-1 of the client's work items laid end to end (R
+    // rows each), so that the shares differ by at most one row; an item cut by a share's end
+    // is staged whole by both neighbours and each runs its own rows of it.
+    const int u0 = sl * g.U, u1 = min(u0 + g.U, items * g.R);
+    int it = u0 / g.R;
+    const int it_last = u1 > u0 ? (u1 - 1) / g.R : -1;
+    if (it <= it_last) fetch(it);
+    for (; it <= it_last; ++it) {
         __syncthreads();   // the products of the previous item are done with the tiles
         stash();
         __syncthreads();
-        if (it + g.S < items) fetch(it + g.S);   // in flight while the products run
+        if (it < it_last) fetch(it + 1);   // in flight while the products run
+        const int r_lo = max(u0 - it * g.R, 0), r_hi = min(u1 - it * g.R, g.R);
+        const int t_lo = r_lo * xsteps, t_hi = r_hi * xsteps;
         // One step = 4 consecutive pixels of a row.  Two operand sets take turns: the set of
         // the step after is read from LDS before the products of a step are issued.
         float a0[MT], b0[NTW], a1[MT], b1[NTW];
-        int xs = 0, po = 0;
+        int xs = 0, po = r_lo * g.SWP;
         auto advance = [&]() {
             po += 4;
             if (++xs == xsteps) { xs = 0; po += g.SWP - g.OWP; }
         };
-        operands(a0, b0, 0, 0);
-        for (int t = 0; t < nsteps; t += 2) {
-            const bool odd = t + 1 < nsteps;
+        operands(a0, b0, 4 * t_lo, po);
+        for (int t = t_lo; t < t_hi; t += 2) {
+            const bool odd = t + 1 < t_hi;
             if (odd) {
                 advance();
                 operands(a1, b1, 4 * (t + 1), po);
             }
             products(a0, b0);
-            if (t + 2 < nsteps) {
+            if (t + 2 < t_hi) {
                 advance();
                 operands(a0, b0, 4 * (t + 2), po);
             }
@@ -799,6 +807,7 @@ static bool wgrad_geom(const LayerGeom &L, int B, int nact, WgradGeom *g) {
     g->items_per_sample = (L.oh + g->R - 1) / g->R;
     (void)nact;
     g->S = 1;  // set by the launcher from the number of resident workgroups
+    g->U = g->R;
     g->MTS = wgrad_wm(*g) * wgrad_mt(*g);
     g->DPL = g->R * g->OWP + ((4 - (g->R * g->OWP) % 32 + 32) % 32);
     const int plane = g->rowsT * g->SWP, dplane = g->R * g->OWP;
@@ -903,15 +912,15 @@ hipError_t launch_conv_wgrad_mfma(hipStream_t s, Profiler *prof, const RoundPara
     if (per_cu < 1) return hipErrorInvalidValue;
     // Slices per client: all workgroups of the launch resident at once (a few workgroups more
     // than fit would cost a whole second pass), never more than the partial-sum scratch holds
-    // (wgrad_target + n_clients slices), and the work items spread evenly.
-    const int items = B * g.items_per_sample;
+    // (wgrad_target + n_clients slices), and the output rows of the work items spread evenly.
+    const int units = B * g.items_per_sample * g.R;
     int cap = per_cu * device_cus();
     if (cap > wgrad_target(L)) cap = wgrad_target(L);
     int S = cap / nact;
     if (S < 1) S = 1;
-    if (S > items) S = items;
-    const int per_slice = (items + S - 1) / S;
-    S = (items + per_slice - 1) / per_slice;  // the fewest slices with the same longest share
+    if (S > units) S = units;
+    g.U = (units + S - 1) / S;
+    S = (units + g.U - 1) / g.U;  // the fewest slices with the same longest share
     g.S = S;
     const bool timed = prof && prof->on[F_CONV_BWD_WEIGHT];
     if (timed) prof->before(F_CONV_BWD_WEIGHT, s);
