@@ -42,6 +42,8 @@ constexpr int kMlpThreads = 64 * kMlpWaves;
 constexpr int kMlpMaxTPW = 7;        // K tiles (of 16) per wave  => D <= 16*8*7 = 896
 constexpr int kMlpMaxG = 16;         // workgroups per client
 constexpr int kMlpRec = 512;         // 64-bit words per exchange record (B*C <= 512)
+constexpr int kMlpPair = 512;        // 64-bit words per pair record (B*16 <= 512)
+constexpr int kMlpHalfTPW = 4;       // K tiles per wave when two workgroups share the columns
 constexpr int kSpinLimit = 1 << 22;  // bounded wait of the exchange poll
 
 // Hides a value from the optimiser so that addresses derived from it are computed where
@@ -106,18 +108,23 @@ struct MlpPack {
 };
 
 // FULL: every wave owns TPW real tiles (D = 16 * 8 * TPW): no pad tiles, loads unguarded.
-template <int NBT, int TPW, bool FAST, bool FULL>
+// HF = 2: two workgroups per unit group, each owning one half of the input columns (its
+// half of the W1 / U1 slice, of the sampled rows and of both big products); they add their
+// partial hidden sums through a second tagged exchange (pair records `prec`) and from
+// there on compute the same numbers side by side; half 0 posts the logits and stores the
+// second layer at the end.
+template <int NBT, int TPW, bool FAST, bool FULL, int HF>
 __global__ void __launch_bounds__(kMlpThreads, 1)
 k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
-            int D, int H, int C, int G, unsigned long long *__restrict__ xrec, uint32_t tag0,
-            int *__restrict__ errflag) {
+            int D, int H, int C, int G, unsigned long long *__restrict__ xrec,
+            unsigned long long *__restrict__ prec, uint32_t tag0, int *__restrict__ errflag) {
     constexpr int B = 16 * NBT;
-    // workgroup -> (client, unit group): consecutive workgroup ids go round the 8 XCDs, so
-    // the G workgroups of one client get ids that land on the same XCD and share its L2
-    // for the mini-batch rows.
+    // workgroup -> (client, unit group, half): consecutive workgroup ids go round the 8 XCDs,
+    // so the workgroups of one client get ids that land on the same XCD and share its L2
+    // for the mini-batch rows and the exchanges.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int a = xcd + 8 * (slot / G);  // index into this launch's records
-    const int g = slot % G;
+    const int a = xcd + 8 * (slot / (G * HF));  // index into this launch's records
+    const int g = (slot % (G * HF)) / HF, hf = slot % HF;
     if (a >= nhere) return;
     const RoundParams p = pack.p[a];
     const gcf_ptr Xg = as_global(p.X);
@@ -128,14 +135,18 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     // the wave index as a scalar, so that everything derived from it (tile counts, column
     // offsets, branches on them) stays in scalar registers and scalar branches
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int KT = (D + 15) >> 4;             // real K tiles (of 16 columns)
+    // real K tiles (of 16 columns) of this half, and the first of them
+    const int KTall = (D + 15) >> 4, KH = (KTall + HF - 1) / HF;
+    const int tbase = hf * KH;
+    const int KT = min(KH, KTall - tbase);
     constexpr int ld = 16 * kMlpWaves * TPW + 4;  // LDS row stride: all tiles + 4 floats of skew
     constexpr int NI = NBT * TPW;             // float4 loads per lane and mini-batch
     // wave w steps through tiles [TPW*w, TPW*w + TPW); the first nt of them are real, the
     // rest are loaded as zeros and meet zero weights
     const int t0 = TPW * wave;
     const int nt = min(max(KT - t0, 0), TPW);
-    const int col0 = 16 * t0;                 // first column of the wave
+    const int col0 = 16 * t0;                 // first column of the wave in the staged rows
+    const int gcol0 = 16 * (tbase + t0);      // ... and in the sample / weight rows
 
     extern __shared__ float smem[];
     // the small arrays come first so that their addresses fit the 16-bit offset field of
@@ -162,7 +173,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     // of the forward product: lane (li, lg) holds, for batch tile bt and K tile tt, the four
     // values x[16*bt + li][col0 + 16*tt + 4*lg .. +3] (one 16-byte load when FAST: D a
     // multiple of 16, so every piece is inside the row and aligned).
-    const gcf_ptr lane_src = Xg + col0 + 4 * lg;
+    const gcf_ptr lane_src = Xg + gcol0 + 4 * lg;
     // rowp: the lane's piece of tile 0 of its row, lane_src + row * D
     auto load_piece = [&](gcf_ptr rowp, int tt) -> f4 {
         f4 x = {0.f, 0.f, 0.f, 0.f};
@@ -171,7 +182,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             if constexpr (FAST) {
                 x = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(src);
             } else {
-                const int col = col0 + 16 * tt + 4 * lg;
+                const int col = gcol0 + 16 * tt + 4 * lg;
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
                     if (col + r < D) x[r] = src[r];
@@ -188,13 +199,13 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     for (int tt = 0; tt < TPW; ++tt) {
         f4 w = {0.f, 0.f, 0.f, 0.f};
         if (tt < nt) {
-            const float *src = Wg + (int64_t)(16 * g + li) * D + 16 * (t0 + tt) + 4 * lg;
+            const float *src = Wg + (int64_t)(16 * g + li) * D + gcol0 + 16 * tt + 4 * lg;
             if constexpr (FAST) {   // D a multiple of 16: the four values are one aligned piece
                 w = *reinterpret_cast<const f4 *>(src);
             } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (16 * (t0 + tt) + 4 * lg + r < D) w[r] = src[r];
+                    if (gcol0 + 16 * tt + 4 * lg + r < D) w[r] = src[r];
             }
         }
         W1r[tt] = w;
@@ -234,6 +245,8 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         }
     }
     unsigned long long *rec_base = xrec + (int64_t)(rec0 + a) * 2 * kMlpMaxG * kMlpRec;
+    // pair records [client][unit group][step parity][half][B * 16]
+    unsigned long long *prec_base = prec + ((int64_t)(rec0 + a) * kMlpMaxG + g) * 4 * kMlpPair;
     bool dead = false;  // the poll expired: keep going, the host will see the flag
     __syncthreads();
 
@@ -266,17 +279,50 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         }
         __syncthreads();
         // ---- h = relu(z1 + b1) ----------------------------------------------------------
-        for (int i = tid; i < B * 16; i += kMlpThreads) {
-            float s = b1s[i & 15];
+        const uint32_t tag = tag0 + (uint32_t)u;
+        if constexpr (HF == 1) {
+            for (int i = tid; i < B * 16; i += kMlpThreads) {
+                float s = b1s[i & 15];
 #pragma unroll
-            for (int w = 0; w < kMlpWaves; ++w) s += red[w * B * 16 + i];
-            hs[i] = s > 0.f ? s : 0.f;
+                for (int w = 0; w < kMlpWaves; ++w) s += red[w * B * 16 + i];
+                hs[i] = s > 0.f ? s : 0.f;
+            }
+        } else {
+            // the own half's sums go to the pair record, the other half's come from there;
+            // both halves add them in the same order (half 0 + half 1), so both get the same h
+            unsigned long long *pr = prec_base + (int64_t)(u & 1) * 2 * kMlpPair;
+            const int i = tid;   // B * 16 <= 512 elements, one per thread
+            float own = 0.f;
+            if (i < B * 16) {
+#pragma unroll
+                for (int w = 0; w < kMlpWaves; ++w) own += red[w * B * 16 + i];
+                const unsigned long long word = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(own);
+                __hip_atomic_store(pr + hf * kMlpPair + i, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            const unsigned long long *theirs = pr + (1 - hf) * kMlpPair + min(i, B * 16 - 1);
+            unsigned long long v = 0;
+            int spins = 0;
+            for (;;) {
+                v = __hip_atomic_load(theirs, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (__all((uint32_t)(v >> 32) == tag) || dead) break;
+                __builtin_amdgcn_s_sleep(1);
+                if ((++spins & 255) == 0) {
+                    if (spins >= kSpinLimit || __hip_atomic_load(errflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                        __hip_atomic_store(errflag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        dead = true;
+                    }
+                }
+            }
+            if (i < B * 16) {
+                const float other = __uint_as_float((uint32_t)v);
+                const float s = b1s[i & 15] + (hf == 0 ? own + other : other + own);
+                hs[i] = s > 0.f ? s : 0.f;
+            }
         }
         __syncthreads();
         // ---- partial logits of the own 16 units -> tagged exchange record ---------------
-        const uint32_t tag = tag0 + (uint32_t)u;
         unsigned long long *rec = rec_base + (int64_t)(u & 1) * kMlpMaxG * kMlpRec;
-        if (wave < NBT) {
+        if (wave < NBT && hf == 0) {
             const int bt = wave;
             f4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -493,14 +539,14 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
 #pragma unroll
     for (int tt = 0; tt < TPW; ++tt) {
         if (tt < nt) {
-            const int64_t base = (int64_t)(16 * g + li) * D + 16 * (t0 + tt) + 4 * lg;
+            const int64_t base = (int64_t)(16 * g + li) * D + gcol0 + 16 * tt + 4 * lg;
             if constexpr (FAST) {
                 *reinterpret_cast<f4 __attribute__((address_space(1))) *>(Wc + base) = W1r[tt];
                 *reinterpret_cast<f4 __attribute__((address_space(1))) *>(Uc + base) = U1r[tt];
             } else {
 #pragma unroll
                 for (int r = 0; r < 4; ++r)
-                    if (16 * (t0 + tt) + 4 * lg + r < D) {
+                    if (gcol0 + 16 * tt + 4 * lg + r < D) {
                         Wc[base + r] = W1r[tt][r];
                         Uc[base + r] = U1r[tt][r];
                     }
@@ -508,7 +554,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         }
     }
     __syncthreads();
-    {
+    if (hf == 0) {
         const int o = tid >> 4, j = tid & 15;
         if (tid < 256 && o < C) {
             Wc[w2_off + (int64_t)o * H + 16 * g + j] = W2s[tid];
@@ -524,7 +570,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         }
     }
     // the loss was accumulated by wave 4, lane 0 of unit group 0
-    if (g == 0 && wave == 4 && lane == 0) *as_global(p.loss) = lossacc[0];
+    if (g == 0 && hf == 0 && wave == 4 && lane == 0) *as_global(p.loss) = lossacc[0];
 }
 
 __global__ void k_zero_words(unsigned long long *p, size_t n) {
@@ -534,10 +580,11 @@ __global__ void k_zero_words(unsigned long long *p, size_t n) {
 
 static int mlp_tpw(int D) { return (D + 15) / 16 <= 2 * kMlpWaves ? 2 : kMlpMaxTPW; }
 
-static size_t mlp_lds_bytes(int D, int B) {
-    const int ld = 16 * kMlpWaves * mlp_tpw(D) + 4;
+static size_t mlp_lds_bytes_tpw(int tpw, int B) {
+    const int ld = 16 * kMlpWaves * tpw + 4;
     return sizeof(float) * ((size_t)B * ld + kMlpWaves * B * 16 + 3 * B * 16 + 512 + 64 + B + 16) + sizeof(int) * B;
 }
+static size_t mlp_lds_bytes(int D, int B) { return mlp_lds_bytes_tpw(mlp_tpw(D), B); }
 
 bool mlp_round_supported(int D, int H, int C, int B) {
     if (!(B == 16 || B == 32)) return false;
@@ -546,21 +593,23 @@ bool mlp_round_supported(int D, int H, int C, int B) {
     return mlp_lds_bytes(D, B) <= 160 * 1024;
 }
 
-// exchange records [client][2][kMlpMaxG][kMlpRec] 64-bit words, then the error flag
+// exchange records [client][2][kMlpMaxG][kMlpRec] 64-bit words, the pair records
+// [client][kMlpMaxG][2][2][kMlpPair], then the error flag
 static size_t mlp_rec_words(int n_clients) { return (size_t)n_clients * 2 * kMlpMaxG * kMlpRec; }
+static size_t mlp_all_words(int n_clients) { return mlp_rec_words(n_clients) + (size_t)n_clients * kMlpMaxG * 4 * kMlpPair; }
 
 size_t mlp_round_scratch_bytes(int n_clients, int B) {
     (void)B;
-    return mlp_rec_words(n_clients) * 8 + 256;
+    return mlp_all_words(n_clients) * 8 + 256;
 }
 
-static int g_mlp_capacity[2][2][3] = {};  // resident workgroups, per instantiation
+static int g_mlp_capacity[2][3][3] = {};  // resident workgroups, per instantiation
 
-template <int NBT, int TPW, bool FAST, bool FULL>
+template <int NBT, int TPW, bool FAST, bool FULL, int HF>
 static hipError_t mlp_capacity(size_t lds, int *cap) {
-    int &cached = g_mlp_capacity[NBT - 1][TPW == kMlpMaxTPW ? 1 : 0][FAST ? (FULL ? 2 : 1) : 0];
+    int &cached = g_mlp_capacity[NBT - 1][HF == 2 ? 2 : TPW == kMlpMaxTPW ? 1 : 0][FAST ? (FULL ? 2 : 1) : 0];
     if (cached > 0) { *cap = cached; return hipSuccess; }
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mlp_round<NBT, TPW, FAST, FULL>),
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_mlp_round<NBT, TPW, FAST, FULL, HF>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     int dev = 0, cus = 0, per_cu = 0;
@@ -568,34 +617,41 @@ static hipError_t mlp_capacity(size_t lds, int *cap) {
     if (e != hipSuccess) return e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_mlp_round<NBT, TPW, FAST, FULL>, kMlpThreads, lds);
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_mlp_round<NBT, TPW, FAST, FULL, HF>, kMlpThreads, lds);
     if (e != hipSuccess) return e;
     *cap = cus * per_cu;
     cached = *cap;
     return hipSuccess;
 }
 
-template <int NBT, int TPW, bool FAST, bool FULL>
+// HF = 2 (two workgroups per unit group) is taken only when all active clients fit one
+// launch that way; otherwise *declined is set and nothing is launched.
+template <int NBT, int TPW, bool FAST, bool FULL, int HF>
 static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *hp, int nact, int max_m,
                              const float *Wg, int D, int H, int C, void *scratch, int n_clients,
-                             uint32_t *epoch) {
+                             uint32_t *epoch, bool *declined = nullptr) {
     constexpr int B = 16 * NBT;
     const int G = H / 16;
-    const size_t lds = mlp_lds_bytes(D, B);
+    const size_t lds = mlp_lds_bytes_tpw(TPW, B);
     int cap = 0;
-    hipError_t e = mlp_capacity<NBT, TPW, FAST, FULL>(lds, &cap);
+    hipError_t e = mlp_capacity<NBT, TPW, FAST, FULL, HF>(lds, &cap);
     if (e != hipSuccess) return e;
     // Clusters per launch: every workgroup that polls must be resident together with its
     // peers.  Workgroups of unused slots exit at once and free their compute unit, so only
     // the working ones count.
-    const int per_launch = cap / G < kMlpPack ? cap / G : kMlpPack;
+    const int per_launch = cap / (G * HF) < kMlpPack ? cap / (G * HF) : kMlpPack;
+    if (HF == 2 && per_launch < nact) {
+        *declined = true;
+        return hipSuccess;
+    }
     if (per_launch < 1) return hipErrorLaunchOutOfResources;
     unsigned long long *xrec = static_cast<unsigned long long *>(scratch);
-    int *errflag = reinterpret_cast<int *>(xrec + mlp_rec_words(n_clients));
+    unsigned long long *prec = xrec + mlp_rec_words(n_clients);
+    int *errflag = reinterpret_cast<int *>(xrec + mlp_all_words(n_clients));
     // step tags of this launch: never 0 (the cleared state) and never a tag that an
     // earlier launch may have left in the records
     if (*epoch == 0 || *epoch > 0xFFFFFFFFu - (uint32_t)max_m - 2u) {
-        k_zero_words<<<(unsigned)((mlp_rec_words(n_clients) + 255) / 256), 256, 0, s>>>(xrec, mlp_rec_words(n_clients));
+        k_zero_words<<<(unsigned)((mlp_all_words(n_clients) + 255) / 256), 256, 0, s>>>(xrec, mlp_all_words(n_clients));
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         *epoch = 1;
@@ -605,11 +661,11 @@ static hipError_t mlp_launch(hipStream_t s, Profiler *prof, const RoundParams *h
     for (int a0 = 0; a0 < nact; a0 += per_launch) {
         const int here = (nact - a0 < per_launch) ? nact - a0 : per_launch;
         const int groups = (here + 7) / 8;  // clients per XCD in this launch
-        const unsigned grid = (unsigned)(8 * groups * G);
+        const unsigned grid = (unsigned)(8 * groups * G * HF);
         MlpPack pack;
         for (int j = 0; j < here; ++j) pack.p[j] = hp[a0 + j];
         if (prof && prof->on[F_MLP_ROUND]) prof->before(F_MLP_ROUND, s);
-        k_mlp_round<NBT, TPW, FAST, FULL><<<grid, kMlpThreads, lds, s>>>(pack, here, a0, Wg, D, H, C, G, xrec, tag0, errflag);
+        k_mlp_round<NBT, TPW, FAST, FULL, HF><<<grid, kMlpThreads, lds, s>>>(pack, here, a0, Wg, D, H, C, G, xrec, prec, tag0, errflag);
         if (prof && prof->on[F_MLP_ROUND]) prof->after(F_MLP_ROUND, s);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
@@ -624,11 +680,22 @@ hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *hp
     const bool small = mlp_tpw(D) == 2;  // at most 2 K tiles per wave
     const bool fast = (D & 15) == 0;
     const bool full = D == 16 * kMlpWaves * mlp_tpw(D);   // no pad tiles
+    // wide inputs: two workgroups per unit group, half of the columns each, when every active
+    // client gets its 2 G workgroups resident in one launch
+    if (!small && ((D + 15) / 16 + 1) / 2 <= kMlpWaves * kMlpHalfTPW) {
+        bool declined = false;
+        hipError_t e;
+        if (B == 16) e = fast ? mlp_launch<1, kMlpHalfTPW, true, false, 2>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch, &declined)
+                              : mlp_launch<1, kMlpHalfTPW, false, false, 2>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch, &declined);
+        else e = fast ? mlp_launch<2, kMlpHalfTPW, true, false, 2>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch, &declined)
+                      : mlp_launch<2, kMlpHalfTPW, false, false, 2>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch, &declined);
+        if (e != hipSuccess || !declined) return e;
+    }
 #define AET_MLP_CASE(nbt, tpw)                                                                        \
     do {                                                                                              \
-        if (full) return mlp_launch<nbt, tpw, true, true>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);   \
-        if (fast) return mlp_launch<nbt, tpw, true, false>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);  \
-        return mlp_launch<nbt, tpw, false, false>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);           \
+        if (full) return mlp_launch<nbt, tpw, true, true, 1>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);   \
+        if (fast) return mlp_launch<nbt, tpw, true, false, 1>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);  \
+        return mlp_launch<nbt, tpw, false, false, 1>(s, prof, hp, nact, max_m, Wg, D, H, C, scratch, n_clients, epoch);           \
     } while (0)
     if (B == 16) {
         if (small) AET_MLP_CASE(1, 2);
@@ -642,14 +709,14 @@ hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *hp
 hipError_t mlp_clear_error_flag(hipStream_t s, void *scratch, int n_clients, int B) {
     (void)B;
     unsigned long long *xrec = static_cast<unsigned long long *>(scratch);
-    k_zero_words<<<1, 64, 0, s>>>(xrec + mlp_rec_words(n_clients), 1);
+    k_zero_words<<<1, 64, 0, s>>>(xrec + mlp_all_words(n_clients), 1);
     return hipGetLastError();
 }
 
 const int *mlp_error_flag_ptr(void *scratch, int n_clients, int B) {
     (void)B;
     unsigned long long *xrec = static_cast<unsigned long long *>(scratch);
-    return reinterpret_cast<const int *>(xrec + mlp_rec_words(n_clients));
+    return reinterpret_cast<const int *>(xrec + mlp_all_words(n_clients));
 }
 
 }  // namespace aet
