@@ -26,7 +26,14 @@
 //     layout the forward pass uses as its B operand, so  w <- w - eta g  and  U <- U + g
 //     are applied to the register-resident slice in place (g never exists in memory).
 //
-// All G workgroups of a client must be resident together: the launcher never has more
+// Wide inputs (more than 32 column tiles) with few enough clients take two workgroups per
+// unit group: each owns half of the input columns (its half of the W1 / U1 slice, of the
+// sampled rows, of the forward and of the backward product); the two add their partial
+// hidden sums through a second tagged exchange and then compute the same h, logits and
+// second-layer updates side by side.  16 clients x 8 unit groups then occupy all 256
+// compute units instead of 128.
+//
+// All workgroups of a client must be resident together: the launcher never has more
 // working workgroups in flight than the device holds (1 per compute unit with this LDS
 // footprint).  The poll is bounded: on expiry an error flag is raised and every workgroup
 // still runs to the end, so the grid always drains.
