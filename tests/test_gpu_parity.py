@@ -91,6 +91,15 @@ def small_cases():
     # dense-ReLU-dense kernel (896 columns, 256 hidden units = 16 workgroups per client) ...
     wl = W.config2(n_clients=2, n_total=2 * 120, d=896, hidden=256, batch=16, rounds=3, a=16, b=16)
     cases["mlp_fused_widest"] = wl
+    # wide inputs run two workgroups per unit group (half of the columns each): a width that
+    # is not a multiple of 16 (ragged last tile in the second half), B = 16, and more clients
+    # than fit one launch that way (20 x 8 x 2 workgroups: falls back to one per unit group)
+    wl = W.config2(n_clients=3, n_total=3 * 100, d=777, hidden=64, batch=32, rounds=3, a=32, b=32)
+    cases["mlp_fused_pair_ragged_width"] = wl
+    wl = W.config2(n_clients=2, n_total=2 * 100, d=530, hidden=32, batch=16, rounds=3, a=16, b=16)
+    cases["mlp_fused_pair_b16_ragged"] = wl
+    wl = W.config2(n_clients=20, n_total=20 * 64, d=784, hidden=128, batch=32, rounds=2, a=32, b=32)
+    cases["mlp_fused_wide_20_clients"] = wl
     # ... and of the softmax-regression kernel: 6 columns per thread with a ragged tail,
     # exactly 2 columns per thread, one column more than 1 per thread
     wl = W.config1(n_clients=3, n_per=40, d=3000, rounds=3, a=2, b=2)
