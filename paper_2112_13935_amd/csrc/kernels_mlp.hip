@@ -257,6 +257,13 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     bool dead = false;  // the poll expired: keep going, the host will see the flag
     __syncthreads();
 
+    auto park_rows = [&]() {
+#pragma unroll
+        for (int bt = 0; bt < NBT; ++bt)
+#pragma unroll
+            for (int tt = 0; tt < TPW; ++tt)
+                *reinterpret_cast<f4 *>(Xs + (16 * bt + li) * ld + col0 + 16 * tt + 4 * lg) = xreg[bt][tt];
+    };
     for (int u = 0; u < p.m; ++u) {
         // ---- z1 partial sums on the matrix cores ----------------------------------------
         {
@@ -272,12 +279,10 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                     for (int bt = 0; bt < NBT; ++bt) acc[bt] = mfma16(xreg[bt][tt][r], W1r[tt][r], acc[bt]);
             }
             // the backward product needs the rows transposed: park them in LDS (this wave's
-            // columns only, so no barrier; the writes drain while the logits are exchanged)
-#pragma unroll
-            for (int bt = 0; bt < NBT; ++bt)
-#pragma unroll
-                for (int tt = 0; tt < TPW; ++tt)
-                    *reinterpret_cast<f4 *>(Xs + (16 * bt + li) * ld + col0 + 16 * tt + 4 * lg) = xreg[bt][tt];
+            // columns only, so no barrier; the writes drain while the logits are exchanged).
+            // With two workgroups per unit group they are parked between the post and the
+            // poll of the pair exchange instead.
+            if constexpr (HF == 1) park_rows();
 #pragma unroll
             for (int bt = 0; bt < NBT; ++bt)
 #pragma unroll
@@ -285,6 +290,14 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                     red[(wave * B + 16 * bt + 4 * lg + r) * 16 + li] = acc[bt][r];
         }
         __syncthreads();
+        // the rows the next recursion samples (Algorithm 2: "sample xi from D_c"; a counter
+        // hash, so they are known ahead); with two workgroups per unit group the hash is
+        // computed while the pair exchange is in flight
+        uint32_t rowv = 0;
+        const bool more = u + 1 < p.m;
+        auto next_rows = [&]() {
+            if (more && lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)(u + 1) * B + lane), p.n_samples);
+        };
         // ---- h = relu(z1 + b1) ----------------------------------------------------------
         const uint32_t tag = tag0 + (uint32_t)u;
         if constexpr (HF == 1) {
@@ -306,6 +319,8 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                 const unsigned long long word = ((unsigned long long)tag << 32) | (unsigned long long)__float_as_uint(own);
                 __hip_atomic_store(pr + hf * kMlpPair + i, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+            park_rows();
+            next_rows();
             const unsigned long long *theirs = pr + (1 - hf) * kMlpPair + min(i, B * 16 - 1);
             unsigned long long v = 0;
             int spins = 0;
@@ -349,8 +364,6 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         // known ahead of time).  Loads of one wave return in order, so nothing is issued
         // before the exchange poll.
         int labn = 0;
-        uint32_t rowv = 0;
-        const bool more = u + 1 < p.m;
         // the rows' indices and the labels now; the row loads themselves are issued a few at
         // a time between the first tiles of the backward product, so that a wave that has to
         // wait for room in the memory pipeline leaves the matrix core to the SIMD's other
@@ -358,7 +371,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         gcf_ptr myrow[NBT];
         auto prefetch_rows = [&]() {
             if (!more) return;
-            if (lane < B) rowv = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)(u + 1) * B + lane), p.n_samples);
+            if constexpr (HF == 1) next_rows();
             if (wave == 0 && lane < B) labn = yg[rowv];
 #pragma unroll
             for (int bt = 0; bt < NBT; ++bt) myrow[bt] = lane_src + (int64_t)__shfl(rowv, 16 * bt + li) * D;
