@@ -119,7 +119,8 @@ bool make_layout(const LayerGeom *lay, int L, int64_t P, int B, int n, int infli
     lo->arrivals = take((size_t)n * inflight * sizeof(Arrival));
     lo->debug = take((size_t)kDebugIdx * 4);
     lo->labels = take((size_t)n * B * 4);
-    lo->fused = take(mlp_round_scratch_bytes(n, B));
+    // exchange records of the fused dense-ReLU-dense engine, only for models it runs
+    lo->fused = take(pick_engine(lay, L, B) == ENGINE_MLP ? mlp_round_scratch_bytes(n, B) : 0);
     size_t wg_floats = 0;
     for (int l = 0; l < L; ++l)
         if (lay[l].type == AET_CONV && conv_wgrad_mfma_supported(lay[l], B))
@@ -321,7 +322,8 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_params[r], hipEventDisableTiming);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_arr[r], hipEventDisableTiming);
     }
-    if (e == hipSuccess) e = mlp_clear_error_flag(ctx->stream, ctx->ws + ctx->lo.fused, n_clients, ctx->B);
+    if (e == hipSuccess && ctx->engine == ENGINE_MLP)
+        e = mlp_clear_error_flag(ctx->stream, ctx->ws + ctx->lo.fused, n_clients, ctx->B);
     // global model and every replica start as w0
     if (e == hipSuccess) e = hipMemcpyAsync(ctx->W0(), w0, (size_t)ctx->P * 4, hipMemcpyHostToDevice, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // w0 is the caller's; do not keep reading it
