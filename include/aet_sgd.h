@@ -139,6 +139,28 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
                     size_t workspace_bytes, int32_t max_inflight, int32_t max_rounds,
                     void *hip_stream);
 
+/* aet_init for callers that cannot allocate device or pinned host memory (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): the context's
+ * workspace is an array inside the library, AET_STATIC_WORKSPACE_BYTES per GPU, held from
+ * the moment the library is loaded until the process ends.  This call and every later call
+ * on such a context allocate nothing with HIP: no hipMalloc / hipHostMalloc / hipFree, no
+ * events; the round and arrival records reach the device in kernel arguments instead of
+ * through pinned staging buffers.
+ *   w0_dev   DEVICE, P floats, canonical layout (read before the call returns)
+ *   the other arguments as for aet_init; the context lives on the current device.
+ * AET_ENOMEM (with the two sizes in aet_last_error(NULL)) when
+ * aet_workspace_bytes(model, n_clients, max_inflight, max_rounds) exceeds
+ * AET_STATIC_WORKSPACE_BYTES.  Every such context on one GPU uses the same array, which
+ * keeps what the last one left (the part the new context uses is cleared by this call):
+ * only ONE may be alive per GPU at a time -- a second aet_init_static on that GPU before
+ * aet_destroy of the first returns AET_ESTATE -- and work of a destroyed context that is
+ * still running on another stream would race with the new one (aet_destroy synchronises
+ * the context's own stream).  Contexts made by aet_init are not affected. */
+#define AET_STATIC_WORKSPACE_BYTES (64 * 1024 * 1024)
+aet_status aet_init_static(aet_ctx **out, const aet_model_desc *model, int32_t n_clients,
+                           const aet_shard *shards, const float *w0_dev, uint64_t seed,
+                           int32_t max_inflight, int32_t max_rounds, void *hip_stream);
+
 /* One tick of local rounds (Algorithm 2, MainComputeNode: one pass of the round loop for
  * every client that is idle, has rounds left and passes the delay checkpoint).  Such a
  * client c, at its round i:

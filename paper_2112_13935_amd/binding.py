@@ -24,7 +24,7 @@ EXPORTS = [
     "aet_last_error", "aet_destroy", "aet_reset", "aet_profile_families",
     "aet_profile_family_name", "aet_profile_enable", "aet_profile_read", "aet_run_ticks",
     "aet_topology_workspace_bytes", "aet_set_topology", "aet_receive", "aet_set_setup",
-    "aet_set_weights",
+    "aet_set_weights", "aet_init_static",
 ]
 
 
@@ -83,6 +83,9 @@ def load_library():
     lib.aet_init.restype = C.c_int
     lib.aet_init.argtypes = [C.POINTER(vp), C.POINTER(aet_model_desc), i32, C.POINTER(aet_shard),
                              vp, u64, vp, C.c_size_t, i32, i32, vp]
+    lib.aet_init_static.restype = C.c_int
+    lib.aet_init_static.argtypes = [C.POINTER(vp), C.POINTER(aet_model_desc), i32, C.POINTER(aet_shard),
+                                    vp, u64, i32, i32, vp]
     lib.aet_run_round.restype = C.c_int
     lib.aet_run_round.argtypes = [vp, C.POINTER(aet_threshold), C.POINTER(aet_eta),
                                   C.POINTER(aet_delay), C.POINTER(i32), vp, vp]
@@ -155,7 +158,9 @@ class AetSgd:
 
     def __init__(self, model, shards_X: Sequence[torch.Tensor], shards_y: Sequence[torch.Tensor],
                  w0: np.ndarray, seed: int, max_inflight: int = 1, max_rounds: int = 64,
-                 stream: Optional[torch.cuda.Stream] = None):
+                 stream: Optional[torch.cuda.Stream] = None, static_workspace: bool = False):
+        """static_workspace: create the context with aet_init_static (the library's own
+        workspace, w0 handed over as a device tensor) instead of aet_init."""
         self.lib = load_library()
         self.n = len(shards_X)
         self._desc = model_desc(model)
@@ -172,9 +177,10 @@ class AetSgd:
         if nbytes == 0:
             raise AetError(AET_EINVAL, "aet_workspace_bytes rejected the arguments")
         self.workspace_bytes = nbytes
-        self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
-        base = self._ws.data_ptr()
-        self._ws_ptr = (base + 255) & ~255
+        if not static_workspace:
+            self._ws = torch.empty(nbytes + 256, dtype=torch.uint8, device=self.device)
+            base = self._ws.data_ptr()
+            self._ws_ptr = (base + 255) & ~255
         sh = (aet_shard * self.n)()
         for c, (x, y) in enumerate(zip(shards_X, shards_y)):
             sh[c] = aet_shard(x.data_ptr(), y.data_ptr(), x.shape[0])
@@ -183,9 +189,16 @@ class AetSgd:
             raise ValueError(f"w0 has {self._w0.size} entries, model has {self.P} parameters")
         self.stream = stream if stream is not None else torch.cuda.current_stream(self.device)
         ctx = C.c_void_p()
-        rc = self.lib.aet_init(C.byref(ctx), C.byref(self._desc), self.n, sh, _hptr(self._w0),
-                               C.c_uint64(seed), C.c_void_p(self._ws_ptr), nbytes, max_inflight,
-                               max_rounds, C.c_void_p(self.stream.cuda_stream))
+        if static_workspace:
+            self._w0_dev = torch.from_numpy(self._w0).to(self.device)
+            torch.cuda.synchronize(self.device)
+            rc = self.lib.aet_init_static(C.byref(ctx), C.byref(self._desc), self.n, sh,
+                                          C.c_void_p(self._w0_dev.data_ptr()), C.c_uint64(seed),
+                                          max_inflight, max_rounds, C.c_void_p(self.stream.cuda_stream))
+        else:
+            rc = self.lib.aet_init(C.byref(ctx), C.byref(self._desc), self.n, sh, _hptr(self._w0),
+                                   C.c_uint64(seed), C.c_void_p(self._ws_ptr), nbytes, max_inflight,
+                                   max_rounds, C.c_void_p(self.stream.cuda_stream))
         if rc != AET_OK:
             raise AetError(rc, self.lib.aet_last_error(None).decode())
         self.ctx = ctx

@@ -18,6 +18,46 @@
 
 using namespace aet;
 
+// ---- workspace inside the library, for aet_init_static ---------------------------------
+// One array per GPU (every device that loads the code object holds its own copy at its own
+// address).  Host code never uses the array's name as an address: the device address is
+// looked up once per device (scratch_address) and that pointer is what kernels, copies and
+// clears get.
+static constexpr size_t kStaticBytes = (size_t)AET_STATIC_WORKSPACE_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+static constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices] = {};
+static const aet_ctx *g_scratch_owner[kMaxDevices] = {};
+
+static hipError_t scratch_address(int dev, void **ptr) {
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return hipSuccess;
+}
+
+// Records that a context without pinned staging buffers hands to the device: they travel
+// in the kernel arguments and one small kernel drops them where the round / server kernels
+// read them (stream-ordered, so nothing has to be fenced).
+constexpr int kPutParams = 48;
+struct ParamsPut { RoundParams p[kPutParams]; };
+__global__ void k_put_params(const ParamsPut pack, int count, RoundParams *__restrict__ dst) {
+    if ((int)threadIdx.x < count) dst[threadIdx.x] = pack.p[threadIdx.x];
+}
+constexpr int kPutArrivals = 224;
+struct ArrivalsPut { Arrival a[kPutArrivals]; };
+__global__ void k_put_arrivals(const ArrivalsPut pack, int count, Arrival *__restrict__ dst) {
+    if ((int)threadIdx.x < count) dst[threadIdx.x] = pack.a[threadIdx.x];
+}
+__global__ void k_clear_bytes16(uint4 *__restrict__ p, size_t n16) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n16) p[i] = uint4{0u, 0u, 0u, 0u};
+}
+
 namespace {
 
 constexpr int kRing = 4;            // pinned staging buffers in flight
@@ -47,6 +87,7 @@ struct Layout {
 std::string g_init_error;
 
 size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
 
 // Geometry of every layer, or false if the description is not supported.
 bool resolve(const aet_model_desc *m, LayerGeom *lay, int64_t *P, std::string *why) {
@@ -160,6 +201,12 @@ struct aet_ctx {
     Arrival *h_arr[kRing] = {};
     hipEvent_t ev_params[kRing] = {}, ev_arr[kRing] = {};
     int ring_p = 0, ring_a = 0;
+    // a context on the library's own workspace has no pinned rings: its records reach the
+    // device through kernel arguments, staged in these host vectors
+    bool static_ws = false;
+    int device = -1;
+    std::vector<RoundParams> v_params;
+    std::vector<Arrival> v_arr;
     bool dead = false;
     // peer-to-peer form: neighbour lists (host copy and device copy in the caller's buffer)
     bool p2p = false;
@@ -257,18 +304,36 @@ size_t aet_workspace_bytes(const aet_model_desc *model, int32_t n_clients, int32
     return lo.total;
 }
 
-aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_clients,
-                    const aet_shard *shards, const float *w0, uint64_t seed, void *workspace,
-                    size_t workspace_bytes, int32_t max_inflight, int32_t max_rounds,
-                    void *hip_stream) {
+// Both forms of Setup.  static_ws: the workspace is the library's own array on the current
+// device, w0 is a DEVICE pointer, and nothing is allocated with HIP (no pinned rings, no
+// events).
+static aet_status init_context(aet_ctx **out, const aet_model_desc *model, int32_t n_clients,
+                               const aet_shard *shards, const float *w0, uint64_t seed, void *workspace,
+                               size_t workspace_bytes, int32_t max_inflight, int32_t max_rounds,
+                               void *hip_stream, bool static_ws) {
     if (!out) return fail(nullptr, AET_EINVAL, "out is NULL");
     *out = nullptr;
-    if (!model || !shards || !w0 || !workspace) return fail(nullptr, AET_EINVAL, "NULL argument");
+    if (!model || !shards || !w0 || (!workspace && !static_ws)) return fail(nullptr, AET_EINVAL, "NULL argument");
     if (n_clients < 1 || n_clients > 65535) return fail(nullptr, AET_EINVAL, "n_clients must be 1..65535");
     if (max_inflight < 1 || max_rounds < 1) return fail(nullptr, AET_EINVAL, "max_inflight and max_rounds must be >= 1");
     if (reinterpret_cast<uintptr_t>(workspace) & 255) return fail(nullptr, AET_EINVAL, "workspace must be 256-byte aligned");
+    int dev = -1;
+    if (static_ws) {
+        // the library's array on the current device: its address once per device, one
+        // context at a time
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return fail(nullptr, AET_EHIP, "hipGetDevice: %s", hipGetErrorString(e));
+        if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, AET_EINVAL, "device ordinal %d not supported", dev);
+        if (g_scratch_owner[dev])
+            return fail(nullptr, AET_ESTATE, "the library's workspace on device %d belongs to a live context: destroy it first", dev);
+        e = scratch_address(dev, &workspace);
+        if (e != hipSuccess) return fail(nullptr, AET_EHIP, "hipGetSymbolAddress: %s", hipGetErrorString(e));
+        workspace_bytes = kStaticBytes;
+    }
     aet_ctx *ctx = new (std::nothrow) aet_ctx();
     if (!ctx) return fail(nullptr, AET_ENOMEM, "host allocation failed");
+    ctx->static_ws = static_ws;
+    ctx->device = dev;
     std::string why;
     if (!resolve(model, ctx->lay, &ctx->P, &why)) {
         delete ctx;
@@ -284,6 +349,8 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
     if (workspace_bytes < ctx->lo.total) {
         const size_t need = ctx->lo.total;
         delete ctx;
+        if (static_ws)
+            return fail(nullptr, AET_ENOMEM, "this model and client count need %zu bytes of workspace, the library's own holds %zu: use aet_init with a workspace of your own", need, workspace_bytes);
         return fail(nullptr, AET_ENOMEM, "workspace too small: %zu bytes given, %zu needed", workspace_bytes, need);
     }
     for (int c = 0; c < n_clients; ++c) {
@@ -316,7 +383,15 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
     ctx->engine = pick_engine(ctx->lay, ctx->L, ctx->B);
 
     hipError_t e = hipSuccess;
-    for (int r = 0; r < kRing && e == hipSuccess; ++r) {
+    if (static_ws) {
+        // the array keeps what the last context left: everything this one will use starts at zero
+        const size_t n16 = (ctx->lo.total + 15) / 16;
+        k_clear_bytes16<<<(unsigned)((n16 + 255) / 256), 256, 0, ctx->stream>>>(reinterpret_cast<uint4 *>(ctx->ws), n16);
+        e = hipGetLastError();
+        ctx->v_params.resize(n_clients);
+        ctx->v_arr.resize((size_t)n_clients * max_inflight);
+    }
+    for (int r = 0; r < kRing && e == hipSuccess && !static_ws; ++r) {
         e = hipHostMalloc(reinterpret_cast<void **>(&ctx->h_params[r]), (size_t)n_clients * sizeof(RoundParams), hipHostMallocDefault);
         if (e == hipSuccess) e = hipHostMalloc(reinterpret_cast<void **>(&ctx->h_arr[r]), (size_t)n_clients * max_inflight * sizeof(Arrival), hipHostMallocDefault);
         if (e == hipSuccess) e = hipEventCreateWithFlags(&ctx->ev_params[r], hipEventDisableTiming);
@@ -325,7 +400,7 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
     if (e == hipSuccess && ctx->engine == ENGINE_MLP)
         e = mlp_clear_error_flag(ctx->stream, ctx->ws + ctx->lo.fused, n_clients, ctx->B);
     // global model and every replica start as w0
-    if (e == hipSuccess) e = hipMemcpyAsync(ctx->W0(), w0, (size_t)ctx->P * 4, hipMemcpyHostToDevice, ctx->stream);
+    if (e == hipSuccess) e = hipMemcpyAsync(ctx->W0(), w0, (size_t)ctx->P * 4, static_ws ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // w0 is the caller's; do not keep reading it
     if (e == hipSuccess) e = hipMemcpyAsync(ctx->Wg(), ctx->W0(), (size_t)ctx->P * 4, hipMemcpyDeviceToDevice, ctx->stream);
     if (e == hipSuccess) e = launch_broadcast_model(ctx->stream, ctx->Wc(0), ctx->Ps, n_clients, ctx->W0());
@@ -334,8 +409,24 @@ aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_client
         aet_destroy(ctx);
         return st;
     }
+    if (static_ws) g_scratch_owner[dev] = ctx;
     *out = ctx;
     return AET_OK;
+}
+
+aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_clients,
+                    const aet_shard *shards, const float *w0, uint64_t seed, void *workspace,
+                    size_t workspace_bytes, int32_t max_inflight, int32_t max_rounds,
+                    void *hip_stream) {
+    return init_context(out, model, n_clients, shards, w0, seed, workspace, workspace_bytes,
+                        max_inflight, max_rounds, hip_stream, false);
+}
+
+aet_status aet_init_static(aet_ctx **out, const aet_model_desc *model, int32_t n_clients,
+                           const aet_shard *shards, const float *w0_dev, uint64_t seed,
+                           int32_t max_inflight, int32_t max_rounds, void *hip_stream) {
+    return init_context(out, model, n_clients, shards, w0_dev, seed, nullptr, 0, max_inflight,
+                        max_rounds, hip_stream, true);
 }
 
 aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *eta,
@@ -401,8 +492,8 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         // staging: the layer engine copies the records to the device from a pinned ring;
         // the dense-ReLU-dense engine takes them in its kernel arguments from plain host memory
         const int ring = ctx->ring_p;
-        RoundParams *hp = ctx->h_params[ring];
-        if (ctx->engine != ENGINE_MLP) {
+        RoundParams *hp = ctx->static_ws ? ctx->v_params.data() : ctx->h_params[ring];
+        if (ctx->engine != ENGINE_MLP && !ctx->static_ws) {
             ctx->ring_p = (ring + 1) % kRing;
             AET_HIP(ctx, hipEventSynchronize(ctx->ev_params[ring]));
         }
@@ -421,8 +512,18 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         RoundParams *dp = hp;
         if (ctx->engine != ENGINE_MLP) {
             dp = reinterpret_cast<RoundParams *>(ctx->ws + ctx->lo.params);
-            AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
-            AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
+            if (ctx->static_ws) {
+                for (int a0 = 0; a0 < nact; a0 += kPutParams) {
+                    const int here = std::min(kPutParams, nact - a0);
+                    ParamsPut put;
+                    std::memcpy(put.p, hp + a0, (size_t)here * sizeof(RoundParams));
+                    k_put_params<<<1, 64, 0, ctx->stream>>>(put, here, dp + a0);
+                    AET_HIP(ctx, hipGetLastError());
+                }
+            } else {
+                AET_HIP(ctx, hipMemcpyAsync(dp, hp, (size_t)nact * sizeof(RoundParams), hipMemcpyHostToDevice, ctx->stream));
+                AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));
+            }
         }
         // server form: every round starts from the global model; peer-to-peer form: from the
         // client's own replica
@@ -469,7 +570,10 @@ static aet_status stage_arrivals(aet_ctx *ctx, float scale, std::vector<Msg> *ar
     if (na == 0) return AET_OK;
     Arrival *dst = pack->a;
     int ring = -1;
-    if (na > kArrivalPack) {
+    if (na > kArrivalPack && ctx->static_ws) {
+        ring = kRing;  // no ring: staged in host memory, handed over in kernel arguments
+        dst = ctx->v_arr.data();
+    } else if (na > kArrivalPack) {
         ring = ctx->ring_a;
         ctx->ring_a = (ring + 1) % kRing;
         AET_HIP(ctx, hipEventSynchronize(ctx->ev_arr[ring]));
@@ -484,8 +588,18 @@ static aet_status stage_arrivals(aet_ctx *ctx, float scale, std::vector<Msg> *ar
         *pack_out = pack;
     } else {
         Arrival *da = reinterpret_cast<Arrival *>(ctx->ws + ctx->lo.arrivals);
-        AET_HIP(ctx, hipMemcpyAsync(da, dst, (size_t)na * sizeof(Arrival), hipMemcpyHostToDevice, ctx->stream));
-        AET_HIP(ctx, hipEventRecord(ctx->ev_arr[ring], ctx->stream));
+        if (ring == kRing) {
+            for (int a0 = 0; a0 < na; a0 += kPutArrivals) {
+                const int here = std::min(kPutArrivals, na - a0);
+                ArrivalsPut put;
+                std::memcpy(put.a, dst + a0, (size_t)here * sizeof(Arrival));
+                k_put_arrivals<<<1, 256, 0, ctx->stream>>>(put, here, da + a0);
+                AET_HIP(ctx, hipGetLastError());
+            }
+        } else {
+            AET_HIP(ctx, hipMemcpyAsync(da, dst, (size_t)na * sizeof(Arrival), hipMemcpyHostToDevice, ctx->stream));
+            AET_HIP(ctx, hipEventRecord(ctx->ev_arr[ring], ctx->stream));
+        }
         *dev_out = da;
     }
     return AET_OK;
@@ -780,6 +894,7 @@ const char *aet_last_error(const aet_ctx *ctx) { return ctx ? ctx->err.c_str() :
 void aet_destroy(aet_ctx *ctx) {
     if (!ctx) return;
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->static_ws && ctx->device >= 0 && g_scratch_owner[ctx->device] == ctx) g_scratch_owner[ctx->device] = nullptr;
     for (int r = 0; r < kRing; ++r) {
         if (ctx->h_params[r]) (void)hipHostFree(ctx->h_params[r]);
         if (ctx->h_arr[r]) (void)hipHostFree(ctx->h_arr[r]);

@@ -19,13 +19,15 @@ def upload(wl, device="cuda:0", n_clients: Optional[int] = None):
 
 
 class Run:
-    def __init__(self, wl, device="cuda:0", shards=None, max_rounds: Optional[int] = None):
+    def __init__(self, wl, device="cuda:0", shards=None, max_rounds: Optional[int] = None,
+                 static_workspace: bool = False):
         self.wl = wl
         self.X, self.y = shards if shards is not None else upload(wl, device)
         self.n = len(self.X)
         self.lib = AetSgd(wl.model, self.X, self.y, wl.w0, wl.seed,
                           max_inflight=wl.delay_max + 1,
-                          max_rounds=max(1, wl.rounds if max_rounds is None else max_rounds))
+                          max_rounds=max(1, wl.rounds if max_rounds is None else max_rounds),
+                          static_workspace=static_workspace)
         if getattr(wl, "setup_weights", None) is not None and self.n == wl.n_clients:
             self.lib.aet_set_setup(wl.setup_weights, wl.setup_seed)
         self.p2p = getattr(wl, "topology", None) is not None and self.n == wl.n_clients
