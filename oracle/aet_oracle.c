@@ -75,6 +75,8 @@ typedef struct {
 typedef struct {
     int64_t s, m, q0, t0, start_tick, arrival;
     double eta, loss;
+    int64_t kink_events;     /* near-kink decisions met in the round (kink analysis on) */
+    double *kink_allow;      /* per parameter tensor: sum of the jumps those would cause */
 } rinfo_t;
 
 typedef struct orc_ctx {
@@ -98,6 +100,8 @@ typedef struct orc_ctx {
     msg_t *queue; int n_queue, cap_queue;
     rinfo_t **rinfo; int *n_rinfo, *cap_rinfo;
     int64_t *ev_tick; int32_t *ev_c, *ev_k; int64_t n_ev, cap_ev;
+    double kink_eps;         /* > 0: kink analysis with this relative margin */
+    int n_tensors;           /* parameter tensors: weights and bias of every conv / dense layer */
     char err[256];
 } orc_ctx;
 
@@ -126,7 +130,7 @@ uint64_t orc_stream(uint64_t seed, uint64_t tag, uint64_t c, uint64_t ctr) {
 static uint32_t to_range(uint64_t h, uint64_t range) {
     return (uint32_t)(((h >> 32) * range) >> 32);
 }
-/* Algorithm 2, "Sample uniformly at random xi from D_c": index of the q-th sample that
+/* Algorithm 2, sampling step of MainComputeNode: index of the q-th sample that
  * client c draws, uniform on [0, n_samples), with replacement. */
 int32_t orc_sample_index(uint64_t seed, int32_t c, int64_t q, int64_t n_samples) {
     return (int32_t)to_range(orc_stream(seed, TAG_SAMPLE, (uint64_t)c, (uint64_t)q),
@@ -368,13 +372,263 @@ double orc_batch_loss_grad(const orc_model *m, const real *w, const float *X, co
 }
 
 /* ------------------------------------------------------------------------------------
+ * Kinks (bookkeeping for the parity tolerance; not part of what the method computes).
+ *
+ * f(w; xi) is piecewise smooth in w: grad f jumps where the pre-activation of a ReLU unit
+ * crosses zero and where the two largest entries of a pooling window cross.  Another
+ * implementation of the same recursion (another precision, another summation order) can
+ * land on the other side of such a point; from there on its w and U differ from this
+ * oracle's by the jump, whatever the quality of its arithmetic.  For one sample whose
+ * forward and backward pass has just run (the scratch still holds activations and deltas)
+ * the functions below find the decisions that lie within a relative margin eps of
+ * flipping,
+ *     ReLU unit:    |z| < eps * (|b| + sum |w| |x|)              (z its pre-activation)
+ *     pool window:  best - second < eps * max(scale of the two)  (scale as above, of the
+ *                   units that produced the two entries; only windows with best > 0)
+ * and, for each, the change of the sample's gradient if that one decision flipped:
+ *     ReLU unit:    the unit's incoming delta, taken as a one-hot delta at its layer and
+ *                   carried down through the layers below with their decisions as they are;
+ *     pool window:  that delta moved from the winning entry to the runner-up.
+ * Per parameter tensor the largest entry of each such change is added up (kink_t.allow).
+ * ---------------------------------------------------------------------------------- */
+typedef struct {
+    double eps;
+    int64_t events;
+    double *allow;                      /* per parameter tensor, in layer order: W then b */
+    real *jump;                         /* P entries, zero between events */
+    real *kd[ORC_MAX_LAYERS + 1];       /* delta of the flipped decision at every level */
+    real *scale[ORC_MAX_LAYERS];        /* |b| + sum |w||x| of every conv / dense output */
+    /* optional list of the events themselves (tests): layer, output index, whole jump */
+    int64_t rec_cap, rec_P;
+    int32_t *rec_layer; int64_t *rec_unit; real *rec_jump;
+} kink_t;
+
+static int kink_alloc(const lay_t *lay, int L, int64_t P, int n_tensors, double eps, kink_t *k) {
+    memset(k, 0, sizeof *k);
+    k->eps = eps;
+    k->allow = (double *)calloc(n_tensors > 0 ? n_tensors : 1, sizeof(double));
+    k->jump = (real *)calloc(P, sizeof(real));
+    if (!k->allow || !k->jump) return -1;
+    k->kd[0] = (real *)calloc(lay[0].in_size, sizeof(real));
+    if (!k->kd[0]) return -1;
+    for (int l = 0; l < L; ++l) {
+        k->kd[l + 1] = (real *)calloc(lay[l].out_size, sizeof(real));
+        if (!k->kd[l + 1]) return -1;
+        if (lay[l].type != ORC_POOL) {
+            k->scale[l] = (real *)calloc(lay[l].out_size, sizeof(real));
+            if (!k->scale[l]) return -1;
+        }
+    }
+    return 0;
+}
+static void kink_free(int L, kink_t *k) {
+    free(k->allow); free(k->jump);
+    for (int l = 0; l <= L; ++l) free(k->kd[l]);
+    for (int l = 0; l < L; ++l) free(k->scale[l]);
+}
+
+/* pre-activation z and its magnitude scale |b| + sum |w||x| of output o of a conv / dense layer */
+static void preactivation(const lay_t *q, const real *w, const real *in, int64_t o, real *z, real *sc) {
+    const real *W = w + q->w_off, *b = w + q->b_off;
+    real acc, mag;
+    if (q->type == ORC_DENSE) {
+        acc = b[o]; mag = (real)fabs((double)b[o]);
+        for (int64_t k = 0; k < q->in_size; ++k) {
+            const real t = W[o * q->in_size + k] * in[k];
+            acc += t; mag += (real)fabs((double)t);
+        }
+    } else {
+        const int co = (int)(o / ((int64_t)q->oh * q->ow));
+        const int oy = (int)((o / q->ow) % q->oh), ox = (int)(o % q->ow);
+        acc = b[co]; mag = (real)fabs((double)b[co]);
+        for (int ci = 0; ci < q->ic; ++ci)
+            for (int ky = 0; ky < q->k; ++ky) {
+                const int iy = oy + ky - q->pad;
+                if (iy < 0 || iy >= q->ih) continue;
+                for (int kx = 0; kx < q->k; ++kx) {
+                    const int ix = ox + kx - q->pad;
+                    if (ix < 0 || ix >= q->iw) continue;
+                    const real t = W[(((int64_t)co * q->ic + ci) * q->k + ky) * q->k + kx] *
+                                   in[((int64_t)ci * q->ih + iy) * q->iw + ix];
+                    acc += t; mag += (real)fabs((double)t);
+                }
+            }
+    }
+    *z = acc; *sc = mag;
+}
+
+/* The delta k->kd[top + 1] at the output of layer `top` (zero but for a few entries) carried
+ * down to the input: adds the parameter gradients it causes into k->jump.  Layers below
+ * `top` apply their ReLU decisions as the forward pass took them; layer `top` itself does
+ * only when mask_top is set (a flipped unit's own delta passes by definition). */
+static void carry_down(const lay_t *lay, int top, int mask_top, const real *w, const scratch_t *s, kink_t *k) {
+    for (int l = top; l >= 0; --l) {
+        const lay_t *q = &lay[l];
+        const real *in = s->act[l], *out = s->act[l + 1];
+        const real *dout = k->kd[l + 1];
+        real *din = k->kd[l];
+        const int masked = q->relu && (l < top || mask_top);
+        for (int64_t i = 0; i < q->in_size; ++i) din[i] = 0;
+        if (q->type == ORC_POOL) {
+            for (int64_t o = 0; o < q->out_size; ++o)
+                if (dout[o] != 0) din[s->amax[l][o]] += dout[o];
+        } else if (q->type == ORC_DENSE) {
+            const real *W = w + q->w_off;
+            for (int o = 0; o < q->oc; ++o) {
+                real d = dout[o];
+                if (masked && !(out[o] > 0)) d = 0;
+                if (d == 0) continue;
+                k->jump[q->b_off + o] += d;
+                for (int64_t j = 0; j < q->in_size; ++j) {
+                    k->jump[q->w_off + (int64_t)o * q->in_size + j] += d * in[j];
+                    din[j] += d * W[(int64_t)o * q->in_size + j];
+                }
+            }
+        } else {
+            const real *W = w + q->w_off;
+            for (int co = 0; co < q->oc; ++co)
+                for (int oy = 0; oy < q->oh; ++oy)
+                    for (int ox = 0; ox < q->ow; ++ox) {
+                        const int64_t o = ((int64_t)co * q->oh + oy) * q->ow + ox;
+                        real d = dout[o];
+                        if (masked && !(out[o] > 0)) d = 0;
+                        if (d == 0) continue;
+                        k->jump[q->b_off + co] += d;
+                        for (int ci = 0; ci < q->ic; ++ci)
+                            for (int ky = 0; ky < q->k; ++ky) {
+                                const int iy = oy + ky - q->pad;
+                                if (iy < 0 || iy >= q->ih) continue;
+                                for (int kx = 0; kx < q->k; ++kx) {
+                                    const int ix = ox + kx - q->pad;
+                                    if (ix < 0 || ix >= q->iw) continue;
+                                    const int64_t wi = (((int64_t)co * q->ic + ci) * q->k + ky) * q->k + kx;
+                                    const int64_t ii = ((int64_t)ci * q->ih + iy) * q->iw + ix;
+                                    k->jump[q->w_off + wi] += d * in[ii];
+                                    din[ii] += d * W[wi];
+                                }
+                            }
+                    }
+        }
+    }
+}
+
+/* after carry_down: per tensor, add the largest |entry| of the jump to the allowance and
+ * clear the jump again (layers 0..top only were touched) */
+static void book_jump(const lay_t *lay, int top, int ev_layer, int64_t ev_unit, kink_t *k) {
+    int t = 0;
+    if (k->events < k->rec_cap) {
+        k->rec_layer[k->events] = ev_layer; k->rec_unit[k->events] = ev_unit;
+        memcpy(k->rec_jump + k->events * k->rec_P, k->jump, sizeof(real) * k->rec_P);
+    }
+    for (int l = 0; l <= top; ++l) {
+        const lay_t *q = &lay[l];
+        if (q->type == ORC_POOL) continue;
+        const int64_t nw = q->b_off - q->w_off, nb = q->oc;
+        double mw = 0, mb = 0;
+        for (int64_t j = 0; j < nw; ++j) {
+            const double a = fabs((double)k->jump[q->w_off + j]);
+            if (a > mw) mw = a;
+            k->jump[q->w_off + j] = 0;
+        }
+        for (int64_t j = 0; j < nb; ++j) {
+            const double a = fabs((double)k->jump[q->b_off + j]);
+            if (a > mb) mb = a;
+            k->jump[q->b_off + j] = 0;
+        }
+        k->allow[t] += mw; k->allow[t + 1] += mb;
+        t += 2;
+    }
+    k->events += 1;
+}
+
+/* All near-kink decisions of the sample that sample_loss_grad has just processed with the
+ * same w and scratch. */
+static void sample_kinks(const lay_t *lay, int L, const real *w, const scratch_t *s, kink_t *k) {
+    for (int l = 0; l < L; ++l) {
+        const lay_t *q = &lay[l];
+        if (q->type != ORC_POOL) {
+            const int wanted = q->relu || (l + 1 < L && lay[l + 1].type == ORC_POOL);
+            if (!wanted) continue;
+            for (int64_t o = 0; o < q->out_size; ++o) {
+                real z, sc;
+                preactivation(q, w, s->act[l], o, &z, &sc);
+                k->scale[l][o] = sc;
+                if (!q->relu || !((real)fabs((double)z) < (real)k->eps * sc)) continue;
+                const real d = s->del[l + 1][o];      /* what reaches the unit from above */
+                for (int64_t j = 0; j < q->out_size; ++j) k->kd[l + 1][j] = 0;
+                k->kd[l + 1][o] = d;
+                if (d != 0) carry_down(lay, l, 0, w, s, k);
+                book_jump(lay, l, l, o, k);
+            }
+        } else {
+            if (l == 0 || lay[l - 1].type == ORC_POOL) continue;   /* no scale to measure the gap against */
+            const real *in = s->act[l];
+            for (int c = 0; c < q->oc; ++c)
+                for (int oy = 0; oy < q->oh; ++oy)
+                    for (int ox = 0; ox < q->ow; ++ox) {
+                        const int64_t o = ((int64_t)c * q->oh + oy) * q->ow + ox;
+                        const int64_t best = s->amax[l][o];
+                        if (!(in[best] > 0)) continue;
+                        int64_t second = -1;
+                        for (int dy = 0; dy < 2; ++dy)
+                            for (int dx = 0; dx < 2; ++dx) {
+                                const int64_t j = ((int64_t)c * q->ih + 2 * oy + dy) * q->iw + 2 * ox + dx;
+                                if (j != best && (second < 0 || in[j] > in[second])) second = j;
+                            }
+                        real sc = k->scale[l - 1][best];
+                        if (k->scale[l - 1][second] > sc) sc = k->scale[l - 1][second];
+                        if (!(in[best] - in[second] < (real)k->eps * sc)) continue;
+                        const real d = s->del[l + 1][o];
+                        /* the runner-up takes the delta, the winner loses it; the layer below
+                         * applies its own ReLU decisions to both */
+                        for (int64_t j = 0; j < q->in_size; ++j) k->kd[l][j] = 0;
+                        k->kd[l][second] = d;
+                        k->kd[l][best] = -d;
+                        if (d != 0) carry_down(lay, l - 1, 1, w, s, k);
+                        book_jump(lay, l - 1, l, o, k);
+                    }
+        }
+    }
+}
+
+static int count_tensors(const lay_t *lay, int L) {
+    int t = 0;
+    for (int l = 0; l < L; ++l) if (lay[l].type != ORC_POOL) t += 2;
+    return t;
+}
+
+/* The near-kink decisions of ONE sample at weights w, for the tests: up to cap events with
+ * the layer they belong to, the output index of the unit / pool window, and the whole jump
+ * of the sample's gradient (cap x P); allow: per parameter tensor, the sum over all events
+ * of the largest |entry| of the jump.  Returns the number of events found (< 0: error). */
+int64_t orc_sample_kinks(const orc_model *m, const real *w, const float *x, int32_t label, double eps,
+                         int64_t cap, int32_t *ev_layer, int64_t *ev_unit, real *ev_jump, double *allow) {
+    lay_t lay[ORC_MAX_LAYERS]; int64_t P; scratch_t s; kink_t k;
+    if (resolve(m, lay, &P)) return -1;
+    const int L = m->n_layers, nt = count_tensors(lay, L);
+    real *g = (real *)calloc(P, sizeof(real));
+    if (!g || scratch_alloc(lay, L, &s)) { free(g); return -2; }
+    if (kink_alloc(lay, L, P, nt, eps, &k)) { free(g); scratch_free(L, &s); kink_free(L, &k); return -2; }
+    k.rec_cap = cap; k.rec_P = P; k.rec_layer = ev_layer; k.rec_unit = ev_unit; k.rec_jump = ev_jump;
+    sample_loss_grad(lay, L, w, x, label, g, &s);
+    sample_kinks(lay, L, w, &s, &k);
+    for (int t = 0; t < nt; ++t) allow[t] = k.allow[t];
+    const int64_t n = k.events;
+    free(g); scratch_free(L, &s); kink_free(L, &k);
+    return n;
+}
+
+/* ------------------------------------------------------------------------------------
  * Context
  * ---------------------------------------------------------------------------------- */
 void orc_destroy(orc_ctx *C) {
     if (!C) return;
     for (int i = 0; i < C->n_queue; ++i) free(C->queue[i].U);
     free(C->queue);
-    if (C->rinfo) for (int c = 0; c < C->n; ++c) free(C->rinfo[c]);
+    if (C->rinfo) for (int c = 0; c < C->n; ++c) {
+        for (int k = 0; k < C->n_rinfo[c]; ++k) free(C->rinfo[c][k].kink_allow);
+        free(C->rinfo[c]);
+    }
     free(C->rinfo); free(C->n_rinfo); free(C->cap_rinfo);
     free(C->ev_tick); free(C->ev_c); free(C->ev_k);
     free(C->X); free(C->y); free(C->N);
@@ -394,6 +648,7 @@ orc_ctx *orc_create(const orc_model *m, int32_t n_clients, const float *const *X
     if (!C) return NULL;
     C->model = *m; C->L = m->n_layers; C->n = n_clients; C->seed = seed;
     if (n_clients < 1 || resolve(m, C->lay, &C->P)) { free(C); return NULL; }
+    C->n_tensors = count_tensors(C->lay, C->L);
     C->X = (const float **)malloc(sizeof(float *) * n_clients);
     C->y = (const int32_t **)malloc(sizeof(int32_t *) * n_clients);
     C->N = (int64_t *)malloc(sizeof(int64_t) * n_clients);
@@ -547,7 +802,10 @@ int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0,
         real *U = (real *)calloc(C->P, sizeof(real));
         real *g = (real *)malloc(sizeof(real) * C->P);
         scratch_t sc;
+        kink_t kk;
+        const int kinks = C->kink_eps > 0;
         if (!U || !g || scratch_alloc(C->lay, C->L, &sc)) { oom = 1; free(U); free(g); continue; }
+        if (kinks && kink_alloc(C->lay, C->L, C->P, C->n_tensors, C->kink_eps, &kk)) { oom = 1; free(U); free(g); continue; }
         if (!C->p2p)
             for (int64_t p = 0; p < C->P; ++p) Wc[p] = C->Wg[p];      /* adopt the broadcast */
         real loss_sum = 0;
@@ -558,6 +816,7 @@ int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0,
                 int32_t idx = orc_sample_index(C->seed, c, C->q_c[c] + u * B + j, C->N[c]);
                 lstep += sample_loss_grad(C->lay, C->L, Wc, C->X[c] + (int64_t)idx * C->lay[0].in_size,
                                           C->y[c][idx], g, &sc);
+                if (kinks) sample_kinks(C->lay, C->L, Wc, &sc, &kk);
             }
             for (int64_t p = 0; p < C->P; ++p) g[p] /= (real)B;
             for (int64_t p = 0; p < C->P; ++p) { Wc[p] -= eta * g[p]; U[p] += g[p]; }
@@ -565,6 +824,14 @@ int orc_run_round(orc_ctx *C, int64_t a, int64_t b, int32_t rounds, double eta0,
         }
         scratch_free(C->L, &sc);
         free(g);
+        if (kinks) {
+            /* a sample's gradient enters the recursion divided by the mini-batch size */
+            ri[ai].kink_events = kk.events;
+            ri[ai].kink_allow = kk.allow;
+            for (int t = 0; t < C->n_tensors; ++t) ri[ai].kink_allow[t] /= (double)B;
+            kk.allow = NULL;
+            kink_free(C->L, &kk);
+        }
         const int64_t f = compute_factor ? compute_factor[c] : 1;
         const int64_t delta = (is_straggler && is_straggler[c])
                                   ? orc_net_delay(delay_seed, c, (int32_t)i, delay_min, delay_max) : 0;
@@ -718,6 +985,20 @@ int orc_get_round_info(orc_ctx *C, int32_t c, int32_t k, int64_t *ints6, double 
     ints6[0] = r->s; ints6[1] = r->m; ints6[2] = r->q0; ints6[3] = r->t0;
     ints6[4] = r->start_tick; ints6[5] = r->arrival;
     dbl2[0] = r->eta; dbl2[1] = r->loss;
+    return 0;
+}
+/* Kink analysis on (eps > 0) or off for the rounds that follow: see the section "Kinks". */
+void orc_set_kink_eps(orc_ctx *C, double eps) { C->kink_eps = eps; }
+int32_t orc_n_tensors(const orc_ctx *C) { return C->n_tensors; }
+/* of round k of client c, run with the analysis on: the number of near-kink decisions and,
+ * per parameter tensor (weights, bias of every conv / dense layer, in order), the sum of the
+ * jumps of the mini-batch gradient they could cause (entries of g, i.e. already / B) */
+int orc_get_round_kinks(orc_ctx *C, int32_t c, int32_t k, int64_t *events, double *allow) {
+    if (c < 0 || c >= C->n || k < 0 || k >= C->n_rinfo[c]) return fail(C, "no such round");
+    const rinfo_t *r = &C->rinfo[c][k];
+    if (!r->kink_allow) return fail(C, "round ran without the kink analysis");
+    *events = r->kink_events;
+    for (int t = 0; t < C->n_tensors; ++t) allow[t] = r->kink_allow[t];
     return 0;
 }
 int64_t orc_event_count(const orc_ctx *C) { return C->n_ev; }

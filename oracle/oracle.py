@@ -112,6 +112,14 @@ def load(prec: str = "f64"):
     lib.orc_history.argtypes = [vp, i32]
     lib.orc_real_bytes.restype = C.c_int
     lib.orc_real_bytes.argtypes = []
+    lib.orc_set_kink_eps.restype = None
+    lib.orc_set_kink_eps.argtypes = [vp, dbl]
+    lib.orc_n_tensors.restype = i32
+    lib.orc_n_tensors.argtypes = [vp]
+    lib.orc_get_round_kinks.restype = C.c_int
+    lib.orc_get_round_kinks.argtypes = [vp, i32, i32, vp, vp]
+    lib.orc_sample_kinks.restype = i64
+    lib.orc_sample_kinks.argtypes = [C.POINTER(_Model), vp, vp, i32, dbl, i64, vp, vp, vp, vp]
     _LIBS[prec] = lib
     return lib
 
@@ -143,6 +151,28 @@ def batch_loss_grad(model, w: np.ndarray, X: np.ndarray, y: np.ndarray, prec: st
     if loss < 0 and loss in (-1.0, -2.0):
         raise ValueError("oracle rejected the model")
     return loss, g
+
+
+def sample_kinks(model, w: np.ndarray, x: np.ndarray, label: int, eps: float, cap: int = 4096,
+                 prec: str = "f64"):
+    """Near-kink decisions of one sample at weights w (see "Kinks" in the C source):
+    (events, allow) with events = [(layer, unit, jump vector)], allow per parameter tensor."""
+    lib = load(prec)
+    dt = np.float64 if prec == "f64" else np.float32
+    w = np.ascontiguousarray(w, dtype=dt)
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    cm = _c_model(model)
+    nt = 2 * sum(1 for L in model.layers if L.type != 1)
+    lay = np.zeros(cap, dtype=np.int32)
+    unit = np.zeros(cap, dtype=np.int64)
+    jump = np.zeros((cap, w.size), dtype=dt)
+    allow = np.zeros(nt, dtype=np.float64)
+    n = int(lib.orc_sample_kinks(C.byref(cm), _ptr(w), _ptr(x), int(label), float(eps), cap,
+                                 _ptr(lay), _ptr(unit), _ptr(jump), _ptr(allow)))
+    if n < 0:
+        raise ValueError("oracle rejected the model")
+    m = min(n, cap)
+    return [(int(lay[j]), int(unit[j]), jump[j].copy()) for j in range(m)], allow, n
 
 
 class Oracle:
@@ -266,6 +296,17 @@ class Oracle:
         return dict(s=int(ints[0]), m=int(ints[1]), q0=int(ints[2]), t0=int(ints[3]),
                     start_tick=int(ints[4]), arrival=int(ints[5]), eta=float(dbl[0]),
                     loss=float(dbl[1]))
+
+    def set_kink_eps(self, eps: float):
+        """Kink analysis on (eps > 0) or off for the rounds that follow."""
+        self.lib.orc_set_kink_eps(self.ctx, float(eps))
+
+    def round_kinks(self, c: int, k: int):
+        """(number of near-kink decisions, allowance per parameter tensor) of round k of c."""
+        ev = C.c_int64(0)
+        allow = np.zeros(int(self.lib.orc_n_tensors(self.ctx)), dtype=np.float64)
+        self._check(self.lib.orc_get_round_kinks(self.ctx, c, k, C.byref(ev), _ptr(allow)))
+        return ev.value, allow
 
     def events(self):
         n = int(self.lib.orc_event_count(self.ctx))
