@@ -24,14 +24,9 @@ def _both(gpu, wl, **kw):
     return gpu(wl, **kw), Oracle(wl, "f64")
 
 
-def _twin(wl):
-    """The oracle's fp32 build: the yardstick for ReLU networks (see parity.py)."""
-    from oracle import Oracle
-    return Oracle(wl, "f32")
-
-
 def report(name, worst):
-    print(f"\n[parity] {name}: " + ", ".join(f"{k} {v:.2e}" for k, v in worst.items()), flush=True)
+    print(f"\n[parity] {name}: " + ", ".join(f"{k} {v:.2e}" if isinstance(v, float) else f"{k} {v}"
+                                             for k, v in worst.items()), flush=True)
 
 
 def test_sample_indices_bit_exact(gpu, oracle_libs):
@@ -141,11 +136,20 @@ def test_small_cases_every_tick(gpu, oracle_libs, name):
     run.close()
 
 
-def test_layer_engine_on_fused_shapes(gpu, oracle_libs, monkeypatch):
+@pytest.fixture
+def select_kernels():
+    """aet_test_select_kernels for one test; the defaults come back afterwards."""
+    from paper_2112_13935_amd import load_library
+    lib = load_library()
+    yield lib.aet_test_select_kernels
+    lib.aet_test_select_kernels(0, 0)
+
+
+def test_layer_engine_on_fused_shapes(gpu, oracle_libs, select_kernels):
     """The layer-by-layer engine on a shape the fused kernel would take: both code paths
     have to match the oracle."""
     from parity import lockstep
-    monkeypatch.setenv("AET_FORCE_LAYER_ENGINE", "1")
+    select_kernels(1, 0)
     wl = small_cases()["mlp_fused_b16_ragged_d"]
     run, orc = _both(gpu, wl)
     report("layer engine on mlp_fused_b16_ragged_d", lockstep(wl, run, orc))
@@ -153,10 +157,10 @@ def test_layer_engine_on_fused_shapes(gpu, oracle_libs, monkeypatch):
 
 
 @pytest.mark.parametrize("name", ["lenet16_factors_stragglers", "cnn8_factors", "mlp_ragged_stragglers"])
-def test_plain_layer_kernels(gpu, oracle_libs, monkeypatch, name):
+def test_plain_layer_kernels(gpu, oracle_libs, select_kernels, name):
     """The plain FMA layer kernels (the matrix-core ones switched off) against the oracle."""
     from parity import lockstep
-    monkeypatch.setenv("AET_PLAIN_LAYERS", "1")
+    select_kernels(0, 1)
     wl = small_cases()[name]
     run, orc = _both(gpu, wl)
     report("plain layer kernels on " + name, lockstep(wl, run, orc))
@@ -218,19 +222,34 @@ def test_config1_full(gpu, oracle_libs):
 
 
 def test_config2_full_clients_20_rounds(gpu, oracle_libs):
-    from parity import lockstep
+    from parity import TOL, lockstep
     wl = W.config2()
     run, orc = _both(gpu, wl)
-    report("config 2 (16 clients, 20 rounds)", lockstep(wl, run, orc, rounds=20, check_every_tick=False))
+    worst = lockstep(wl, run, orc, rounds=20, check_every=5)
+    report("config 2 (16 clients, 20 rounds; U and w_c every fifth tick)", worst)
+    assert worst["Wg"] <= TOL          # the global model meets the flat bar after 20 rounds
     run.close()
 
 
+@pytest.mark.timeout(600)
 def test_config3_full_clients_20_rounds(gpu, oracle_libs):
-    from parity import lockstep
+    from parity import TOL, lockstep
     wl = W.config3()
     run, orc = _both(gpu, wl)
-    report("config 3 (64 clients, 20 rounds)",
-           lockstep(wl, run, orc, rounds=20, check_every_tick=False, twin=_twin(wl)))
+    worst = lockstep(wl, run, orc, rounds=20, check_every=5)
+    report("config 3 (64 clients, 20 rounds; U and w_c every fifth tick)", worst)
+    assert worst["Wg"] <= TOL          # the global model meets the flat bar after 20 rounds
+    run.close()
+
+
+def test_config3_every_recursion_from_a_common_start(gpu, oracle_libs):
+    """LeNet at its full layer shapes, all 64 clients: rounds of one recursion each (a = 0,
+    b = B), every tick restarted from the oracle's global model, so each mini-batch gradient,
+    update and aggregation is compared on its own."""
+    from parity import lockstep
+    wl = W.config3(rounds=6, a=0, b=16)
+    run, orc = _both(gpu, wl)
+    report("config 3, single recursions from a common start", lockstep(wl, run, orc, resync=True))
     run.close()
 
 
@@ -241,107 +260,68 @@ def test_config4_full_layer_shapes(gpu, oracle_libs):
     wl = W.config4(n_clients=3, n_per=200, rounds=2)
     wl.compute_factor = np.array([1, 2, 1], dtype=np.int32)
     run, orc = _both(gpu, wl)
-    report("config 4 shapes (3 clients, 2 rounds)", lockstep(wl, run, orc, twin=_twin(wl)))
+    report("config 4 shapes (3 clients, 2 rounds)", lockstep(wl, run, orc))
     run.close()
 
 
-@pytest.mark.timeout(400)
-def test_config4_full_size_first_tick(gpu, oracle_libs):
+def test_config4_every_recursion_from_a_common_start(gpu, oracle_libs):
+    """The CNN at its full layer shapes and B = 64: rounds of one recursion each, restarted
+    from the oracle's global model after every tick."""
+    from parity import lockstep
+    wl = W.config4(n_clients=4, n_per=300, rounds=3, a=0, b=64)
+    wl.compute_factor = None
+    run, orc = _both(gpu, wl)
+    report("config 4, single recursions from a common start", lockstep(wl, run, orc, resync=True))
+    run.close()
+
+
+@pytest.mark.timeout(900)
+def test_config4_full_size_first_two_ticks(gpu, oracle_libs):
     """The CNN workload at full size in the launch configuration the benchmark times: all 32
-    clients in every launch, B = 64.  After the first tick (round 0 of every client: two
-    recursions from the common start) clients 0 and 1 are compared with an oracle run of
-    those two clients (rounds are independent of each other until the server aggregates),
-    client 31's round is recomputed from the oracle's index map and its mini-batch gradient
-    (Algorithm 2, inner loop: w <- w - eta g, U <- U + g), and for every client the round
-    bookkeeping is exact and w_start - w_end = eta U holds in the GPU's own numbers."""
-    from oracle import Oracle
-    from oracle.oracle import batch_loss_grad
-    from parity import TOL, TWIN_FACTOR, CEILING, tensor_relerrs, weight_unit_errs
+    clients, B = 64.  Tick 0: round 0 of every client against the oracle (U, w_c, loss,
+    bookkeeping), then the first aggregation at P = 1.12 M.  Tick 1: round 1 of the clients
+    whose compute factor is 1, from the aggregated model, and the second aggregation."""
+    from parity import lockstep
     wl = W.config4()
-    model, B = wl.model, wl.model.batch
-    run = gpu(wl)
-    orc, twin = Oracle(wl, "f64", n_clients=2), Oracle(wl, "f32", n_clients=2)
-    fin_g = run.run_round()
-    assert fin_g == [(c, 0) for c in range(wl.n_clients)]
-    assert orc.run_round() == twin.run_round() == [(0, 0), (1, 0)]
-    w0 = wl.w0.astype(np.float64)
-    m0 = wl.b // B
-    eta = float(np.float32(wl.eta0))          # t = 0: eta_0 itself
-    worst = {}
-
-    twin_worst = {}
-
-    def check(quantity, c, errs, twin_errs):
-        tw = twin_worst.setdefault(quantity, [0.0] * len(twin_errs))
-        for j, (e, t) in enumerate(zip(errs, twin_errs)):
-            tw[j] = max(tw[j], t)
-            bar = min(CEILING, max(TOL, TWIN_FACTOR * t))
-            assert e <= bar, f"{quantity}, client {c}, tensor {j}: {e:.3e} > {bar:.1e} (fp32 twin {t:.3e})"
-            worst[quantity] = max(worst.get(quantity, 0.0), e)
-
-    for c in range(wl.n_clients):
-        ig = run.lib.aet_get_round_info(c, 0)
-        assert (ig["s"], ig["m"], ig["q0"], ig["t0"], ig["start_tick"]) == (wl.b, m0, 0, 0, 0)
-        assert ig["arrival"] == int(wl.compute_factor[c]) - 1 and ig["eta"] == eta
-        U = run.lib.aet_get_U(c, 0).astype(np.float64)
-        w_end = run.lib.aet_get_weights(c).astype(np.float64)
-        err = np.abs((w0 - w_end) / eta - U).max()
-        assert err <= 1e-4 * max(1.0, np.abs(U).max()), (c, err)
-    for c in (0, 1):
-        io, ig = orc.round_info(c, 0), run.lib.aet_get_round_info(c, 0)
-        for key in ("s", "m", "q0", "t0", "start_tick", "arrival"):
-            assert ig[key] == io[key], (c, key)
-        wo, Uo = orc.get_weights(c), orc.get_U(c, 0)
-        check("w_c", c, tensor_relerrs(model, run.lib.aet_get_weights(c), wo),
-              tensor_relerrs(model, twin.get_weights(c), wo))
-        check("U_weight_units", c, weight_unit_errs(model, io["eta"], run.lib.aet_get_U(c, 0), Uo, wo),
-              weight_unit_errs(model, io["eta"], twin.get_U(c, 0), Uo, wo))
-        worst["loss"] = max(worst.get("loss", 0.0), abs(ig["loss"] - io["loss"]) / abs(io["loss"]))
-    c = wl.n_clients - 1          # yardstick: the twin's worst errors on clients 0 and 1
-    wo, Uo = w0.copy(), np.zeros(w0.size)
-    for u in range(m0):
-        idx = [orc.sample_index(c, u * B + j, wl.X[c].shape[0]) for j in range(B)]
-        _, g = batch_loss_grad(model, wo, wl.X[c][idx], wl.y[c][idx])
-        wo, Uo = wo - eta * g, Uo + g
-    check("w_c", c, tensor_relerrs(model, run.lib.aet_get_weights(c), wo), twin_worst["w_c"])
-    check("U_weight_units", c, weight_unit_errs(model, eta, run.lib.aet_get_U(c, 0), Uo, wo),
-          twin_worst["U_weight_units"])
-    report("config 4 at full size, first tick (clients 0, 1, 31 of 32)", worst)
-    assert worst["loss"] <= TOL
+    run, orc = _both(gpu, wl)
+    worst = lockstep(wl, run, orc, stop_after_ticks=2)
+    report("config 4 at full size, ticks 0 and 1 (all 32 clients)", worst)
+    assert orc.tick == 2 and sum(orc.history(c) for c in range(wl.n_clients)) > 0
     run.close()
 
 
+@pytest.mark.timeout(900)
 def test_config4_reduced_20_rounds(gpu, oracle_libs):
-    """Same architecture at 16x16 images and half width, 8 clients with compute factors,
+    """Same architecture at 16x16 images and half width, 6 clients with compute factors,
     20 rounds; all sides restart from the oracle's global model after every tick (a
     free-running CNN run of this length drifts by its own rounding: see parity.py)."""
     from parity import lockstep
-    wl = W.config4(n_clients=8, n_per=300, hw=16, width=16, fc=64, batch=16, rounds=20, a=16, b=32)
+    wl = W.config4(n_clients=6, n_per=300, hw=16, width=16, fc=64, batch=16, rounds=20, a=16, b=32)
     run, orc = _both(gpu, wl)
-    report("config 4 reduced (8 clients, 20 rounds, common start per tick)",
-           lockstep(wl, run, orc, check_every_tick=True, twin=_twin(wl), resync=True))
+    report("config 4 reduced (6 clients, 20 rounds, common start per tick)",
+           lockstep(wl, run, orc, resync=True))
     run.close()
 
 
 def test_config4_reduced_free_running_8_rounds(gpu, oracle_libs):
-    """The same workload left to itself for 8 rounds, while the fp32 twin still stays within
-    about 1e-3 of the fp64 oracle."""
+    """The same workload left to itself for 8 rounds."""
     from parity import lockstep
-    wl = W.config4(n_clients=8, n_per=300, hw=16, width=16, fc=64, batch=16, rounds=8, a=16, b=32)
+    wl = W.config4(n_clients=6, n_per=300, hw=16, width=16, fc=64, batch=16, rounds=8, a=16, b=32)
     run, orc = _both(gpu, wl)
-    report("config 4 reduced (8 clients, 8 rounds, free running)",
-           lockstep(wl, run, orc, check_every_tick=False, twin=_twin(wl)))
+    report("config 4 reduced (6 clients, 8 rounds, free running)", lockstep(wl, run, orc, check_every=2))
     run.close()
 
 
-def test_config5_full_clients_8_rounds(gpu, oracle_libs):
-    """All 1,024 clients and 3,072 features; 8 rounds (stragglers with delays up to 5
-    ticks are in flight throughout)."""
+@pytest.mark.timeout(900)
+def test_config5_full_clients_20_rounds(gpu, oracle_libs):
+    """All 1,024 clients and 3,072 features, the 20 rounds the tolerance is defined on
+    (stragglers with delays up to 5 ticks are in flight throughout): losses of every round,
+    U and w_c of every client every fifth tick, every client's model and the global model at
+    the end."""
     from parity import lockstep
-    wl = W.config5(rounds=8)
+    wl = W.config5(rounds=20)
     run, orc = _both(gpu, wl)
-    report("config 5 (1024 clients, 8 rounds)",
-           lockstep(wl, run, orc, check_every_tick=False, check_clients=set(range(0, 1024, 37))))
+    report("config 5 (1024 clients, 20 rounds)", lockstep(wl, run, orc, check_every=5))
     run.close()
 
 
