@@ -132,8 +132,8 @@ size_t aet_workspace_bytes(const aet_model_desc *model, int32_t n_clients, int32
  *   hip_stream    a hipStream_t passed as void* (NULL = the default stream)
  * Sample q (counting from 0 over the client's whole life) of client c is row
  *   ((h >> 32) * n_samples) >> 32,  h = SplitMix64 stream value number q of the stream
- * keyed by (seed, client): uniform with replacement ("Sample uniformly at random xi from
- * D_c", Algorithm 2), a pure function of (seed, c, q). */
+ * keyed by (seed, client): uniform with replacement (the sampling step of Algorithm 2,
+ * MainComputeNode), a pure function of (seed, c, q). */
 aet_status aet_init(aet_ctx **out, const aet_model_desc *model, int32_t n_clients,
                     const aet_shard *shards, const float *w0, uint64_t seed, void *workspace,
                     size_t workspace_bytes, int32_t max_inflight, int32_t max_rounds,
@@ -281,6 +281,31 @@ aet_status aet_synchronize(aet_ctx *ctx);
  * model); round counters, recursion and sample counters, the history H, the message
  * queue and the tick counter are cleared.  Enqueued, no sync. */
 aet_status aet_reset(aet_ctx *ctx);
+
+/* Which engine runs the local rounds, and what it needs from the device.
+ *   - softmax regression (one dense layer, batch 1, 10 classes, up to 3072 inputs): one
+ *     workgroup per client runs the whole round with the replica in registers;
+ *   - dense-ReLU-dense models (batch 16 or 32, hidden width a multiple of 16 up to 256, up
+ *     to 896 inputs): a CLUSTER of workgroups per client runs the whole round and
+ *     exchanges partial sums through tagged records in the workspace.  PRECONDITION: all
+ *     workgroups of a cluster must be resident on the GPU together.  The launcher sizes its
+ *     launches from the occupancy the device reports for an otherwise idle GPU; if other
+ *     work occupies compute units at the same time (another stream, process or a
+ *     compute-unit mask) a cluster may not become resident.  The wait of a workgroup for
+ *     its peers is bounded: when it expires the kernel raises an error flag and still runs
+ *     to its end (nothing hangs), the results of that launch are invalid, and the next call
+ *     that synchronises (aet_synchronize, any getter with on_host != 0, aet_get_round_info)
+ *     returns AET_EHIP; from then on every call on the context returns AET_ESTATE.  There
+ *     is no fall-back to another engine inside a context: create a new one (after
+ *     aet_test_select_kernels(1, 0) it runs on the layer-by-layer engine);
+ *   - every other model: one short kernel sequence per recursion (layer-by-layer engine).
+ *
+ * Test hook: contexts created after this call use the layer-by-layer engine for every
+ * model (force_layer_engine != 0) and / or its plain-FMA kernels instead of the matrix-core
+ * ones (plain_layers != 0), so that the kernel sets can be checked against each other and
+ * against the oracle.  Process-wide; (0, 0) restores the defaults.  It also changes what
+ * aet_workspace_bytes returns. */
+void aet_test_select_kernels(int32_t force_layer_engine, int32_t plain_layers);
 
 /* Optional kernel timing for measurement harnesses.  The library's kernels are grouped
  * in families (aet_profile_family_name gives each family's kernel name); while a family

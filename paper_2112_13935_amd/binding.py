@@ -24,7 +24,7 @@ EXPORTS = [
     "aet_last_error", "aet_destroy", "aet_reset", "aet_profile_families",
     "aet_profile_family_name", "aet_profile_enable", "aet_profile_read", "aet_run_ticks",
     "aet_topology_workspace_bytes", "aet_set_topology", "aet_receive", "aet_set_setup",
-    "aet_set_weights", "aet_init_static",
+    "aet_set_weights", "aet_init_static", "aet_test_select_kernels",
 ]
 
 
@@ -133,6 +133,8 @@ def load_library():
     lib.aet_profile_enable.argtypes = [vp, i32, i32]
     lib.aet_profile_read.restype = C.c_int
     lib.aet_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double), i32]
+    lib.aet_test_select_kernels.restype = None
+    lib.aet_test_select_kernels.argtypes = [i32, i32]
     lib.aet_destroy.restype = None
     lib.aet_destroy.argtypes = [vp]
     _LIB = lib

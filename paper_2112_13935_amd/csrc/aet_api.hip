@@ -134,9 +134,11 @@ bool resolve(const aet_model_desc *m, LayerGeom *lay, int64_t *P, std::string *w
 // which engine runs the local rounds of this model
 enum Engine { ENGINE_LAYERS = 0, ENGINE_MLP = 1, ENGINE_SOFTMAX = 2 };
 
+// aet_test_select_kernels: which kernel set contexts created from now on use
+int g_force_layer_engine = 0, g_plain_layers = 0;
+
 Engine pick_engine(const LayerGeom *lay, int L, int B) {
-    const char *force = std::getenv("AET_FORCE_LAYER_ENGINE");
-    if (force && force[0] == '1') return ENGINE_LAYERS;
+    if (g_force_layer_engine) return ENGINE_LAYERS;
     if (L == 2 && lay[0].type == AET_DENSE && lay[1].type == AET_DENSE && lay[0].relu &&
         mlp_round_supported((int)lay[0].in_size, lay[0].oc, lay[1].oc, B))
         return ENGINE_MLP;
@@ -285,6 +287,11 @@ const std::vector<int64_t> &setup_shares(aet_ctx *ctx, int64_t i, int64_t a, int
 
 extern "C" {
 
+void aet_test_select_kernels(int32_t force_layer_engine, int32_t plain_layers) {
+    g_force_layer_engine = force_layer_engine != 0;
+    g_plain_layers = plain_layers != 0;
+}
+
 int64_t aet_n_params(const aet_model_desc *model) {
     LayerGeom lay[AET_MAX_LAYERS];
     int64_t P;
@@ -375,11 +382,7 @@ static aet_status init_context(aet_ctx **out, const aet_model_desc *model, int32
         ctx->sc.amax[l] = ctx->lay[l].type == AET_POOL ? reinterpret_cast<uint8_t *>(ctx->ws + ctx->lo.amax[l]) : nullptr;
     ctx->sc.labels = reinterpret_cast<int32_t *>(ctx->ws + ctx->lo.labels);
     ctx->sc.wgrad = reinterpret_cast<float *>(ctx->ws + ctx->lo.wgrad);
-    {
-        // AET_PLAIN_LAYERS=1: plain FMA kernels, to cross-check the matrix-core layer kernels
-        const char *e = std::getenv("AET_PLAIN_LAYERS");
-        ctx->sc.plain = e && e[0] == '1';
-    }
+    ctx->sc.plain = g_plain_layers != 0;
     ctx->engine = pick_engine(ctx->lay, ctx->L, ctx->B);
 
     hipError_t e = hipSuccess;
@@ -773,6 +776,7 @@ static aet_status copy_out(aet_ctx *ctx, const float *src, float *dst, int32_t o
 
 aet_status aet_get_U(aet_ctx *ctx, int32_t client, int32_t round, float *dst, int32_t on_host) {
     if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
     if (!dst) return fail(ctx, AET_EINVAL, "dst is NULL");
     for (const Msg &m : ctx->queue)
         if (m.c == client && m.k == round) return copy_out(ctx, ctx->Uslot(m.slot), dst, on_host);
@@ -781,6 +785,7 @@ aet_status aet_get_U(aet_ctx *ctx, int32_t client, int32_t round, float *dst, in
 
 aet_status aet_get_weights(aet_ctx *ctx, int32_t client, float *dst, int32_t on_host) {
     if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
     if (!dst) return fail(ctx, AET_EINVAL, "dst is NULL");
     if (client >= ctx->n) return fail(ctx, AET_EINVAL, "client out of range");
     return copy_out(ctx, client < 0 ? ctx->Wg() : ctx->Wc(client), dst, on_host);
@@ -802,12 +807,15 @@ aet_status aet_get_round_info(aet_ctx *ctx, int32_t client, int32_t round, int64
     if (!ctx) return AET_EINVAL;
     if (client < 0 || client >= ctx->n || round < 0 || round >= (int)ctx->recs[client].size())
         return fail(ctx, AET_ESTATE, "client %d has not run round %d", client, round);
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
     const RoundRec &r = ctx->recs[client][round];
     if (ints) { ints[0] = r.s; ints[1] = r.m; ints[2] = r.q0; ints[3] = r.t0; ints[4] = r.start; ints[5] = r.arrival; }
     if (dbls) {
         float loss = 0.f;
         AET_HIP(ctx, hipMemcpyAsync(&loss, ctx->loss_at(client, round), 4, hipMemcpyDeviceToHost, ctx->stream));
         AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        const aet_status st = check_device_flag(ctx);
+        if (st != AET_OK) return st;
         dbls[0] = (double)r.eta;
         dbls[1] = r.m > 0 ? (double)loss / (double)r.m : 0.0;
     }
@@ -817,6 +825,7 @@ aet_status aet_get_round_info(aet_ctx *ctx, int32_t client, int32_t round, int64
 aet_status aet_debug_sample_indices(aet_ctx *ctx, int32_t client, int64_t q0, int32_t count,
                                     int32_t *dst) {
     if (!ctx) return AET_EINVAL;
+    if (ctx->dead) return fail(ctx, AET_ESTATE, "context is unusable after a HIP error");
     if (client < 0 || client >= ctx->n || q0 < 0 || count < 0 || count > kDebugIdx || !dst)
         return fail(ctx, AET_EINVAL, "bad argument");
     if (count == 0) return AET_OK;

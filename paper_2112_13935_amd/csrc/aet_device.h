@@ -16,8 +16,7 @@ __host__ __device__ __forceinline__ uint64_t splitmix_mix(uint64_t z) {
 __host__ __device__ __forceinline__ uint64_t splitmix_at(uint64_t key, uint64_t ctr) {
     return splitmix_mix(key + (ctr + 1) * 0x9E3779B97F4A7C15ULL);
 }
-// "Sample uniformly at random xi from D_c" (Algorithm 2): the row that sample counter q
-// selects, by multiply-shift of the hash's top 32 bits onto [0, n_samples).
+// Algorithm 2, sampling step: the row that sample counter q selects, by multiply-shift of the hash's top 32 bits onto [0, n_samples).
 __host__ __device__ __forceinline__ uint32_t sample_row(uint64_t key, uint64_t q, uint32_t n_samples) {
     const uint64_t h = splitmix_at(key, q);
     return (uint32_t)(((h >> 32) * (uint64_t)n_samples) >> 32);

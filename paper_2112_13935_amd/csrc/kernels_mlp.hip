@@ -290,7 +290,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                     red[(wave * B + 16 * bt + 4 * lg + r) * 16 + li] = acc[bt][r];
         }
         __syncthreads();
-        // the rows the next recursion samples (Algorithm 2: "sample xi from D_c"; a counter
+        // the rows the next recursion samples (Algorithm 2, sampling step; a counter
         // hash, so they are known ahead); with two workgroups per unit group the hash is
         // computed while the pair exchange is in flight
         uint32_t rowv = 0;
@@ -360,7 +360,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             }
         }
         // ---- prefetch the rows of the NEXT recursion into registers ----------------------
-        // (Algorithm 2: "sample xi from D_c"; the indices are a counter hash, so they are
+        // (Algorithm 2, sampling step; the indices are a counter hash, so they are
         // known ahead of time).  Loads of one wave return in order, so nothing is issued
         // before the exchange poll.
         int labn = 0;

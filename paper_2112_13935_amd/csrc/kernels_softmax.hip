@@ -144,7 +144,7 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
 
     // one recursion on sample x; meanwhile the next sample is fetched into xn
     auto recursion = [&](int u, const float (&x)[NC], int lab, float (&xn)[NC], int &labn) {
-        // prefetch (Algorithm 2: "sample xi from D_c"; the index is a counter hash)
+        // prefetch (Algorithm 2, sampling step; the index is a counter hash)
         if (u + 1 < p.m) load_row(sample_row(p.key, (uint64_t)(p.q0 + u + 1), p.n_samples), xn, labn);
         // partial logits of this thread's columns, summed over the wave
         float(*zp)[16] = zpart[u & 1];
