@@ -9,8 +9,9 @@
 //   z_o = b_o + sum_k W[o][k] x[k]   per-thread partial sums, DPP reduction inside a wave,
 //                                    one LDS hop across the 8 waves (fixed order)
 //   p = softmax(z), dz = p - onehot  lane o of every 16-lane row handles class o (DPP row
-//                                    reductions); dz is then read lane by lane
-//   W[o][k] -= eta dz_o x[k];  U[o][k] += dz_o x[k]      in registers (g never stored)
+//                                    reductions); dz is then handed to the matrix cores
+//   W[o][k] -= eta dz_o x[k];  U[o][k] += dz_o x[k]      in registers, as 4 x 4 outer products
+//                                    on the matrix cores (g never stored)
 //
 // At the end of the round w_c and U are written to HBM once.
 #include "aet_device.h"
@@ -33,25 +34,6 @@ __device__ __forceinline__ float wave_sum_dpp(float v) {
     v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x143, 0xC, 0xF, false));
     return v;
 }
-
-#define AET_DPP_ADD(v, ctrl, rmask, bc) \
-    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), ctrl, rmask, 0xF, bc))
-template <int N>
-__device__ __forceinline__ void wave_sum_dpp_many(float (&v)[N]) {
-#pragma unroll
-    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0xB1, 0xF, true);
-#pragma unroll
-    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x4E, 0xF, true);
-#pragma unroll
-    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x141, 0xF, true);
-#pragma unroll
-    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x140, 0xF, true);
-#pragma unroll
-    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x142, 0xA, false);
-#pragma unroll
-    for (int o = 0; o < N; ++o) AET_DPP_ADD(v[o], 0x143, 0xC, false);
-}
-#undef AET_DPP_ADD
 
 // Sums of N values over the 64 lanes of a wave, several values per instruction.  The lane
 // swaps of gfx950 exchange half-waves (rows of 16 lanes) between two registers, so that one
@@ -105,10 +87,24 @@ __device__ __forceinline__ float row_max_dpp(float v) {
     return v;
 }
 
-// C classes (<= 16), NC columns per thread; EXACT: D == 512 * NC, no column guards
-template <int C, int NC, bool EXACT>
+// ---- the round kernel: rank-1 updates on the matrix cores ----------------------------------
+// Two thirds of a recursion's multiply-adds are the rank-1 updates  W -= eta dz x^T  and
+// U += dz x^T.  v_mfma_f32_4x4x1_16b_f32 computes 16 independent 4 x 4 outer products
+// D[b] += A[b] B[b]^T: lane l supplies A[b = l/4][i = l%4] and B[b][n = l%4] and receives, in
+// its four result registers, the products of the four A entries of its block with ITS OWN B
+// entry.  With B = the lane's own column of the sampled row and A = four entries of
+// (-eta) dz (the same four in every block), one instruction updates four class rows of the
+// lane's own column: the replica keeps the ownership it has in the vector-ALU form (thread t
+// owns columns t, t+512, ... of every class row), so the logits still need no other lane's
+// data, and three instructions per 64 columns cover classes 0..11 (rows 10 and 11 stay
+// zero).  The vector ALU is left with the dot products, the reductions and the softmax.
+// NC columns per thread; EXACT: D == 512 * NC, no column guards.
+typedef float f4v __attribute__((ext_vector_type(4)));
+
+template <int NC, bool EXACT>
 __global__ void __launch_bounds__(kSmThreads, 1)
 k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
+    constexpr int C = 10, Q = 3;   // classes, groups of four class rows
     const RoundParams p = rp[blockIdx.x];
     const gcf_ptr Xg = as_global(p.X);
     const gci_ptr yg = as_global(p.y);
@@ -117,18 +113,19 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
 
     __shared__ float zpart[2][kSmWaves][16];
 
-    // adopt the global model (server form) or go on from the own replica (Wg == NULL:
-    // peer-to-peer form); U = 0.  Lane `cls` of every row keeps bias and its U entry.
     if (!Wg) Wg = p.W;
-    float W[C][NC], U[C][NC];
+    f4v W[NC][Q], U[NC][Q];
 #pragma unroll
-    for (int o = 0; o < C; ++o) {
+    for (int j = 0; j < NC; ++j) {
+        const int k = tid + kSmThreads * j;
 #pragma unroll
-        for (int j = 0; j < NC; ++j) {
-            const int k = tid + kSmThreads * j;
-            W[o][j] = (EXACT || k < D) ? Wg[(int64_t)o * D + k] : 0.f;
-            U[o][j] = 0.f;
-        }
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int o = 4 * q + r;
+                W[j][q][r] = (o < C && (EXACT || k < D)) ? Wg[(int64_t)o * D + k] : 0.f;
+                U[j][q][r] = 0.f;
+            }
     }
     float bias = cls < C ? Wg[(int64_t)C * D + cls] : 0.f, Ub = 0.f;
     float loss_acc = 0.f;
@@ -142,21 +139,17 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
         lab = yg[row];
     };
 
-    // one recursion on sample x; meanwhile the next sample is fetched into xn
     auto recursion = [&](int u, const float (&x)[NC], int lab, float (&xn)[NC], int &labn) {
         // prefetch (Algorithm 2, sampling step; the index is a counter hash)
         if (u + 1 < p.m) load_row(sample_row(p.key, (uint64_t)(p.q0 + u + 1), p.n_samples), xn, labn);
-        // partial logits of this thread's columns, summed over the wave
         float(*zp)[16] = zpart[u & 1];
         float s[C];
 #pragma unroll
         for (int o = 0; o < C; ++o) {
             s[o] = 0.f;
 #pragma unroll
-            for (int j = 0; j < NC; ++j) s[o] += W[o][j] * x[j];
+            for (int j = 0; j < NC; ++j) s[o] += W[j][o >> 2][o & 3] * x[j];
         }
-        // the C sums over the wave, four classes per register at the end; the first lane of
-        // every row posts its classes
         float t[(C + 3) / 4];
         wave_sum_rows<C>(s, t);
         if (cls == 0) {
@@ -166,7 +159,6 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
                 if (4 * k + o0 < C) zp[wave][4 * k + o0] = t[k];
         }
         __syncthreads();
-        // lane cls of every row: logit of class cls, then the softmax inside the row
         float z = bias;
 #pragma unroll
         for (int w = 0; w < kSmWaves; ++w) z += zp[w][cls];
@@ -178,20 +170,20 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
         if (cls == lab) loss_acc += lse - z;
         bias -= p.eta * dzl;
         Ub += dzl;
-        // w <- w - eta g, U <- U + g, with g = dz x^T; dz is read from the lanes that hold it
+        // w <- w - eta g, U <- U + g with g = dz x^T: lane l hands the matrix core entry
+        // 4q + l%4 of dz (lanes 10..15 of a row hold zeros) and its own x
 #pragma unroll
-        for (int o = 0; o < C; ++o) {
-            const float dz = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, dzl), o));
-            const float ed = p.eta * dz;
+        for (int q = 0; q < Q; ++q) {
+            const float a = __shfl(dzl, 4 * q + (lane & 3), 64);
+            const float na = -p.eta * a;
 #pragma unroll
             for (int j = 0; j < NC; ++j) {
-                W[o][j] -= ed * x[j];
-                U[o][j] += dz * x[j];
+                W[j][q] = __builtin_amdgcn_mfma_f32_4x4x1f32(na, x[j], W[j][q], 0, 0, 0);
+                U[j][q] = __builtin_amdgcn_mfma_f32_4x4x1f32(a, x[j], U[j][q], 0, 0, 0);
             }
         }
     };
 
-    // two register sets alternate as "current" and "next" sample
     float xa[NC], xb[NC];
     int la = 0, lb = 0;
     if (p.m > 0) load_row(sample_row(p.key, (uint64_t)p.q0, p.n_samples), xa, la);
@@ -202,15 +194,14 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
     }
     if (u < p.m) recursion(u, xa, la, xb, lb);
 
-    // the replica and the message payload go to HBM
 #pragma unroll
-    for (int o = 0; o < C; ++o) {
+    for (int j = 0; j < NC; ++j) {
+        const int k = tid + kSmThreads * j;
+        if (EXACT || k < D) {
 #pragma unroll
-        for (int j = 0; j < NC; ++j) {
-            const int k = tid + kSmThreads * j;
-            if (EXACT || k < D) {
-                Wc[(int64_t)o * D + k] = W[o][j];
-                Uc[(int64_t)o * D + k] = U[o][j];
+            for (int o = 0; o < C; ++o) {
+                Wc[(int64_t)o * D + k] = W[j][o >> 2][o & 3];
+                Uc[(int64_t)o * D + k] = U[j][o >> 2][o & 3];
             }
         }
     }
@@ -218,7 +209,6 @@ k_softmax_round(const RoundParams *__restrict__ rp, const float *Wg, int D) {
         Wc[(int64_t)C * D + tid] = bias;
         Uc[(int64_t)C * D + tid] = Ub;
     }
-    // every thread with cls == label added the sample's loss: take wave 0, row 0
     if (wave == 0) {
         float l = lane < 16 ? loss_acc : 0.f;
         l = wave_sum_dpp(l);
@@ -237,13 +227,13 @@ hipError_t launch_softmax_round(hipStream_t s, Profiler *prof, const RoundParams
     const bool timed = prof && prof->on[F_SOFTMAX_ROUND];
     if (timed) prof->before(F_SOFTMAX_ROUND, s);
     if (D <= kSmThreads)
-        k_softmax_round<10, 1, false><<<nact, kSmThreads, 0, s>>>(dp, Wg, D);
+        k_softmax_round<1, false><<<nact, kSmThreads, 0, s>>>(dp, Wg, D);
     else if (D <= 2 * kSmThreads)
-        k_softmax_round<10, 2, false><<<nact, kSmThreads, 0, s>>>(dp, Wg, D);
+        k_softmax_round<2, false><<<nact, kSmThreads, 0, s>>>(dp, Wg, D);
     else if (D == 6 * kSmThreads)
-        k_softmax_round<10, 6, true><<<nact, kSmThreads, 0, s>>>(dp, Wg, D);
+        k_softmax_round<6, true><<<nact, kSmThreads, 0, s>>>(dp, Wg, D);
     else
-        k_softmax_round<10, 6, false><<<nact, kSmThreads, 0, s>>>(dp, Wg, D);
+        k_softmax_round<6, false><<<nact, kSmThreads, 0, s>>>(dp, Wg, D);
     if (timed) prof->after(F_SOFTMAX_ROUND, s);
     return hipGetLastError();
 }
