@@ -132,7 +132,7 @@ bool resolve(const aet_model_desc *m, LayerGeom *lay, int64_t *P, std::string *w
 }
 
 // which engine runs the local rounds of this model
-enum Engine { ENGINE_LAYERS = 0, ENGINE_MLP = 1, ENGINE_SOFTMAX = 2 };
+enum Engine { ENGINE_LAYERS = 0, ENGINE_MLP = 1, ENGINE_SOFTMAX = 2, ENGINE_LENET = 3 };
 
 // aet_test_select_kernels: which kernel set contexts created from now on use
 int g_force_layer_engine = 0, g_plain_layers = 0;
@@ -144,6 +144,7 @@ Engine pick_engine(const LayerGeom *lay, int L, int B) {
         return ENGINE_MLP;
     if (L == 1 && lay[0].type == AET_DENSE && softmax_round_supported((int)lay[0].in_size, lay[0].oc, B))
         return ENGINE_SOFTMAX;
+    if (lenet_round_supported(lay, L, B)) return ENGINE_LENET;
     return ENGINE_LAYERS;
 }
 
@@ -163,7 +164,8 @@ bool make_layout(const LayerGeom *lay, int L, int64_t P, int B, int n, int infli
     lo->debug = take((size_t)kDebugIdx * 4);
     lo->labels = take((size_t)n * B * 4);
     // exchange records of the fused dense-ReLU-dense engine, only for models it runs
-    lo->fused = take(pick_engine(lay, L, B) == ENGINE_MLP ? mlp_round_scratch_bytes(n, B) : 0);
+    const Engine eng = pick_engine(lay, L, B);
+    lo->fused = take(eng == ENGINE_MLP ? mlp_round_scratch_bytes(n, B) : eng == ENGINE_LENET ? lenet_round_scratch_bytes(n) : 0);
     size_t wg_floats = 0;
     for (int l = 0; l < L; ++l)
         if (lay[l].type == AET_CONV && conv_wgrad_mfma_supported(lay[l], B))
@@ -402,6 +404,8 @@ static aet_status init_context(aet_ctx **out, const aet_model_desc *model, int32
     }
     if (e == hipSuccess && ctx->engine == ENGINE_MLP)
         e = mlp_clear_error_flag(ctx->stream, ctx->ws + ctx->lo.fused, n_clients, ctx->B);
+    if (e == hipSuccess && ctx->engine == ENGINE_LENET)
+        e = lenet_clear_error_flag(ctx->stream, ctx->ws + ctx->lo.fused, n_clients);
     // global model and every replica start as w0
     if (e == hipSuccess) e = hipMemcpyAsync(ctx->W0(), w0, (size_t)ctx->P * 4, static_ws ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, ctx->stream);
     if (e == hipSuccess) e = hipStreamSynchronize(ctx->stream);  // w0 is the caller's; do not keep reading it
@@ -536,6 +540,9 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
                                           ctx->lay[0].oc, ctx->lay[1].oc, ctx->B, ctx->ws + ctx->lo.fused, ctx->n, &ctx->epoch));
         } else if (ctx->engine == ENGINE_SOFTMAX) {
             AET_HIP(ctx, launch_softmax_round(ctx->stream, ctx->profp(), dp, nact, start, (int)ctx->lay[0].in_size, ctx->lay[0].oc));
+        } else if (ctx->engine == ENGINE_LENET) {
+            AET_HIP(ctx, launch_lenet_round(ctx->stream, ctx->profp(), dp, nact, (int)max_m, start, ctx->lay, ctx->L, ctx->B,
+                                            ctx->ws + ctx->lo.fused, ctx->n, &ctx->epoch));
         } else {
             AET_HIP(ctx, launch_begin_round(ctx->stream, ctx->profp(), dp, nact, start, ctx->P));
             for (int64_t u = 0; u < max_m; ++u)
@@ -733,9 +740,11 @@ aet_status aet_receive(aet_ctx *ctx, float scale, int32_t *n_applied, int32_t *a
 
 // After a synchronisation: did a fused kernel give up waiting for its cluster peers?
 static aet_status check_device_flag(aet_ctx *ctx) {
-    if (ctx->engine != ENGINE_MLP) return AET_OK;
+    if (ctx->engine != ENGINE_MLP && ctx->engine != ENGINE_LENET) return AET_OK;
     int flag = 0;
-    AET_HIP(ctx, hipMemcpyAsync(&flag, mlp_error_flag_ptr(ctx->ws + ctx->lo.fused, ctx->n, ctx->B), 4, hipMemcpyDeviceToHost, ctx->stream));
+    const int *dflag = ctx->engine == ENGINE_MLP ? mlp_error_flag_ptr(ctx->ws + ctx->lo.fused, ctx->n, ctx->B)
+                                                 : lenet_error_flag_ptr(ctx->ws + ctx->lo.fused, ctx->n);
+    AET_HIP(ctx, hipMemcpyAsync(&flag, dflag, 4, hipMemcpyDeviceToHost, ctx->stream));
     AET_HIP(ctx, hipStreamSynchronize(ctx->stream));
     if (flag) {
         ctx->dead = true;

@@ -58,7 +58,7 @@ struct LayerScratch {
 enum Family {
     F_BEGIN_ROUND = 0, F_GATHER, F_DENSE_FWD, F_DENSE_BWD_DATA, F_DENSE_BWD_WEIGHT, F_CONV_FWD,
     F_CONV_BWD_DATA, F_CONV_BWD_WEIGHT, F_POOL_FWD, F_POOL_BWD, F_SOFTMAX_CE, F_SERVER_REDUCE,
-    F_SOFTMAX_ROUND, F_MLP_ROUND, F_NEIGHBOUR_APPLY, F_COUNT
+    F_SOFTMAX_ROUND, F_MLP_ROUND, F_NEIGHBOUR_APPLY, F_LENET_ROUND, F_COUNT
 };
 const char *family_name(int fam);
 
@@ -129,5 +129,13 @@ hipError_t launch_mlp_round(hipStream_t s, Profiler *prof, const RoundParams *hp
                             int n_clients, uint32_t *epoch);
 hipError_t mlp_clear_error_flag(hipStream_t s, void *scratch, int n_clients, int B);
 const int *mlp_error_flag_ptr(void *scratch, int n_clients, int B);
+// fused round of LeNet-5-style models (kernels_lenet.hip); dp: DEVICE array of round records
+bool lenet_round_supported(const LayerGeom *lay, int L, int B);
+size_t lenet_round_scratch_bytes(int n_clients);
+hipError_t launch_lenet_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int max_m,
+                              const float *Wg, const LayerGeom *lay, int L, int B, void *scratch,
+                              int n_clients, uint32_t *epoch);
+hipError_t lenet_clear_error_flag(hipStream_t s, void *scratch, int n_clients);
+const int *lenet_error_flag_ptr(void *scratch, int n_clients);
 
 }  // namespace aet

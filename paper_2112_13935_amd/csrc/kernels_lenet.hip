@@ -1,0 +1,931 @@
+// Fused local round for LeNet-5-style models:
+//   conv 5x5 (1 -> 6, ReLU), 2x2 max pool, conv 5x5 (6 -> 16, ReLU), 2x2 max pool,
+//   dense F0 -> 120 (ReLU), dense 120 -> 84 (ReLU), dense 84 -> 10, mini-batch B = 16.
+//
+// One launch runs the whole round (Algorithm 2, MainComputeNode: all s_i/B recursions) of
+// every active client.  A client is a cluster of 4 workgroups.  Workgroup g
+//   - runs the convolutional part for samples 4g..4g+3 of every mini-batch, with a full copy
+//     of the two filter banks in LDS;
+//   - owns 30 of the 120 units of the first dense layer and 21 of the 84 of the second (their
+//     weight rows in LDS, for all 16 samples), and a full copy of the last layer.
+// The replica and U never leave the chip during the round: weights live in LDS (they are read
+// in several patterns), every thread keeps the U entries of the weights it updates in
+// registers.  Per recursion the workgroups of a cluster exchange, through tagged 64-bit
+// {step, value} words in memory that every reader polls for the current step (no barrier
+// across workgroups, no fence):
+//   forward   the pooled output of the second convolution, the outputs of the two hidden
+//             dense layers (each workgroup posts its samples / units, everyone reads all);
+//   backward  partial sums of d loss / d (input) of the two hidden dense layers over the own
+//             units (readers add the four partials in workgroup order), and the partial
+//             gradients of the two filter banks over the own samples (likewise), after
+//             which every workgroup applies the same update to its copy.
+// Every exchange involves all four workgroups in both directions, so one record per
+// exchange is enough: nobody can post step u+1 of an exchange before everybody has read
+// step u of it.
+//
+// Max pooling keeps, per window, which of its four inputs won; the backward pass through a
+// convolution + ReLU + pool stage touches only that input (the other three get no gradient),
+// so the filter gradients are sums over one position per window instead of four.
+//
+// All workgroups of a client must be resident together; the wait for a peer's word is
+// bounded and raises an error flag instead of hanging (every workgroup still runs to the end).
+#include "aet_device.h"
+#include "aet_internal.h"
+
+namespace aet {
+
+namespace {
+
+typedef float f4 __attribute__((ext_vector_type(4)));
+typedef unsigned long long u64;
+
+constexpr int kLnThreads = 512;
+constexpr int kLnG = 4;              // workgroups per client
+constexpr int kLnB = 16;             // mini-batch
+constexpr int kF1 = 120, kF2 = 84, kNC = 10;
+constexpr int kU1 = kF1 / kLnG, kU2 = kF2 / kLnG;   // units of the hidden layers per workgroup
+constexpr int kS1 = 124, kS2 = 88;   // LDS row strides of arrays with 120 / 84 columns
+constexpr int kConvP = 2572;         // parameters of the two filter banks (150 + 6 + 2400 + 16)
+constexpr int kLnSpin = 1 << 22;     // bounded wait of the exchange poll
+
+// exchange records of one client, in 64-bit words
+constexpr int kXA1 = 0;              // [16][256]      pooled output of conv 2
+constexpr int kXA2 = 4096;           // [16][128]      output of dense 1
+constexpr int kXA3 = 6144;           // [16][96]       output of dense 2
+constexpr int kXB1 = 7680;           // [4][16][128]   partial d loss / d (output of dense 1)
+constexpr int kXB2 = 15872;          // [4][16][256]   partial d loss / d (pooled output of conv 2)
+constexpr int kXB3 = 32256;          // [4][2576]      partial filter-bank gradients
+constexpr int kXWords = 43008;
+
+struct LenetDims {
+    int H0, P1, H2, P2, F0;          // input side, sides after pool 1 / conv 2 / pool 2, F0 = 16 P2^2
+    int64_t o_f1, o_f2, o_f3;        // offsets of the dense layers in the flat parameter vector
+};
+
+__device__ __forceinline__ float row16_sum_ln(float v) {
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true));
+    v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true));
+    return v;
+}
+__device__ __forceinline__ float row16_max_ln(float v) {
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x141, 0xF, 0xF, true)));
+    v = fmaxf(v, __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x140, 0xF, 0xF, true)));
+    return v;
+}
+
+// Hides a value from the optimiser so that what is derived from it is computed where it is used.
+__device__ __forceinline__ int opaque(int x) {
+    asm volatile("" : "+v"(x));
+    return x;
+}
+
+__device__ __forceinline__ void xpost(u64 *p, uint32_t tag, float v) {
+    __hip_atomic_store(p, ((u64)tag << 32) | (u64)__float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+struct Waiter {
+    uint32_t tag;
+    int *errflag;
+    bool dead;
+};
+
+// N words at once (the loads are in flight together); repeated until every needed word shows
+// the current step.  Words that are not needed still point at valid memory.
+template <int N>
+__device__ __forceinline__ void xfetch(const u64 *(&p)[N], const bool (&need)[N], float (&out)[N], Waiter &w) {
+    int spins = 0;
+    for (;;) {
+        u64 v[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) v[i] = __hip_atomic_load(p[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bool ok = true;
+#pragma unroll
+        for (int i = 0; i < N; ++i) ok = ok && (!need[i] || (uint32_t)(v[i] >> 32) == w.tag);
+        if (ok || w.dead) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) out[i] = __uint_as_float((uint32_t)v[i]);
+            return;
+        }
+        __builtin_amdgcn_s_sleep(1);
+        if ((++spins & 255) == 0) {
+            if (spins >= kLnSpin || __hip_atomic_load(w.errflag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) {
+                __hip_atomic_store(w.errflag, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                w.dead = true;
+            }
+        }
+    }
+}
+
+// 5 x 5 convolution at the four positions of a 2 x 2 window from a 6 x 6 patch, added to acc
+__device__ __forceinline__ void conv_window(const float (&patch)[6][6], const float *__restrict__ wv, float (&acc)[4]) {
+#pragma unroll
+    for (int ky = 0; ky < 5; ++ky)
+#pragma unroll
+        for (int kx = 0; kx < 5; ++kx) {
+            const float wgt = wv[ky * 5 + kx];
+            acc[0] += wgt * patch[ky][kx];
+            acc[1] += wgt * patch[ky][kx + 1];
+            acc[2] += wgt * patch[ky + 1][kx];
+            acc[3] += wgt * patch[ky + 1][kx + 1];
+        }
+}
+// ReLU, then the first maximum of the window in row-major order
+__device__ __forceinline__ float relu_pool(const float (&acc)[4], int &which) {
+    float best = acc[0] > 0.f ? acc[0] : 0.f;
+    which = 0;
+#pragma unroll
+    for (int k = 1; k < 4; ++k) {
+        const float v = acc[k] > 0.f ? acc[k] : 0.f;
+        if (v > best) { best = v; which = k; }
+    }
+    return best;
+}
+
+__global__ void __launch_bounds__(kLnThreads, 1)
+k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const float *Wg, const LenetDims d,
+              u64 *__restrict__ xrec, uint32_t tag0, int *__restrict__ errflag) {
+    // consecutive workgroup ids go round the 8 XCDs: the four workgroups of a client get ids
+    // that land on the same XCD and exchange through its L2
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int a = xcd + 8 * (slot / kLnG), g = slot % kLnG;
+    if (a >= nhere) return;
+    const RoundParams p = rp[a];
+    const gcf_ptr Xg = as_global(p.X);
+    const gci_ptr yg = as_global(p.y);
+    const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
+    const int tid = threadIdx.x;
+    const int H0 = d.H0, P1 = d.P1, H2 = d.H2, P2 = d.P2, F0 = d.F0;
+    const int nwin1 = P1 * P1, nwin2 = P2 * P2, npix = H0 * H0;
+    const int P1S = 6 * nwin1 + 8;       // per-sample stride of the pooled conv-1 maps
+    const int F0P = F0 + 4;              // row stride of arrays with F0 columns
+    const float invB = 1.0f / (float)kLnB;
+    const float eta = p.eta;
+
+    extern __shared__ __align__(16) float smem[];
+    auto up4 = [](int n) { return (n + 3) & ~3; };
+    float *xs = smem;                              // [4][npix]          own samples
+    float *p1 = xs + up4(4 * npix);                // [4][P1S]           pooled conv 1 (after ReLU)
+    float *a0 = p1 + 4 * P1S;                      // [16][F0P]          pooled conv 2, all samples
+    uint8_t *idx1 = reinterpret_cast<uint8_t *>(a0 + 16 * F0P);          // [4][6][nwin1] winner of each window
+    uint8_t *idx2 = idx1 + up4(4 * 6 * nwin1);                           // [4][F0]
+    float *wc1 = reinterpret_cast<float *>(idx2 + up4(4 * F0));          // [150] + bias [6] (+ pad)
+    float *wc2 = wc1 + 160;                        // [16][152]
+    float *wc2b = wc2 + 16 * 152;                  // [16]
+    float *w1s = wc2b + 16;                        // [30][F0P]
+    float *b1s = w1s + kU1 * F0P;                  // [32]
+    float *w2s = b1s + 32;                         // [21][kS1]
+    float *b2s = w2s + kU2 * kS1;                  // [32]
+    float *w3s = b2s + 32;                         // [10][kS2]
+    float *b3s = w3s + kNC * kS2;                  // [16]
+    float *h1 = b3s + 16;                          // [16][kS1]
+    float *h2 = h1 + 16 * kS1;                     // [16][kS2]
+    float *dz = h2 + 16 * kS2;                     // [16][16]   d loss / d logits
+    float *dh2 = dz + 256;                         // [16][kS2]
+    float *d2own = dh2 + 16 * kS2;                 // [16][24]   delta of the own units of dense 2
+    float *d1own = d2own + 16 * 24;                // [16][32]   ... of dense 1
+    float *dp2 = d1own + 16 * 32;                  // [4][F0]    delta at the pooled conv-2 outputs (own samples)
+    float *gsum = dp2 + up4(4 * F0);               // [2576]     filter-bank gradients over the own samples
+    float *c1part = gsum + 2576;                   // [14][160]  conv-1 gradient, partial over window groups
+    float *lossb = c1part + 14 * 160;              // [16]
+    int *labs = reinterpret_cast<int *>(lossb + 16);   // [16]
+    float *lossacc = reinterpret_cast<float *>(labs + 16);  // [4]
+    // regions that are dead by the time these are needed
+    float *dc2 = a0;                               // [4][16][H2*H2]  delta at the conv-2 outputs (after the dense backward)
+    float *dp1 = h1;                               // [4][P1S]        delta at the pooled conv-1 outputs
+
+    u64 *rec = xrec + (int64_t)(rec0 + a) * kXWords;
+    Waiter wt{tag0, errflag, false};
+
+    // ---- adopt the global model (server form) or go on from the own replica (Wg == NULL) ----
+    const float *src = Wg ? Wg : p.W;
+    for (int i = tid; i < 156; i += kLnThreads) wc1[i] = src[i];
+    for (int i = tid; i < 2400; i += kLnThreads) wc2[(i / 150) * 152 + i % 150] = src[156 + i];
+    if (tid < 16) wc2b[tid] = src[2556 + tid];
+    for (int i = tid; i < kU1 * F0; i += kLnThreads) {
+        const int ul = i / F0, k = i % F0;
+        w1s[ul * F0P + k] = src[d.o_f1 + (int64_t)(kU1 * g + ul) * F0 + k];
+    }
+    if (tid < kU1) b1s[tid] = src[d.o_f1 + (int64_t)kF1 * F0 + kU1 * g + tid];
+    for (int i = tid; i < kU2 * kF1; i += kLnThreads) {
+        const int ul = i / kF1, k = i % kF1;
+        w2s[ul * kS1 + k] = src[d.o_f2 + (int64_t)(kU2 * g + ul) * kF1 + k];
+    }
+    if (tid < kU2) b2s[tid] = src[d.o_f2 + kF2 * kF1 + kU2 * g + tid];
+    for (int i = tid; i < kNC * kF2; i += kLnThreads) w3s[(i / kF2) * kS2 + i % kF2] = src[d.o_f3 + i];
+    if (tid < kNC) b3s[tid] = src[d.o_f3 + kNC * kF2 + tid];
+    if (tid == 0) lossacc[0] = 0.f;
+    // U of the weights this thread updates
+    float U1[15], U2[5], U3[2], UC[6];
+    float U1b = 0.f, U2b = 0.f, U3b = 0.f;
+#pragma unroll
+    for (int j = 0; j < 15; ++j) U1[j] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 5; ++j) U2[j] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) U3[j] = 0.f;
+#pragma unroll
+    for (int j = 0; j < 6; ++j) UC[j] = 0.f;
+
+    // the own samples' rows travel global -> registers (one recursion ahead) -> LDS
+    const int nq = npix >> 2;   // 16-byte pieces per row
+    auto load_rows = [&](int u, f4 (&xr)[2], int &lab) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = tid + kLnThreads * j;
+            xr[j] = f4{0.f, 0.f, 0.f, 0.f};
+            if (e < 4 * nq) {
+                const int s = e / nq, q = e % nq;
+                const uint32_t row = sample_row(p.key, (uint64_t)(p.q0 + (int64_t)u * kLnB + 4 * g + s), p.n_samples);
+                xr[j] = *reinterpret_cast<const f4 __attribute__((address_space(1))) *>(Xg + (int64_t)row * npix + 4 * q);
+            }
+        }
+        lab = 0;
+        if (tid < kLnB) lab = yg[sample_row(p.key, (uint64_t)(p.q0 + (int64_t)u * kLnB + tid), p.n_samples)];
+    };
+    auto store_rows = [&](const f4 (&xr)[2], int lab) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = tid + kLnThreads * j;
+            if (e < 4 * nq) *reinterpret_cast<f4 *>(xs + 4 * e) = xr[j];   // s * npix + 4 q = 4 e
+        }
+        if (tid < kLnB) labs[tid] = lab;
+    };
+    f4 xr[2];
+    int labr = 0;
+    if (p.m > 0) {
+        load_rows(0, xr, labr);
+        store_rows(xr, labr);
+    }
+    __syncthreads();
+
+    for (int u = 0; u < p.m; ++u) {
+        // index arithmetic is redone where it is used instead of being kept in registers across
+        // the whole recursion
+        int tq = opaque(tid);
+        wt.tag = tag0 + (uint32_t)u;
+        const bool more = u + 1 < p.m;
+        if (more) load_rows(u + 1, xr, labr);   // Algorithm 2, sampling step: a counter hash, known ahead
+
+        tq = opaque(tq);
+        // ---- conv 1 + ReLU + pool: item = (sample, window, three of the six channels) --------
+#pragma unroll 1
+        for (int it = tq; it < 8 * nwin1; it += kLnThreads) {
+            const int half = it & 1, w = it >> 1, px = w % P1, py = (w / P1) % P1, s = w / nwin1;
+            float patch[6][6];
+            const float *xp = xs + s * npix + (2 * py) * H0 + 2 * px;
+#pragma unroll
+            for (int i = 0; i < 6; ++i)
+#pragma unroll
+                for (int j = 0; j < 6; ++j) patch[i][j] = xp[i * H0 + j];
+#pragma unroll
+            for (int cc = 0; cc < 3; ++cc) {
+                const int c = 3 * half + cc;
+                const float b = wc1[150 + c];
+                float acc[4] = {b, b, b, b};
+                conv_window(patch, wc1 + c * 25, acc);
+                int which;
+                const float v = relu_pool(acc, which);
+                p1[s * P1S + c * nwin1 + py * P1 + px] = v;
+                idx1[(s * 6 + c) * nwin1 + py * P1 + px] = (uint8_t)which;
+            }
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- conv 2 + ReLU + pool: item = (sample, channel, window); a wave holds 16 windows x 4
+        // channels of one sample, so patch reads are broadcast over the channels ----------------
+#pragma unroll 1
+        for (int it = tq; it < 64 * nwin2; it += kLnThreads) {
+            const int c4 = it & 3, r = it >> 2, win = r % nwin2, cg = (r / nwin2) & 3, s = r / (4 * nwin2);
+            const int c = 4 * cg + c4, oy = win / P2, ox = win % P2;
+            const float b = wc2b[c];
+            float acc[4] = {b, b, b, b};
+#pragma unroll 1
+            for (int ci = 0; ci < 6; ++ci) {
+                float patch[6][6];
+                const float *pp = p1 + s * P1S + ci * nwin1 + (2 * oy) * P1 + 2 * ox;
+#pragma unroll
+                for (int i = 0; i < 6; ++i)
+#pragma unroll
+                    for (int j = 0; j < 6; ++j) patch[i][j] = pp[i * P1 + j];
+                conv_window(patch, wc2 + c * 152 + ci * 25, acc);
+            }
+            int which;
+            const float v = relu_pool(acc, which);
+            const int f = c * nwin2 + win;    // flattened C, H, W
+            a0[(4 * g + s) * F0P + f] = v;
+            idx2[s * F0 + f] = (uint8_t)which;
+            xpost(rec + kXA1 + (4 * g + s) * 256 + f, wt.tag, v);
+        }
+        // the other workgroups' samples
+        for (int e0 = tq; e0 < 16 * F0; e0 += 4 * kLnThreads) {
+            const u64 *ptr[4];
+            bool need[4];
+            float val[4];
+            int dst[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = e0 + kLnThreads * i;
+                const bool in = e < 16 * F0;
+                const int b = in ? e / F0 : 0, f = in ? e % F0 : 0;
+                need[i] = in && (b >> 2) != g;
+                ptr[i] = rec + kXA1 + b * 256 + f;
+                dst[i] = b * F0P + f;
+            }
+            xfetch<4>(ptr, need, val, wt);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (need[i]) a0[dst[i]] = val[i];
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- dense 1, own units: thread = (unit, sample) ----------------------------------------
+        if (tq < kU1 * 16) {
+            const int ul = tq >> 4, b = tq & 15;
+            float acc = b1s[ul];
+            const float *wr = w1s + ul * F0P, *ar = a0 + b * F0P;
+            for (int k = 0; k < F0; k += 4) {
+                const f4 wv = *reinterpret_cast<const f4 *>(wr + k), av = *reinterpret_cast<const f4 *>(ar + k);
+                acc += wv[0] * av[0];
+                acc += wv[1] * av[1];
+                acc += wv[2] * av[2];
+                acc += wv[3] * av[3];
+            }
+            const float h = acc > 0.f ? acc : 0.f;
+            h1[b * kS1 + kU1 * g + ul] = h;
+            xpost(rec + kXA2 + b * 128 + kU1 * g + ul, wt.tag, h);
+        }
+        for (int e0 = tq; e0 < 16 * kF1; e0 += 4 * kLnThreads) {
+            const u64 *ptr[4];
+            bool need[4];
+            float val[4];
+            int dst[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = e0 + kLnThreads * i;
+                const bool in = e < 16 * kF1;
+                const int b = in ? e / kF1 : 0, k = in ? e % kF1 : 0;
+                need[i] = in && k / kU1 != g;
+                ptr[i] = rec + kXA2 + b * 128 + k;
+                dst[i] = b * kS1 + k;
+            }
+            xfetch<4>(ptr, need, val, wt);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (need[i]) h1[dst[i]] = val[i];
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- dense 2, own units ------------------------------------------------------------------
+        if (tq < kU2 * 16) {
+            const int ul = tq >> 4, b = tq & 15;
+            float acc = b2s[ul];
+            const float *wr = w2s + ul * kS1, *ar = h1 + b * kS1;
+            for (int k = 0; k < kF1; k += 4) {
+                const f4 wv = *reinterpret_cast<const f4 *>(wr + k), av = *reinterpret_cast<const f4 *>(ar + k);
+                acc += wv[0] * av[0];
+                acc += wv[1] * av[1];
+                acc += wv[2] * av[2];
+                acc += wv[3] * av[3];
+            }
+            const float h = acc > 0.f ? acc : 0.f;
+            h2[b * kS2 + kU2 * g + ul] = h;
+            xpost(rec + kXA3 + b * 96 + kU2 * g + ul, wt.tag, h);
+        }
+        for (int e0 = tq; e0 < 16 * kF2; e0 += 4 * kLnThreads) {
+            const u64 *ptr[4];
+            bool need[4];
+            float val[4];
+            int dst[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int e = e0 + kLnThreads * i;
+                const bool in = e < 16 * kF2;
+                const int b = in ? e / kF2 : 0, k = in ? e % kF2 : 0;
+                need[i] = in && k / kU2 != g;
+                ptr[i] = rec + kXA3 + b * 96 + k;
+                dst[i] = b * kS2 + k;
+            }
+            xfetch<4>(ptr, need, val, wt);
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (need[i]) h2[dst[i]] = val[i];
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- dense 3 (every workgroup, all samples), softmax, d logits: thread = (sample, class) --
+        if (tq < 256) {
+            const int b = tq >> 4, o = tq & 15;
+            float z = 0.f;
+            if (o < kNC) {
+                z = b3s[o];
+                const float *wr = w3s + o * kS2, *ar = h2 + b * kS2;
+                for (int k = 0; k < kF2; k += 4) {
+                    const f4 wv = *reinterpret_cast<const f4 *>(wr + k), av = *reinterpret_cast<const f4 *>(ar + k);
+                    z += wv[0] * av[0];
+                    z += wv[1] * av[1];
+                    z += wv[2] * av[2];
+                    z += wv[3] * av[3];
+                }
+            }
+            const float zmax = row16_max_ln(o < kNC ? z : -3.0e38f);
+            const float ex = o < kNC ? __expf(z - zmax) : 0.f;
+            const float lse = zmax + __logf(row16_sum_ln(ex));
+            const int lab = labs[b];
+            if (o == lab) lossb[b] = lse - z;
+            dz[b * 16 + o] = o < kNC ? __expf(z - lse) - (o == lab ? 1.f : 0.f) : 0.f;
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- backward through dense 3: d h2 (reads the not yet updated weights) ------------------
+        for (int e = tq; e < 16 * kF2; e += kLnThreads) {
+            const int b = e / kF2, k = e % kF2;
+            float acc = 0.f;
+#pragma unroll
+            for (int o = 0; o < kNC; ++o) acc += dz[b * 16 + o] * w3s[o * kS2 + k];
+            dh2[b * kS2 + k] = acc;
+        }
+        if (g == 0 && tq == 0) {
+            float s = 0.f;
+            for (int b = 0; b < kLnB; ++b) s += lossb[b];
+            lossacc[0] += s * invB;
+        }
+        __syncthreads();
+        // dense 3: w <- w - eta g, U <- U + g (the same in every workgroup); delta of the own
+        // units of dense 2
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = tq + kLnThreads * j;
+            if (e < kNC * kF2) {
+                const int o = e / kF2, k = e % kF2;
+                float s = 0.f;
+#pragma unroll
+                for (int b = 0; b < kLnB; ++b) s += dz[b * 16 + o] * h2[b * kS2 + k];
+                const float gv = s * invB;
+                w3s[o * kS2 + k] -= eta * gv;
+                U3[j] += gv;
+            }
+        }
+        if (tq < kNC) {
+            float s = 0.f;
+#pragma unroll
+            for (int b = 0; b < kLnB; ++b) s += dz[b * 16 + tq];
+            const float gv = s * invB;
+            b3s[tq] -= eta * gv;
+            U3b += gv;
+        }
+        if (tq < kU2 * 16) {
+            const int ul = tq >> 4, b = tq & 15, k = kU2 * g + ul;
+            d2own[b * 24 + ul] = h2[b * kS2 + k] > 0.f ? dh2[b * kS2 + k] : 0.f;
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- backward through dense 2: partial d h1 over the own units -> exchange ---------------
+        for (int e = tq; e < 16 * kF1; e += kLnThreads) {
+            const int b = e / kF1, k = e % kF1;
+            float acc = 0.f;
+#pragma unroll
+            for (int ul = 0; ul < kU2; ++ul) acc += d2own[b * 24 + ul] * w2s[ul * kS1 + k];
+            xpost(rec + kXB1 + g * 2048 + b * 128 + k, wt.tag, acc);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const int e = tq + kLnThreads * j;
+            if (e < kU2 * kF1) {
+                const int ul = e / kF1, k = e % kF1;
+                float s = 0.f;
+#pragma unroll
+                for (int b = 0; b < kLnB; ++b) s += d2own[b * 24 + ul] * h1[b * kS1 + k];
+                const float gv = s * invB;
+                w2s[ul * kS1 + k] -= eta * gv;
+                U2[j] += gv;
+            }
+        }
+        if (tq < kU2) {
+            float s = 0.f;
+#pragma unroll
+            for (int b = 0; b < kLnB; ++b) s += d2own[b * 24 + tq];
+            const float gv = s * invB;
+            b2s[tq] -= eta * gv;
+            U2b += gv;
+        }
+        // delta of the own units of dense 1: the four partials in workgroup order
+        {
+            const bool act = tq < kU1 * 16;
+            const int ul = act ? tq >> 4 : 0, b = tq & 15, k = kU1 * g + ul;
+            const u64 *ptr[4];
+            bool need[4];
+            float val[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ptr[i] = rec + kXB1 + i * 2048 + b * 128 + k;
+                need[i] = act;
+            }
+            xfetch<4>(ptr, need, val, wt);
+            if (act) {
+                float s = val[0];
+                s += val[1];
+                s += val[2];
+                s += val[3];
+                d1own[b * 32 + ul] = h1[b * kS1 + k] > 0.f ? s : 0.f;
+            }
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- backward through dense 1: partial d a0 over the own units -> exchange ---------------
+        for (int e0 = tq; e0 < 16 * F0; e0 += 8 * kLnThreads) {
+            float acc[8];
+            int bb[8], ff[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int e = e0 + kLnThreads * i;
+                const bool in = e < 16 * F0;
+                bb[i] = in ? e / F0 : 0;
+                ff[i] = in ? e % F0 : 0;
+                acc[i] = 0.f;
+            }
+#pragma unroll 2
+            for (int ul = 0; ul < kU1; ++ul) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[i] += d1own[bb[i] * 32 + ul] * w1s[ul * F0P + ff[i]];
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                if (e0 + kLnThreads * i < 16 * F0) xpost(rec + kXB2 + g * 4096 + bb[i] * 256 + ff[i], wt.tag, acc[i]);
+        }
+        // which of the own pooled conv-2 outputs are positive (a0 is overwritten below)
+        bool pos2[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = tq + kLnThreads * j;
+            pos2[j] = e < 4 * F0 && a0[(4 * g + e / F0) * F0P + e % F0] > 0.f;
+        }
+        __syncthreads();
+        // dense 1: w <- w - eta g, U <- U + g on the own rows
+#pragma unroll
+        for (int j = 0; j < 15; ++j) {
+            const int e = tq + kLnThreads * j;
+            if (e < kU1 * F0) {
+                const int ul = e / F0, k = e % F0;
+                float s = 0.f;
+#pragma unroll
+                for (int b = 0; b < kLnB; ++b) s += d1own[b * 32 + ul] * a0[b * F0P + k];
+                const float gv = s * invB;
+                w1s[ul * F0P + k] -= eta * gv;
+                U1[j] += gv;
+            }
+        }
+        if (tq < kU1) {
+            float s = 0.f;
+#pragma unroll
+            for (int b = 0; b < kLnB; ++b) s += d1own[b * 32 + tq];
+            const float gv = s * invB;
+            b1s[tq] -= eta * gv;
+            U1b += gv;
+        }
+        // delta at the own samples' pooled conv-2 outputs (masked by the ReLU)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = tq + kLnThreads * j;
+            const bool act = e < 4 * F0;
+            const int s = act ? e / F0 : 0, f = act ? e % F0 : 0;
+            const u64 *ptr[4];
+            bool need[4];
+            float val[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ptr[i] = rec + kXB2 + i * 4096 + (4 * g + s) * 256 + f;
+                need[i] = act;
+            }
+            xfetch<4>(ptr, need, val, wt);
+            if (act) {
+                float t = val[0];
+                t += val[1];
+                t += val[2];
+                t += val[3];
+                dp2[e] = pos2[j] ? t : 0.f;
+            }
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- backward through conv 2 ---------------------------------------------------------------
+        // delta at the conv-2 outputs: zero but at the winner of every window
+        for (int i = tq; i < 64 * H2 * H2; i += kLnThreads) dc2[i] = 0.f;
+        __syncthreads();
+        for (int e = tq; e < 4 * F0; e += kLnThreads) {
+            const int s = e / F0, f = e % F0, c = f / nwin2, win = f % nwin2;
+            const int k = idx2[e], y = 2 * (win / P2) + (k >> 1), x = 2 * (win % P2) + (k & 1);
+            dc2[((s * 16 + c) * H2 + y) * H2 + x] = dp2[e];
+        }
+        // filter gradient over the own samples: thread = (channel, input channel, filter row);
+        // one position per window
+        if (tq < 480) {
+            const int c = tq / 30, r = tq % 30, ci = r / 5, ky = r % 5;
+            float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+            for (int s = 0; s < 4; ++s)
+#pragma unroll 2
+                for (int win = 0; win < nwin2; ++win) {
+                    const int e = s * F0 + c * nwin2 + win;
+                    const float dl = dp2[e];
+                    const int k = idx2[e], y = 2 * (win / P2) + (k >> 1), x = 2 * (win % P2) + (k & 1);
+                    const float *row = p1 + s * P1S + ci * nwin1 + (y + ky) * P1 + x;
+#pragma unroll
+                    for (int kx = 0; kx < 5; ++kx) acc[kx] += dl * row[kx];
+                }
+#pragma unroll
+            for (int kx = 0; kx < 5; ++kx) gsum[156 + c * 150 + ci * 25 + ky * 5 + kx] = acc[kx];
+        } else if (tq < 496) {
+            const int c = tq - 480;
+            float s = 0.f;
+            for (int i = 0; i < 4; ++i)
+                for (int win = 0; win < nwin2; ++win) s += dp2[i * F0 + c * nwin2 + win];
+            gsum[2556 + c] = s;
+        }
+        __syncthreads();
+        // delta at the pooled conv-1 outputs (dense correlation with the flipped filters), masked
+        // by the ReLU: item = (sample, input channel, row, half a row)
+        {
+            const int XW = P1 >> 1;   // <= 6
+#pragma unroll 1
+            for (int it = tq; it < 48 * P1; it += kLnThreads) {
+                const int half = it & 1, r = it >> 1, yy = r % P1, ci = (r / P1) % 6, s = r / (6 * P1);
+                const int x0 = half * XW;
+                float acc[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                const int ky_lo = yy - (H2 - 1) > 0 ? yy - (H2 - 1) : 0, ky_hi = yy < 4 ? yy : 4;
+#pragma unroll 1
+                for (int c = 0; c < 16; ++c) {
+#pragma unroll 1
+                    for (int ky = ky_lo; ky <= ky_hi; ++ky) {
+                        const float *row = dc2 + ((s * 16 + c) * H2 + (yy - ky)) * H2;
+                        const float *wrow = wc2 + c * 152 + ci * 25 + ky * 5;
+                        float seg[10];   // delta at columns x0 - 4 .. x0 + 5
+#pragma unroll
+                        for (int i = 0; i < 10; ++i) {
+                            const int x = x0 - 4 + i;
+                            seg[i] = (x >= 0 && x < H2) ? row[x] : 0.f;
+                        }
+#pragma unroll
+                        for (int kx = 0; kx < 5; ++kx) {
+                            const float wgt = wrow[kx];
+#pragma unroll
+                            for (int xi = 0; xi < 6; ++xi) acc[xi] += seg[xi + 4 - kx] * wgt;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int xi = 0; xi < 6; ++xi)
+                    if (xi < XW) {
+                        const int o = s * P1S + ci * nwin1 + yy * P1 + x0 + xi;
+                        dp1[o] = p1[o] > 0.f ? acc[xi] : 0.f;
+                    }
+            }
+        }
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- conv-1 filter gradient over the own samples: thread = (window group, channel,
+        // filter row or bias); one position per window ---------------------------------------------
+        if (tq < 14 * 36) {
+            const int grp = tq / 36, r = tq % 36;
+            if (r < 30) {
+                const int c = r / 5, ky = r % 5;
+                float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll 2
+                for (int i = grp; i < 4 * nwin1; i += 14) {
+                    const int s = i / nwin1, win = i % nwin1;
+                    const float dl = dp1[s * P1S + c * nwin1 + win];
+                    const int k = idx1[(s * 6 + c) * nwin1 + win];
+                    const int y = 2 * (win / P1) + (k >> 1), x = 2 * (win % P1) + (k & 1);
+                    const float *row = xs + s * npix + (y + ky) * H0 + x;
+#pragma unroll
+                    for (int kx = 0; kx < 5; ++kx) acc[kx] += dl * row[kx];
+                }
+#pragma unroll
+                for (int kx = 0; kx < 5; ++kx) c1part[grp * 160 + c * 25 + ky * 5 + kx] = acc[kx];
+            } else {
+                const int c = r - 30;
+                float s = 0.f;
+                for (int i = grp; i < 4 * nwin1; i += 14) s += dp1[(i / nwin1) * P1S + c * nwin1 + i % nwin1];
+                c1part[grp * 160 + 150 + c] = s;
+            }
+        }
+        __syncthreads();
+        if (tq < 156) {
+            float s = 0.f;
+#pragma unroll
+            for (int grp = 0; grp < 14; ++grp) s += c1part[grp * 160 + tq];
+            gsum[tq] = s;
+        }
+        // the next recursion's rows and labels (xs and labs are not read any more)
+        if (more) store_rows(xr, labr);
+        __syncthreads();
+
+        tq = opaque(tq);
+        // ---- filter banks: exchange the partial gradients, add them in workgroup order, update ----
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            const int e = tq + kLnThreads * j;
+            if (e < kConvP) xpost(rec + kXB3 + g * 2576 + e, wt.tag, gsum[e]);
+        }
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            const int e = tq + kLnThreads * j;
+            const bool act = e < kConvP;
+            const u64 *ptr[4];
+            bool need[4];
+            float val[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ptr[i] = rec + kXB3 + i * 2576 + (act ? e : 0);
+                need[i] = act;
+            }
+            xfetch<4>(ptr, need, val, wt);
+            if (act) {
+                float t = val[0];
+                t += val[1];
+                t += val[2];
+                t += val[3];
+                const float gv = t * invB;
+                float *w = e < 156 ? wc1 + e : e < 2556 ? wc2 + ((e - 156) / 150) * 152 + (e - 156) % 150 : wc2b + (e - 2556);
+                *w -= eta * gv;
+                UC[j] += gv;
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- end of round: the replica and the message payload go to HBM ------------------------------
+#pragma unroll
+    for (int j = 0; j < 15; ++j) {
+        const int e = tid + kLnThreads * j;
+        if (e < kU1 * F0) {
+            const int ul = e / F0, k = e % F0;
+            const int64_t o = d.o_f1 + (int64_t)(kU1 * g + ul) * F0 + k;
+            Wc[o] = w1s[ul * F0P + k];
+            Uc[o] = U1[j];
+        }
+    }
+    if (tid < kU1) {
+        const int64_t o = d.o_f1 + (int64_t)kF1 * F0 + kU1 * g + tid;
+        Wc[o] = b1s[tid];
+        Uc[o] = U1b;
+    }
+#pragma unroll
+    for (int j = 0; j < 5; ++j) {
+        const int e = tid + kLnThreads * j;
+        if (e < kU2 * kF1) {
+            const int ul = e / kF1, k = e % kF1;
+            const int64_t o = d.o_f2 + (int64_t)(kU2 * g + ul) * kF1 + k;
+            Wc[o] = w2s[ul * kS1 + k];
+            Uc[o] = U2[j];
+        }
+    }
+    if (tid < kU2) {
+        const int64_t o = d.o_f2 + kF2 * kF1 + kU2 * g + tid;
+        Wc[o] = b2s[tid];
+        Uc[o] = U2b;
+    }
+    if (g == 0) {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int e = tid + kLnThreads * j;
+            if (e < kNC * kF2) {
+                Wc[d.o_f3 + e] = w3s[(e / kF2) * kS2 + e % kF2];
+                Uc[d.o_f3 + e] = U3[j];
+            }
+        }
+        if (tid < kNC) {
+            Wc[d.o_f3 + kNC * kF2 + tid] = b3s[tid];
+            Uc[d.o_f3 + kNC * kF2 + tid] = U3b;
+        }
+#pragma unroll
+        for (int j = 0; j < 6; ++j) {
+            const int e = tid + kLnThreads * j;
+            if (e < kConvP) {
+                Wc[e] = e < 156 ? wc1[e] : e < 2556 ? wc2[((e - 156) / 150) * 152 + (e - 156) % 150] : wc2b[e - 2556];
+                Uc[e] = UC[j];
+            }
+        }
+        if (tid == 0) *as_global(p.loss) = lossacc[0];
+    }
+}
+
+__global__ void k_zero_words_ln(u64 *p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0ull;
+}
+
+bool lenet_dims(const LayerGeom *lay, int L, int B, LenetDims *d) {
+    if (L != 7 || B != kLnB) return false;
+    const LayerGeom &c1 = lay[0], &q1 = lay[1], &c2 = lay[2], &q2 = lay[3], &f1 = lay[4], &f2 = lay[5], &f3 = lay[6];
+    if (c1.type != 0 || q1.type != 1 || c2.type != 0 || q2.type != 1 || f1.type != 2 || f2.type != 2 || f3.type != 2) return false;
+    if (c1.k != 5 || c1.pad != 0 || !c1.relu || c1.ic != 1 || c1.oc != 6 || c1.ih != c1.iw) return false;
+    if (c2.k != 5 || c2.pad != 0 || !c2.relu || c2.oc != 16) return false;
+    if (f1.oc != kF1 || !f1.relu || f2.oc != kF2 || !f2.relu || f3.oc != kNC || f3.relu) return false;
+    d->H0 = c1.ih; d->P1 = q1.oh; d->H2 = c2.oh; d->P2 = q2.oh;
+    d->F0 = 16 * d->P2 * d->P2;
+    if (d->H0 > 32 || (d->H0 * d->H0) % 4 || d->P1 > 12 || (d->P1 & 1) || d->P2 < 1 || d->F0 > 256) return false;
+    if ((int64_t)d->F0 != f1.in_size) return false;
+    d->o_f1 = f1.w_off; d->o_f2 = f2.w_off; d->o_f3 = f3.w_off;
+    if (c1.w_off != 0 || c1.b_off != 150 || c2.w_off != 156 || c2.b_off != 2556 || f1.w_off != kConvP) return false;
+    return true;
+}
+
+size_t lenet_lds_bytes(const LenetDims &d) {
+    auto up4 = [](int n) { return (n + 3) & ~3; };
+    const int nwin1 = d.P1 * d.P1, P1S = 6 * nwin1 + 8, F0P = d.F0 + 4;
+    size_t fl = up4(4 * d.H0 * d.H0) + 4 * P1S + 16 * F0P;
+    fl += (up4(4 * 6 * nwin1) + up4(4 * d.F0)) / 4;
+    fl += 160 + 16 * 152 + 16 + kU1 * F0P + 32 + kU2 * kS1 + 32 + kNC * kS2 + 16;
+    fl += 16 * kS1 + 16 * kS2 + 256 + 16 * kS2 + 16 * 24 + 16 * 32 + up4(4 * d.F0) + 2576 + 14 * 160 + 16 + 16 + 4;
+    return fl * 4;
+}
+
+int g_lenet_per_cu = 0;
+
+}  // namespace
+
+bool lenet_round_supported(const LayerGeom *lay, int L, int B) {
+    LenetDims d;
+    if (!lenet_dims(lay, L, B, &d)) return false;
+    // the regions that take turns in LDS must fit where they are put
+    const int P1S = 6 * d.P1 * d.P1 + 8;
+    if (64 * d.H2 * d.H2 > 16 * (d.F0 + 4)) return false;                 // d conv-2 outputs over a0
+    if (4 * P1S > 16 * kS1 + 16 * kS2 + 256 + 16 * kS2) return false;     // d pooled conv-1 outputs over h1 .. dh2
+    return lenet_lds_bytes(d) <= 160 * 1024;
+}
+
+size_t lenet_round_scratch_bytes(int n_clients) { return (size_t)n_clients * kXWords * 8 + 256; }
+
+hipError_t lenet_clear_error_flag(hipStream_t s, void *scratch, int n_clients) {
+    u64 *xrec = static_cast<u64 *>(scratch);
+    k_zero_words_ln<<<1, 64, 0, s>>>(xrec + (size_t)n_clients * kXWords, 1);
+    return hipGetLastError();
+}
+
+const int *lenet_error_flag_ptr(void *scratch, int n_clients) {
+    return reinterpret_cast<const int *>(static_cast<u64 *>(scratch) + (size_t)n_clients * kXWords);
+}
+
+hipError_t launch_lenet_round(hipStream_t s, Profiler *prof, const RoundParams *dp, int nact, int max_m,
+                              const float *Wg, const LayerGeom *lay, int L, int B, void *scratch,
+                              int n_clients, uint32_t *epoch) {
+    if (nact <= 0) return hipSuccess;
+    LenetDims d;
+    if (!lenet_dims(lay, L, B, &d)) return hipErrorInvalidValue;
+    const size_t lds = lenet_lds_bytes(d);
+    hipError_t e;
+    if (g_lenet_per_cu == 0) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lenet_round), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+        if (e != hipSuccess) return e;
+    }
+    int dev = 0, cus = 0, per_cu = 0;
+    e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_lenet_round, kLnThreads, lds);
+    if (e != hipSuccess) return e;
+    g_lenet_per_cu = per_cu;
+    // clusters per launch: every workgroup that polls must be resident together with its peers
+    const int per_launch = cus * per_cu / kLnG;
+    if (per_launch < 1) return hipErrorLaunchOutOfResources;
+    u64 *xrec = static_cast<u64 *>(scratch);
+    int *errflag = reinterpret_cast<int *>(xrec + (size_t)n_clients * kXWords);
+    // step tags of this launch: never 0 (the cleared state) and never a tag that an earlier
+    // launch may have left in the records
+    if (*epoch == 0 || *epoch > 0xFFFFFFFFu - (uint32_t)max_m - 2u) {
+        const size_t words = (size_t)n_clients * kXWords;
+        k_zero_words_ln<<<(unsigned)((words + 255) / 256), 256, 0, s>>>(xrec, words);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        *epoch = 1;
+    }
+    const uint32_t tag0 = *epoch;
+    *epoch += (uint32_t)max_m + 1u;
+    for (int a0 = 0; a0 < nact; a0 += per_launch) {
+        const int here = nact - a0 < per_launch ? nact - a0 : per_launch;
+        const unsigned grid = (unsigned)(8 * ((here + 7) / 8) * kLnG);
+        if (prof && prof->on[F_LENET_ROUND]) prof->before(F_LENET_ROUND, s);
+        k_lenet_round<<<grid, kLnThreads, lds, s>>>(dp + a0, here, a0, Wg, d, xrec, tag0, errflag);
+        if (prof && prof->on[F_LENET_ROUND]) prof->after(F_LENET_ROUND, s);
+        e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+}  // namespace aet

@@ -7,7 +7,8 @@ const char *family_name(int fam) {
     static const char *names[F_COUNT] = {
         "k_begin_round", "k_gather", "k_dense_fwd", "k_dense_bwd_data", "k_dense_bwd_weight",
         "k_conv_fwd", "k_conv_bwd_data", "k_conv_bwd_weight", "k_pool_fwd", "k_pool_bwd",
-        "k_softmax_ce", "server_reduce", "k_softmax_round", "k_mlp_round", "k_apply_neighbour_U"};
+        "k_softmax_ce", "server_reduce", "k_softmax_round", "k_mlp_round", "k_apply_neighbour_U",
+        "k_lenet_round"};
     return (fam >= 0 && fam < F_COUNT) ? names[fam] : "";
 }
 

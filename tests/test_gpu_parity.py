@@ -115,6 +115,18 @@ def small_cases():
     cases["mlp_layers_aligned_b4"] = wl
     wl = W.config2(n_clients=3, n_total=3 * 80, d=256, hidden=120, batch=16, rounds=3, a=16, b=16)
     cases["mlp_layers_256_120_b16"] = wl
+    # shapes the fused LeNet round kernel takes (mini-batch 16, a cluster of four workgroups per
+    # client): 16 x 16 images (one pooled pixel per channel in front of the dense layers) with
+    # compute factors and stragglers, and the full 28 x 28 shape
+    wl = W.config3(n_clients=5, n_per=60, hw=16, batch=16, rounds=4, a=16, b=32)
+    wl.compute_factor = np.array([1, 2, 1, 3, 1], dtype=np.int32)
+    wl.is_straggler = np.array([0, 1, 0, 0, 1], dtype=np.uint8)
+    wl.delay_min, wl.delay_max, wl.delay_seed = 1, 2, 11
+    cases["lenet_fused_16x16_factors_stragglers"] = wl
+    wl = W.config3(n_clients=3, n_per=80, hw=28, batch=16, rounds=3, a=16, b=16)
+    cases["lenet_fused_28x28"] = wl
+    wl = W.config3(n_clients=9, n_per=50, hw=20, batch=16, rounds=3, a=16, b=0)
+    cases["lenet_fused_20x20_empty_first_round"] = wl
     # convolutions with 6 and 12 channels on 12 x 12 images: ragged channel groups in the
     # staging code, a pooling layer whose input rows are not 16-byte aligned (6 wide)
     wl = W.config4(n_clients=2, n_per=30, hw=12, width=6, fc=16, batch=4, rounds=3, a=4, b=4)
