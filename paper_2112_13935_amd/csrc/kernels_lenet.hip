@@ -58,7 +58,7 @@ constexpr int kXB3 = 32256;          // [4][2576]      partial filter-bank gradi
 constexpr int kXWords = 43008;
 
 struct LenetDims {
-    int H0, P1, H2, P2, F0;          // input side, sides after pool 1 / conv 2 / pool 2, F0 = 16 P2^2
+    int H0, P1, H2, P2, F0, lgF0;    // input side, sides after pool 1 / conv 2 / pool 2, F0 = 16 P2^2 = 2^lgF0
     int64_t o_f1, o_f2, o_f3;        // offsets of the dense layers in the flat parameter vector
 };
 
@@ -170,9 +170,13 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     float *xs = smem;                              // [4][npix]          own samples
     float *p1 = xs + up4(4 * npix);                // [4][P1S]           pooled conv 1 (after ReLU)
     float *a0 = p1 + 4 * P1S;                      // [16][F0P]          pooled conv 2, all samples
-    uint8_t *idx1 = reinterpret_cast<uint8_t *>(a0 + 16 * F0P);          // [4][6][nwin1] winner of each window
-    uint8_t *idx2 = idx1 + up4(4 * 6 * nwin1);                           // [4][F0]
-    float *wc1 = reinterpret_cast<float *>(idx2 + up4(4 * F0));          // [150] + bias [6] (+ pad)
+    float *d2own = a0 + 16 * F0P;                  // [16][24]   delta of the own units of dense 2
+    float *d1own = d2own + 16 * 24;                // [32][16]   ... of dense 1, unit-major
+    // the winner of every pooling window, as the offset of that input inside its map
+    uint16_t *off1 = reinterpret_cast<uint16_t *>(d1own + 16 * 32);        // [4][6][nwin1] in the H0 x H0 image (top-left of the 5 x 5 patch)
+    uint16_t *off2 = off1 + up4(4 * 6 * nwin1);                          // [4][F0]       in the P1 x P1 pooled conv-1 map
+    uint8_t *pos2 = reinterpret_cast<uint8_t *>(off2 + up4(4 * F0));     // [4][F0]       in the H2 x H2 conv-2 map
+    float *wc1 = reinterpret_cast<float *>(pos2 + up4(4 * F0));          // [150] + bias [6] (+ pad)
     float *wc2 = wc1 + 160;                        // [16][152]
     float *wc2b = wc2 + 16 * 152;                  // [16]
     float *w1s = wc2b + 16;                        // [30][F0P]
@@ -185,16 +189,15 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     float *h2 = h1 + 16 * kS1;                     // [16][kS2]
     float *dz = h2 + 16 * kS2;                     // [16][16]   d loss / d logits
     float *dh2 = dz + 256;                         // [16][kS2]
-    float *d2own = dh2 + 16 * kS2;                 // [16][24]   delta of the own units of dense 2
-    float *d1own = d2own + 16 * 24;                // [16][32]   ... of dense 1
-    float *dp2 = d1own + 16 * 32;                  // [4][F0]    delta at the pooled conv-2 outputs (own samples)
+    float *dp2 = dh2 + 16 * kS2;                   // [4][F0]    delta at the pooled conv-2 outputs (own samples)
     float *gsum = dp2 + up4(4 * F0);               // [2576]     filter-bank gradients over the own samples
     float *c1part = gsum + 2576;                   // [14][160]  conv-1 gradient, partial over window groups
     float *lossb = c1part + 14 * 160;              // [16]
     int *labs = reinterpret_cast<int *>(lossb + 16);   // [16]
     float *lossacc = reinterpret_cast<float *>(labs + 16);  // [4]
     // regions that are dead by the time these are needed
-    float *dc2 = a0;                               // [4][16][H2*H2]  delta at the conv-2 outputs (after the dense backward)
+    float *dc2 = a0;                               // [4][16][CS2]    delta at the conv-2 outputs, over a0 .. d1own (after the dense backward)
+    const int CS2 = H2 * H2 + 4;                   // its channel stride: the rows of consecutive channels start 4 banks apart
     float *dp1 = h1;                               // [4][P1S]        delta at the pooled conv-1 outputs
 
     u64 *rec = xrec + (int64_t)(rec0 + a) * kXWords;
@@ -290,7 +293,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 int which;
                 const float v = relu_pool(acc, which);
                 p1[s * P1S + c * nwin1 + py * P1 + px] = v;
-                idx1[(s * 6 + c) * nwin1 + py * P1 + px] = (uint8_t)which;
+                off1[(s * 6 + c) * nwin1 + py * P1 + px] = (uint16_t)((2 * py + (which >> 1)) * H0 + 2 * px + (which & 1));
             }
         }
         __syncthreads();
@@ -318,27 +321,28 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             const float v = relu_pool(acc, which);
             const int f = c * nwin2 + win;    // flattened C, H, W
             a0[(4 * g + s) * F0P + f] = v;
-            idx2[s * F0 + f] = (uint8_t)which;
+            off2[s * F0 + f] = (uint16_t)((2 * oy + (which >> 1)) * P1 + 2 * ox + (which & 1));
+            pos2[s * F0 + f] = (uint8_t)((2 * oy + (which >> 1)) * H2 + 2 * ox + (which & 1));
             xpost(rec + kXA1 + (4 * g + s) * 256 + f, wt.tag, v);
         }
         // the other workgroups' samples
-        for (int e0 = tq; e0 < 16 * F0; e0 += 4 * kLnThreads) {
-            const u64 *ptr[4];
-            bool need[4];
-            float val[4];
-            int dst[4];
+        for (int e0 = tq; e0 < 16 * F0; e0 += 8 * kLnThreads) {
+            const u64 *ptr[8];
+            bool need[8];
+            float val[8];
+            int dst[8];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 8; ++i) {
                 const int e = e0 + kLnThreads * i;
                 const bool in = e < 16 * F0;
-                const int b = in ? e / F0 : 0, f = in ? e % F0 : 0;
+                const int b = in ? e >> d.lgF0 : 0, f = in ? e & (F0 - 1) : 0;
                 need[i] = in && (b >> 2) != g;
                 ptr[i] = rec + kXA1 + b * 256 + f;
                 dst[i] = b * F0P + f;
             }
-            xfetch<4>(ptr, need, val, wt);
+            xfetch<8>(ptr, need, val, wt);
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+            for (int i = 0; i < 8; ++i)
                 if (need[i]) a0[dst[i]] = val[i];
         }
         __syncthreads();
@@ -347,15 +351,16 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         // ---- dense 1, own units: thread = (unit, sample) ----------------------------------------
         if (tq < kU1 * 16) {
             const int ul = tq >> 4, b = tq & 15;
-            float acc = b1s[ul];
+            // four partial sums (one per position in the 16-byte pieces), so that consecutive
+            // multiply-adds do not wait for each other
+            f4 part = {b1s[ul], 0.f, 0.f, 0.f};
             const float *wr = w1s + ul * F0P, *ar = a0 + b * F0P;
+#pragma unroll 4
             for (int k = 0; k < F0; k += 4) {
                 const f4 wv = *reinterpret_cast<const f4 *>(wr + k), av = *reinterpret_cast<const f4 *>(ar + k);
-                acc += wv[0] * av[0];
-                acc += wv[1] * av[1];
-                acc += wv[2] * av[2];
-                acc += wv[3] * av[3];
+                part += wv * av;
             }
+            const float acc = (part[0] + part[1]) + (part[2] + part[3]);
             const float h = acc > 0.f ? acc : 0.f;
             h1[b * kS1 + kU1 * g + ul] = h;
             xpost(rec + kXA2 + b * 128 + kU1 * g + ul, wt.tag, h);
@@ -385,15 +390,14 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         // ---- dense 2, own units ------------------------------------------------------------------
         if (tq < kU2 * 16) {
             const int ul = tq >> 4, b = tq & 15;
-            float acc = b2s[ul];
+            f4 part = {b2s[ul], 0.f, 0.f, 0.f};
             const float *wr = w2s + ul * kS1, *ar = h1 + b * kS1;
+#pragma unroll 5
             for (int k = 0; k < kF1; k += 4) {
                 const f4 wv = *reinterpret_cast<const f4 *>(wr + k), av = *reinterpret_cast<const f4 *>(ar + k);
-                acc += wv[0] * av[0];
-                acc += wv[1] * av[1];
-                acc += wv[2] * av[2];
-                acc += wv[3] * av[3];
+                part += wv * av;
             }
+            const float acc = (part[0] + part[1]) + (part[2] + part[3]);
             const float h = acc > 0.f ? acc : 0.f;
             h2[b * kS2 + kU2 * g + ul] = h;
             xpost(rec + kXA3 + b * 96 + kU2 * g + ul, wt.tag, h);
@@ -425,15 +429,14 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             const int b = tq >> 4, o = tq & 15;
             float z = 0.f;
             if (o < kNC) {
-                z = b3s[o];
+                f4 part = {b3s[o], 0.f, 0.f, 0.f};
                 const float *wr = w3s + o * kS2, *ar = h2 + b * kS2;
+#pragma unroll 7
                 for (int k = 0; k < kF2; k += 4) {
                     const f4 wv = *reinterpret_cast<const f4 *>(wr + k), av = *reinterpret_cast<const f4 *>(ar + k);
-                    z += wv[0] * av[0];
-                    z += wv[1] * av[1];
-                    z += wv[2] * av[2];
-                    z += wv[3] * av[3];
+                    part += wv * av;
                 }
+                z = (part[0] + part[1]) + (part[2] + part[3]);
             }
             const float zmax = row16_max_ln(o < kNC ? z : -3.0e38f);
             const float ex = o < kNC ? __expf(z - zmax) : 0.f;
@@ -537,59 +540,79 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 s += val[1];
                 s += val[2];
                 s += val[3];
-                d1own[b * 32 + ul] = h1[b * kS1 + k] > 0.f ? s : 0.f;
+                d1own[ul * 16 + b] = h1[b * kS1 + k] > 0.f ? s : 0.f;
             }
         }
         __syncthreads();
 
         tq = opaque(tq);
         // ---- backward through dense 1: partial d a0 over the own units -> exchange ---------------
-        for (int e0 = tq; e0 < 16 * F0; e0 += 8 * kLnThreads) {
-            float acc[8];
-            int bb[8], ff[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int e = e0 + kLnThreads * i;
-                const bool in = e < 16 * F0;
-                bb[i] = in ? e / F0 : 0;
-                ff[i] = in ? e % F0 : 0;
-                acc[i] = 0.f;
-            }
+        {
+            // thread = (column f of a0, group of NB consecutive samples), NB = 16 F0 / 512 (at least 1)
+            const int f = tq & (F0 - 1), grp = tq >> d.lgF0;
+            const int nb = F0 >= 32 ? (16 * F0) / kLnThreads : 1;       // 8, 2 or 1 samples per thread
+            if (nb == 8) {
+                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 2
-            for (int ul = 0; ul < kU1; ++ul) {
+                for (int ul = 0; ul < kU1; ++ul) {
+                    const float wv = w1s[ul * F0P + f];
+                    const f4 da = *reinterpret_cast<const f4 *>(d1own + ul * 16 + 8 * grp);
+                    const f4 db = *reinterpret_cast<const f4 *>(d1own + ul * 16 + 8 * grp + 4);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) acc[i] += d1own[bb[i] * 32 + ul] * w1s[ul * F0P + ff[i]];
+                    for (int i = 0; i < 4; ++i) {
+                        acc[i] += da[i] * wv;
+                        acc[4 + i] += db[i] * wv;
+                    }
+                }
+#pragma unroll
+                for (int i = 0; i < 8; ++i) xpost(rec + kXB2 + g * 4096 + (8 * grp + i) * 256 + f, wt.tag, acc[i]);
+            } else if (grp * nb < kLnB) {
+                for (int i = 0; i < nb; ++i) {
+                    const int b = grp * nb + i;
+                    float acc = 0.f;
+                    for (int ul = 0; ul < kU1; ++ul) acc += d1own[ul * 16 + b] * w1s[ul * F0P + f];
+                    xpost(rec + kXB2 + g * 4096 + b * 256 + f, wt.tag, acc);
+                }
             }
-#pragma unroll
-            for (int i = 0; i < 8; ++i)
-                if (e0 + kLnThreads * i < 16 * F0) xpost(rec + kXB2 + g * 4096 + bb[i] * 256 + ff[i], wt.tag, acc[i]);
         }
         // which of the own pooled conv-2 outputs are positive (a0 is overwritten below)
-        bool pos2[2];
+        bool alive2[2];
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int e = tq + kLnThreads * j;
-            pos2[j] = e < 4 * F0 && a0[(4 * g + e / F0) * F0P + e % F0] > 0.f;
+            alive2[j] = e < 4 * F0 && a0[(4 * g + e / F0) * F0P + e % F0] > 0.f;
         }
         __syncthreads();
-        // dense 1: w <- w - eta g, U <- U + g on the own rows
+        // dense 1: w <- w - eta g, U <- U + g on the own rows; the thread's entries share their
+        // column k, so its 16 inputs are read once
+        {
+            const int k = tq & (F0 - 1), ul0 = tq >> d.lgF0, ustep = kLnThreads >> d.lgF0;
+            float av[kLnB];
 #pragma unroll
-        for (int j = 0; j < 15; ++j) {
-            const int e = tq + kLnThreads * j;
-            if (e < kU1 * F0) {
-                const int ul = e / F0, k = e % F0;
-                float s = 0.f;
+            for (int b = 0; b < kLnB; ++b) av[b] = a0[b * F0P + k];
 #pragma unroll
-                for (int b = 0; b < kLnB; ++b) s += d1own[b * 32 + ul] * a0[b * F0P + k];
-                const float gv = s * invB;
-                w1s[ul * F0P + k] -= eta * gv;
-                U1[j] += gv;
+            for (int j = 0; j < 15; ++j) {
+                const int ul = ul0 + ustep * j;
+                if (ul < kU1) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const f4 dv = *reinterpret_cast<const f4 *>(d1own + ul * 16 + 4 * q);
+                        s += dv[0] * av[4 * q];
+                        s += dv[1] * av[4 * q + 1];
+                        s += dv[2] * av[4 * q + 2];
+                        s += dv[3] * av[4 * q + 3];
+                    }
+                    const float gv = s * invB;
+                    w1s[ul * F0P + k] -= eta * gv;
+                    U1[j] += gv;
+                }
             }
         }
         if (tq < kU1) {
             float s = 0.f;
 #pragma unroll
-            for (int b = 0; b < kLnB; ++b) s += d1own[b * 32 + tq];
+            for (int b = 0; b < kLnB; ++b) s += d1own[tq * 16 + b];
             const float gv = s * invB;
             b1s[tq] -= eta * gv;
             U1b += gv;
@@ -614,7 +637,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 t += val[1];
                 t += val[2];
                 t += val[3];
-                dp2[e] = pos2[j] ? t : 0.f;
+                dp2[e] = alive2[j] ? t : 0.f;
             }
         }
         __syncthreads();
@@ -622,75 +645,147 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         tq = opaque(tq);
         // ---- backward through conv 2 ---------------------------------------------------------------
         // delta at the conv-2 outputs: zero but at the winner of every window
-        for (int i = tq; i < 64 * H2 * H2; i += kLnThreads) dc2[i] = 0.f;
+        for (int i = tq; i < 64 * CS2; i += kLnThreads) dc2[i] = 0.f;
         __syncthreads();
         for (int e = tq; e < 4 * F0; e += kLnThreads) {
-            const int s = e / F0, f = e % F0, c = f / nwin2, win = f % nwin2;
-            const int k = idx2[e], y = 2 * (win / P2) + (k >> 1), x = 2 * (win % P2) + (k & 1);
-            dc2[((s * 16 + c) * H2 + y) * H2 + x] = dp2[e];
+            const int s = e >> d.lgF0, f = e & (F0 - 1), c = f / nwin2;
+            dc2[(s * 16 + c) * CS2 + pos2[e]] = dp2[e];
         }
         // filter gradient over the own samples: thread = (channel, input channel, filter row);
         // one position per window
         if (tq < 480) {
-            const int c = tq / 30, r = tq % 30, ci = r / 5, ky = r % 5;
+            // the channel varies fastest over the lanes: their rows start at the channels' own
+            // winner offsets and so fall into different LDS banks
+            const int c = tq & 15, r = tq >> 4, ci = r / 5, ky = r % 5;
             float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
-            for (int s = 0; s < 4; ++s)
-#pragma unroll 2
-                for (int win = 0; win < nwin2; ++win) {
-                    const int e = s * F0 + c * nwin2 + win;
-                    const float dl = dp2[e];
-                    const int k = idx2[e], y = 2 * (win / P2) + (k >> 1), x = 2 * (win % P2) + (k & 1);
-                    const float *row = p1 + s * P1S + ci * nwin1 + (y + ky) * P1 + x;
+            for (int s = 0; s < 4; ++s) {
+                const float *base = p1 + s * P1S + ci * nwin1 + ky * P1;
+                const int e0 = s * F0 + c * nwin2;
+#pragma unroll 1
+                for (int w0 = 0; w0 < nwin2; w0 += 8) {
+                    // the deltas and winner offsets of eight windows first, then their rows
+                    float dl[8], rv[8][5];
+                    int of[8];
 #pragma unroll
-                    for (int kx = 0; kx < 5; ++kx) acc[kx] += dl * row[kx];
+                    for (int i = 0; i < 8; ++i) {
+                        const int win = w0 + i < nwin2 ? w0 + i : nwin2 - 1;
+                        dl[i] = dp2[e0 + win];
+                        of[i] = off2[e0 + win];
+                    }
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+#pragma unroll
+                        for (int kx = 0; kx < 5; ++kx) rv[i][kx] = base[of[i] + kx];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        const float dv = w0 + i < nwin2 ? dl[i] : 0.f;
+#pragma unroll
+                        for (int kx = 0; kx < 5; ++kx) acc[kx] += dv * rv[i][kx];
+                    }
                 }
+            }
 #pragma unroll
             for (int kx = 0; kx < 5; ++kx) gsum[156 + c * 150 + ci * 25 + ky * 5 + kx] = acc[kx];
         } else if (tq < 496) {
             const int c = tq - 480;
             float s = 0.f;
-            for (int i = 0; i < 4; ++i)
-                for (int win = 0; win < nwin2; ++win) s += dp2[i * F0 + c * nwin2 + win];
+            if (nwin2 == 16) {
+                f4 v[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) v[i] = *reinterpret_cast<const f4 *>(dp2 + (i >> 2) * F0 + c * 16 + 4 * (i & 3));
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    s += v[i][0];
+                    s += v[i][1];
+                    s += v[i][2];
+                    s += v[i][3];
+                }
+            } else {
+                for (int i = 0; i < 4; ++i)
+                    for (int win = 0; win < nwin2; ++win) s += dp2[i * F0 + c * nwin2 + win];
+            }
             gsum[2556 + c] = s;
         }
         __syncthreads();
+        tq = opaque(tq);
         // delta at the pooled conv-1 outputs (dense correlation with the flipped filters), masked
-        // by the ReLU: item = (sample, input channel, row, half a row)
+        // by the ReLU.  A wave takes one output row yy and two input channels: lane = (channels c
+        // and c + 8, sample, input channel); the filter rows that reach row yy are the same
+        // for the whole wave (scalar loop bounds), whole delta rows are read without guards, and
+        // the eight channel groups of a lane octet are added in a fixed tree.
         {
-            const int XW = P1 >> 1;   // <= 6
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int cq = lane & 7, s = (lane >> 3) & 3, cil = lane >> 5;
 #pragma unroll 1
-            for (int it = tq; it < 48 * P1; it += kLnThreads) {
-                const int half = it & 1, r = it >> 1, yy = r % P1, ci = (r / P1) % 6, s = r / (6 * P1);
-                const int x0 = half * XW;
-                float acc[6] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int wi = wave; wi < 3 * P1; wi += kLnThreads / 64) {
+                const int yy = wi / 3, ci = 2 * (wi - 3 * yy) + cil;
                 const int ky_lo = yy - (H2 - 1) > 0 ? yy - (H2 - 1) : 0, ky_hi = yy < 4 ? yy : 4;
-#pragma unroll 1
-                for (int c = 0; c < 16; ++c) {
-#pragma unroll 1
-                    for (int ky = ky_lo; ky <= ky_hi; ++ky) {
-                        const float *row = dc2 + ((s * 16 + c) * H2 + (yy - ky)) * H2;
+                float acc[12];
+#pragma unroll
+                for (int x = 0; x < 12; ++x) acc[x] = 0.f;
+                // operands of one filter row: the delta rows of the lane's two channels and the
+                // five weights of each; the next row's operands are fetched before the products
+                // of the current one are issued
+                auto fetch = [&](int ky, float (&dv)[2][8], float (&wv)[2][5]) {
+#pragma unroll
+                    for (int cc = 0; cc < 2; ++cc) {
+                        const int c = cq + 8 * cc;
+                        const float *row = dc2 + (s * 16 + c) * CS2 + (yy - ky) * H2;
                         const float *wrow = wc2 + c * 152 + ci * 25 + ky * 5;
-                        float seg[10];   // delta at columns x0 - 4 .. x0 + 5
+                        if (H2 == 8) {
+                            const f4 lo = *reinterpret_cast<const f4 *>(row), hi = *reinterpret_cast<const f4 *>(row + 4);
 #pragma unroll
-                        for (int i = 0; i < 10; ++i) {
-                            const int x = x0 - 4 + i;
-                            seg[i] = (x >= 0 && x < H2) ? row[x] : 0.f;
+                            for (int x = 0; x < 4; ++x) { dv[cc][x] = lo[x]; dv[cc][4 + x] = hi[x]; }
+                        } else {
+                            // narrower maps: what lies beyond the row is read (it is inside the
+                            // buffer) and dropped
+#pragma unroll
+                            for (int x = 0; x < 8; ++x) {
+                                const float v = row[x];
+                                dv[cc][x] = x < H2 ? v : 0.f;
+                            }
                         }
 #pragma unroll
-                        for (int kx = 0; kx < 5; ++kx) {
-                            const float wgt = wrow[kx];
-#pragma unroll
-                            for (int xi = 0; xi < 6; ++xi) acc[xi] += seg[xi + 4 - kx] * wgt;
-                        }
+                        for (int kx = 0; kx < 5; ++kx) wv[cc][kx] = wrow[kx];
                     }
+                };
+                auto products = [&](const float (&dv)[2][8], const float (&wv)[2][5]) {
+#pragma unroll
+                    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                        for (int x = 0; x < 8; ++x)
+#pragma unroll
+                            for (int kx = 0; kx < 5; ++kx) acc[x + kx] += dv[cc][x] * wv[cc][kx];
+                };
+                float dva[2][8], wva[2][5], dvb[2][8], wvb[2][5];
+                fetch(ky_lo, dva, wva);
+                for (int ky = ky_lo;; ky += 2) {
+                    if (ky + 1 <= ky_hi) fetch(ky + 1, dvb, wvb);
+                    products(dva, wva);
+                    if (ky + 1 > ky_hi) break;
+                    if (ky + 2 <= ky_hi) fetch(ky + 2, dva, wva);
+                    products(dvb, wvb);
+                    if (ky + 2 > ky_hi) break;
                 }
+                // the eight channel pairs of a lane octet: neighbours, the other pair of the quad,
+                // the other quad (fixed order, the same in every run)
 #pragma unroll
-                for (int xi = 0; xi < 6; ++xi)
-                    if (xi < XW) {
-                        const int o = s * P1S + ci * nwin1 + yy * P1 + x0 + xi;
-                        dp1[o] = p1[o] > 0.f ? acc[xi] : 0.f;
-                    }
+                for (int x = 0; x < 12; ++x) {
+                    float t = acc[x];
+                    t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0xB1, 0xF, 0xF, true));
+                    t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x4E, 0xF, 0xF, true));
+                    t += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, t), 0x141, 0xF, 0xF, true));
+                    acc[x] = t;
+                }
+                if (cq == 0) {
+#pragma unroll
+                    for (int x = 0; x < 12; ++x)
+                        if (x < P1) {
+                            const int o = s * P1S + ci * nwin1 + yy * P1 + x;
+                            dp1[o] = p1[o] > 0.f ? acc[x] : 0.f;
+                        }
+                }
             }
         }
         __syncthreads();
@@ -703,22 +798,40 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             if (r < 30) {
                 const int c = r / 5, ky = r % 5;
                 float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-                for (int i = grp; i < 4 * nwin1; i += 14) {
-                    const int s = i / nwin1, win = i % nwin1;
-                    const float dl = dp1[s * P1S + c * nwin1 + win];
-                    const int k = idx1[(s * 6 + c) * nwin1 + win];
-                    const int y = 2 * (win / P1) + (k >> 1), x = 2 * (win % P1) + (k & 1);
-                    const float *row = xs + s * npix + (y + ky) * H0 + x;
+#pragma unroll 1
+                for (int s = 0; s < 4; ++s) {
+                    const float *dl_p = dp1 + s * P1S + c * nwin1;
+                    const uint16_t *of_p = off1 + (s * 6 + c) * nwin1;
+                    const float *base = xs + s * npix + ky * H0;
+#pragma unroll 1
+                    for (int w0 = grp; w0 < nwin1; w0 += 4 * 14) {
+                        float dl[4], rv[4][5];
+                        int of[4];
 #pragma unroll
-                    for (int kx = 0; kx < 5; ++kx) acc[kx] += dl * row[kx];
+                        for (int i = 0; i < 4; ++i) {
+                            const int win = w0 + 14 * i < nwin1 ? w0 + 14 * i : w0;
+                            dl[i] = dl_p[win];
+                            of[i] = of_p[win];
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+#pragma unroll
+                            for (int kx = 0; kx < 5; ++kx) rv[i][kx] = base[of[i] + kx];
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const float dv = w0 + 14 * i < nwin1 ? dl[i] : 0.f;
+#pragma unroll
+                            for (int kx = 0; kx < 5; ++kx) acc[kx] += dv * rv[i][kx];
+                        }
+                    }
                 }
 #pragma unroll
                 for (int kx = 0; kx < 5; ++kx) c1part[grp * 160 + c * 25 + ky * 5 + kx] = acc[kx];
             } else {
                 const int c = r - 30;
                 float s = 0.f;
-                for (int i = grp; i < 4 * nwin1; i += 14) s += dp1[(i / nwin1) * P1S + c * nwin1 + i % nwin1];
+                for (int i = 0; i < 4; ++i)
+                    for (int win = grp; win < nwin1; win += 14) s += dp1[i * P1S + c * nwin1 + win];
                 c1part[grp * 160 + 150 + c] = s;
             }
         }
@@ -741,41 +854,49 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             if (e < kConvP) xpost(rec + kXB3 + g * 2576 + e, wt.tag, gsum[e]);
         }
 #pragma unroll
-        for (int j = 0; j < 6; ++j) {
-            const int e = tq + kLnThreads * j;
-            const bool act = e < kConvP;
-            const u64 *ptr[4];
-            bool need[4];
-            float val[4];
+        for (int j0 = 0; j0 < 6; j0 += 3) {
+            const u64 *ptr[12];
+            bool need[12];
+            float val[12];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                ptr[i] = rec + kXB3 + i * 2576 + (act ? e : 0);
-                need[i] = act;
+            for (int jj = 0; jj < 3; ++jj) {
+                const int e = tq + kLnThreads * (j0 + jj);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    ptr[4 * jj + i] = rec + kXB3 + i * 2576 + (e < kConvP ? e : 0);
+                    need[4 * jj + i] = e < kConvP;
+                }
             }
-            xfetch<4>(ptr, need, val, wt);
-            if (act) {
-                float t = val[0];
-                t += val[1];
-                t += val[2];
-                t += val[3];
-                const float gv = t * invB;
-                float *w = e < 156 ? wc1 + e : e < 2556 ? wc2 + ((e - 156) / 150) * 152 + (e - 156) % 150 : wc2b + (e - 2556);
-                *w -= eta * gv;
-                UC[j] += gv;
+            xfetch<12>(ptr, need, val, wt);
+#pragma unroll
+            for (int jj = 0; jj < 3; ++jj) {
+                const int e = tq + kLnThreads * (j0 + jj);
+                if (e < kConvP) {
+                    float t = val[4 * jj];
+                    t += val[4 * jj + 1];
+                    t += val[4 * jj + 2];
+                    t += val[4 * jj + 3];
+                    const float gv = t * invB;
+                    float *w = e < 156 ? wc1 + e : e < 2556 ? wc2 + ((e - 156) / 150) * 152 + (e - 156) % 150 : wc2b + (e - 2556);
+                    *w -= eta * gv;
+                    UC[j0 + jj] += gv;
+                }
             }
         }
         __syncthreads();
     }
 
     // ---- end of round: the replica and the message payload go to HBM ------------------------------
+    {
+        const int k = tid & (F0 - 1), ul0 = tid >> d.lgF0, ustep = kLnThreads >> d.lgF0;
 #pragma unroll
-    for (int j = 0; j < 15; ++j) {
-        const int e = tid + kLnThreads * j;
-        if (e < kU1 * F0) {
-            const int ul = e / F0, k = e % F0;
-            const int64_t o = d.o_f1 + (int64_t)(kU1 * g + ul) * F0 + k;
-            Wc[o] = w1s[ul * F0P + k];
-            Uc[o] = U1[j];
+        for (int j = 0; j < 15; ++j) {
+            const int ul = ul0 + ustep * j;
+            if (ul < kU1) {
+                const int64_t o = d.o_f1 + (int64_t)(kU1 * g + ul) * F0 + k;
+                Wc[o] = w1s[ul * F0P + k];
+                Uc[o] = U1[j];
+            }
         }
     }
     if (tid < kU1) {
@@ -837,7 +958,9 @@ bool lenet_dims(const LayerGeom *lay, int L, int B, LenetDims *d) {
     if (f1.oc != kF1 || !f1.relu || f2.oc != kF2 || !f2.relu || f3.oc != kNC || f3.relu) return false;
     d->H0 = c1.ih; d->P1 = q1.oh; d->H2 = c2.oh; d->P2 = q2.oh;
     d->F0 = 16 * d->P2 * d->P2;
-    if (d->H0 > 32 || (d->H0 * d->H0) % 4 || d->P1 > 12 || (d->P1 & 1) || d->P2 < 1 || d->F0 > 256) return false;
+    if (d->H0 > 32 || (d->H0 * d->H0) % 4 || d->P1 > 12 || (d->P1 & 1) || d->H2 > 8) return false;
+    if (d->F0 != 16 && d->F0 != 64 && d->F0 != 256) return false;   // P2 = 1, 2 or 4
+    d->lgF0 = d->F0 == 16 ? 4 : d->F0 == 64 ? 6 : 8;
     if ((int64_t)d->F0 != f1.in_size) return false;
     d->o_f1 = f1.w_off; d->o_f2 = f2.w_off; d->o_f3 = f3.w_off;
     if (c1.w_off != 0 || c1.b_off != 150 || c2.w_off != 156 || c2.b_off != 2556 || f1.w_off != kConvP) return false;
@@ -848,7 +971,7 @@ size_t lenet_lds_bytes(const LenetDims &d) {
     auto up4 = [](int n) { return (n + 3) & ~3; };
     const int nwin1 = d.P1 * d.P1, P1S = 6 * nwin1 + 8, F0P = d.F0 + 4;
     size_t fl = up4(4 * d.H0 * d.H0) + 4 * P1S + 16 * F0P;
-    fl += (up4(4 * 6 * nwin1) + up4(4 * d.F0)) / 4;
+    fl += (2 * up4(4 * 6 * nwin1) + 2 * up4(4 * d.F0) + up4(4 * d.F0)) / 4;
     fl += 160 + 16 * 152 + 16 + kU1 * F0P + 32 + kU2 * kS1 + 32 + kNC * kS2 + 16;
     fl += 16 * kS1 + 16 * kS2 + 256 + 16 * kS2 + 16 * 24 + 16 * 32 + up4(4 * d.F0) + 2576 + 14 * 160 + 16 + 16 + 4;
     return fl * 4;
@@ -863,7 +986,7 @@ bool lenet_round_supported(const LayerGeom *lay, int L, int B) {
     if (!lenet_dims(lay, L, B, &d)) return false;
     // the regions that take turns in LDS must fit where they are put
     const int P1S = 6 * d.P1 * d.P1 + 8;
-    if (64 * d.H2 * d.H2 > 16 * (d.F0 + 4)) return false;                 // d conv-2 outputs over a0
+    if (64 * (d.H2 * d.H2 + 4) > 16 * (d.F0 + 4) + 16 * 24 + 16 * 32) return false;   // d conv-2 outputs over a0 .. d1own
     if (4 * P1S > 16 * kS1 + 16 * kS2 + 256 + 16 * kS2) return false;     // d pooled conv-1 outputs over h1 .. dh2
     return lenet_lds_bytes(d) <= 160 * 1024;
 }
