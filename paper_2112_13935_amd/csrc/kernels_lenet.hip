@@ -188,8 +188,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     float *h1 = b3s + 16;                          // [16][kS1]
     float *h2 = h1 + 16 * kS1;                     // [16][kS2]
     float *dz = h2 + 16 * kS2;                     // [16][16]   d loss / d logits
-    float *dh2 = dz + 256;                         // [16][kS2]
-    float *dp2 = dh2 + 16 * kS2;                   // [4][F0]    delta at the pooled conv-2 outputs (own samples)
+    float *dp2 = dz + 256 + 16 * kS2;              // (16 x kS2 floats of room in front: dp1 reaches into them)                   // [4][F0]    delta at the pooled conv-2 outputs (own samples)
     float *gsum = dp2 + up4(4 * F0);               // [2576]     filter-bank gradients over the own samples
     float *c1part = gsum + 2576;                   // [14][160]  conv-1 gradient, partial over window groups
     float *lossb = c1part + 14 * 160;              // [16]
@@ -299,14 +298,15 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         __syncthreads();
 
         tq = opaque(tq);
-        // ---- conv 2 + ReLU + pool: item = (sample, channel, window); a wave holds 16 windows x 4
-        // channels of one sample, so patch reads are broadcast over the channels ----------------
+        // ---- conv 2 + ReLU + pool: item = (sample, pair of channels, window); a wave holds 16
+        // windows x 4 channel pairs of one sample, so patch reads are broadcast over the pairs and
+        // every patch value feeds the products of two channels ------------------------------------
 #pragma unroll 1
-        for (int it = tq; it < 64 * nwin2; it += kLnThreads) {
-            const int c4 = it & 3, r = it >> 2, win = r % nwin2, cg = (r / nwin2) & 3, s = r / (4 * nwin2);
-            const int c = 4 * cg + c4, oy = win / P2, ox = win % P2;
-            const float b = wc2b[c];
-            float acc[4] = {b, b, b, b};
+        for (int it = tq; it < 32 * nwin2; it += kLnThreads) {
+            const int cp4 = it & 3, r = it >> 2, win = r % nwin2, ch = (r / nwin2) & 1, s = r / (2 * nwin2);
+            const int c = 2 * (4 * ch + cp4), oy = win / P2, ox = win % P2;
+            const float b0 = wc2b[c], b1 = wc2b[c + 1];
+            float acc0[4] = {b0, b0, b0, b0}, acc1[4] = {b1, b1, b1, b1};
 #pragma unroll 1
             for (int ci = 0; ci < 6; ++ci) {
                 float patch[6][6];
@@ -315,15 +315,19 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 for (int i = 0; i < 6; ++i)
 #pragma unroll
                     for (int j = 0; j < 6; ++j) patch[i][j] = pp[i * P1 + j];
-                conv_window(patch, wc2 + c * 152 + ci * 25, acc);
+                conv_window(patch, wc2 + c * 152 + ci * 25, acc0);
+                conv_window(patch, wc2 + (c + 1) * 152 + ci * 25, acc1);
             }
-            int which;
-            const float v = relu_pool(acc, which);
-            const int f = c * nwin2 + win;    // flattened C, H, W
-            a0[(4 * g + s) * F0P + f] = v;
-            off2[s * F0 + f] = (uint16_t)((2 * oy + (which >> 1)) * P1 + 2 * ox + (which & 1));
-            pos2[s * F0 + f] = (uint8_t)((2 * oy + (which >> 1)) * H2 + 2 * ox + (which & 1));
-            xpost(rec + kXA1 + (4 * g + s) * 256 + f, wt.tag, v);
+#pragma unroll
+            for (int cc = 0; cc < 2; ++cc) {
+                int which;
+                const float v = cc == 0 ? relu_pool(acc0, which) : relu_pool(acc1, which);
+                const int f = (c + cc) * nwin2 + win;    // flattened C, H, W
+                a0[(4 * g + s) * F0P + f] = v;
+                off2[s * F0 + f] = (uint16_t)((2 * oy + (which >> 1)) * P1 + 2 * ox + (which & 1));
+                pos2[s * F0 + f] = (uint8_t)((2 * oy + (which >> 1)) * H2 + 2 * ox + (which & 1));
+                xpost(rec + kXA1 + (4 * g + s) * 256 + f, wt.tag, v);
+            }
         }
         // the other workgroups' samples
         for (int e0 = tq; e0 < 16 * F0; e0 += 8 * kLnThreads) {
@@ -448,22 +452,32 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         __syncthreads();
 
         tq = opaque(tq);
-        // ---- backward through dense 3: d h2 (reads the not yet updated weights) ------------------
-        for (int e = tq; e < 16 * kF2; e += kLnThreads) {
-            const int b = e / kF2, k = e % kF2;
+        // ---- backward through dense 3: only the own units of dense 2 need their delta (reads the
+        // not yet updated weights of dense 3) -----------------------------------------------------
+        if (tq < kU2 * 16) {
+            const int ul = tq >> 4, b = tq & 15, k = kU2 * g + ul;
             float acc = 0.f;
 #pragma unroll
             for (int o = 0; o < kNC; ++o) acc += dz[b * 16 + o] * w3s[o * kS2 + k];
-            dh2[b * kS2 + k] = acc;
+            d2own[b * 24 + ul] = h2[b * kS2 + k] > 0.f ? acc : 0.f;
         }
-        if (g == 0 && tq == 0) {
+        if (g == 0 && tq == 511) {
             float s = 0.f;
             for (int b = 0; b < kLnB; ++b) s += lossb[b];
             lossacc[0] += s * invB;
         }
         __syncthreads();
-        // dense 3: w <- w - eta g, U <- U + g (the same in every workgroup); delta of the own
-        // units of dense 2
+
+        tq = opaque(tq);
+        // ---- backward through dense 2: partial d h1 over the own units -> exchange ---------------
+        for (int e = tq; e < 16 * kF1; e += kLnThreads) {
+            const int b = e / kF1, k = e % kF1;
+            float acc = 0.f;
+#pragma unroll
+            for (int ul = 0; ul < kU2; ++ul) acc += d2own[b * 24 + ul] * w2s[ul * kS1 + k];
+            xpost(rec + kXB1 + g * 2048 + b * 128 + k, wt.tag, acc);
+        }
+        // dense 3: w <- w - eta g, U <- U + g (the same in every workgroup)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int e = tq + kLnThreads * j;
@@ -484,21 +498,6 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             const float gv = s * invB;
             b3s[tq] -= eta * gv;
             U3b += gv;
-        }
-        if (tq < kU2 * 16) {
-            const int ul = tq >> 4, b = tq & 15, k = kU2 * g + ul;
-            d2own[b * 24 + ul] = h2[b * kS2 + k] > 0.f ? dh2[b * kS2 + k] : 0.f;
-        }
-        __syncthreads();
-
-        tq = opaque(tq);
-        // ---- backward through dense 2: partial d h1 over the own units -> exchange ---------------
-        for (int e = tq; e < 16 * kF1; e += kLnThreads) {
-            const int b = e / kF1, k = e % kF1;
-            float acc = 0.f;
-#pragma unroll
-            for (int ul = 0; ul < kU2; ++ul) acc += d2own[b * 24 + ul] * w2s[ul * kS1 + k];
-            xpost(rec + kXB1 + g * 2048 + b * 128 + k, wt.tag, acc);
         }
         __syncthreads();
 #pragma unroll
@@ -709,6 +708,13 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         }
         __syncthreads();
         tq = opaque(tq);
+        // the conv-2 part of the filter gradient is complete: post it now, it travels while the
+        // rest of the backward pass runs
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const int e = 156 + tq + kLnThreads * j;
+            if (e < kConvP) xpost(rec + kXB3 + g * 2576 + e, wt.tag, gsum[e]);
+        }
         // delta at the pooled conv-1 outputs (dense correlation with the flipped filters), masked
         // by the ReLU.  A wave takes one output row yy and two input channels: lane = (channels c
         // and c + 8, sample, input channel); the filter rows that reach row yy are the same
@@ -836,23 +842,15 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             }
         }
         __syncthreads();
-        if (tq < 156) {
+        // ---- filter banks: exchange the partial gradients, add them in workgroup order, update ----
+        if (tq < 156) {   // the conv-1 part: the thread that adds the window groups posts the sum
             float s = 0.f;
 #pragma unroll
             for (int grp = 0; grp < 14; ++grp) s += c1part[grp * 160 + tq];
-            gsum[tq] = s;
+            xpost(rec + kXB3 + g * 2576 + tq, wt.tag, s);
         }
         // the next recursion's rows and labels (xs and labs are not read any more)
         if (more) store_rows(xr, labr);
-        __syncthreads();
-
-        tq = opaque(tq);
-        // ---- filter banks: exchange the partial gradients, add them in workgroup order, update ----
-#pragma unroll
-        for (int j = 0; j < 6; ++j) {
-            const int e = tq + kLnThreads * j;
-            if (e < kConvP) xpost(rec + kXB3 + g * 2576 + e, wt.tag, gsum[e]);
-        }
 #pragma unroll
         for (int j0 = 0; j0 < 6; j0 += 3) {
             const u64 *ptr[12];
