@@ -121,12 +121,18 @@ __device__ __forceinline__ void xfetch(const u64 *(&p)[N], const bool (&need)[N]
 }
 
 // 5 x 5 convolution at the four positions of a 2 x 2 window from a 6 x 6 patch, added to acc
+// (the 25 weights are fetched together: fetched one by one next to their products, every
+// fetch would wait out its own LDS round trip)
 __device__ __forceinline__ void conv_window(const float (&patch)[6][6], const float *__restrict__ wv, float (&acc)[4]) {
+    float w[25];
+#pragma unroll
+    for (int i = 0; i < 25; ++i) w[i] = wv[i];
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ky = 0; ky < 5; ++ky)
 #pragma unroll
         for (int kx = 0; kx < 5; ++kx) {
-            const float wgt = wv[ky * 5 + kx];
+            const float wgt = w[ky * 5 + kx];
             acc[0] += wgt * patch[ky][kx];
             acc[1] += wgt * patch[ky][kx + 1];
             acc[2] += wgt * patch[ky + 1][kx];
@@ -676,6 +682,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                     for (int i = 0; i < 8; ++i)
 #pragma unroll
                         for (int kx = 0; kx < 5; ++kx) rv[i][kx] = base[of[i] + kx];
+                    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                     for (int i = 0; i < 8; ++i) {
                         const float dv = w0 + i < nwin2 ? dl[i] : 0.f;
@@ -768,9 +775,11 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 fetch(ky_lo, dva, wva);
                 for (int ky = ky_lo;; ky += 2) {
                     if (ky + 1 <= ky_hi) fetch(ky + 1, dvb, wvb);
+                    __builtin_amdgcn_sched_barrier(0);
                     products(dva, wva);
                     if (ky + 1 > ky_hi) break;
                     if (ky + 2 <= ky_hi) fetch(ky + 2, dva, wva);
+                    __builtin_amdgcn_sched_barrier(0);
                     products(dvb, wvb);
                     if (ky + 2 > ky_hi) break;
                 }
@@ -823,6 +832,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                         for (int i = 0; i < 4; ++i)
 #pragma unroll
                             for (int kx = 0; kx < 5; ++kx) rv[i][kx] = base[of[i] + kx];
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const float dv = w0 + 14 * i < nwin1 ? dl[i] : 0.f;
