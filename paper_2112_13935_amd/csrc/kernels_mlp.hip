@@ -104,9 +104,8 @@ __device__ __forceinline__ float col_sum16(const float *a, int lane) {
 }
 
 // FAST: D is a multiple of 16, so every row piece is one aligned 16-byte load.
-// NBT: batch tiles of 16 samples; TPW: K tiles every wave steps through (waves that own
-// fewer real tiles run the remaining ones as no-ops on zero weights, so that the tile loops
-// are free of branches and the compiler can keep the matrix pipeline full).
+// NBT: batch tiles of 16 samples; TPW: K-tile slots of a wave (a wave that owns fewer tiles
+// skips the rest with scalar branches).
 // The round records of one launch travel in the kernel arguments: no staging copy, no
 // buffer whose reuse would have to be fenced with events.
 constexpr int kMlpPack = 48;
@@ -148,12 +147,15 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
     const int KT = min(KH, KTall - tbase);
     constexpr int ld = 16 * kMlpWaves * TPW + 4;  // LDS row stride: all tiles + 4 floats of skew
     constexpr int NI = NBT * TPW;             // float4 loads per lane and mini-batch
-    // wave w steps through tiles [TPW*w, TPW*w + TPW); the first nt of them are real, the
-    // rest are loaded as zeros and meet zero weights
-    const int t0 = TPW * wave;
-    const int nt = min(max(KT - t0, 0), TPW);
-    const int col0 = 16 * t0;                 // first column of the wave in the staged rows
-    const int gcol0 = 16 * (tbase + t0);      // ... and in the sample / weight rows
+    // the KT tiles are dealt out evenly: wave w owns nt consecutive tiles from t0 on, the
+    // first KT % 8 waves one more than the others (waves w and w + 4 share a SIMD and its
+    // matrix core: dealt this way the four SIMDs differ by one tile at most).  A wave has
+    // TPW tile slots in registers and in the staged rows; slots beyond nt are skipped.
+    const int tb = KT / kMlpWaves, te = KT % kMlpWaves;
+    const int nt = tb + (wave < te ? 1 : 0);
+    const int t0 = wave * tb + min(wave, te);
+    const int col0 = 16 * TPW * wave;         // first column of the wave's slots in the staged rows
+    const int gcol0 = 16 * (tbase + t0);      // first own column in the sample / weight rows
 
     extern __shared__ float smem[];
     // the small arrays come first so that their addresses fit the 16-bit offset field of
@@ -262,7 +264,8 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         for (int bt = 0; bt < NBT; ++bt)
 #pragma unroll
             for (int tt = 0; tt < TPW; ++tt)
-                *reinterpret_cast<f4 *>(Xs + (16 * bt + li) * ld + col0 + 16 * tt + 4 * lg) = xreg[bt][tt];
+                if (FULL || tt < nt)
+                    *reinterpret_cast<f4 *>(Xs + (16 * bt + li) * ld + col0 + 16 * tt + 4 * lg) = xreg[bt][tt];
     };
     for (int u = 0; u < p.m; ++u) {
         // ---- z1 partial sums on the matrix cores ----------------------------------------
@@ -271,6 +274,8 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
 #pragma unroll
             for (int bt = 0; bt < NBT; ++bt) acc[bt] = f4{0.f, 0.f, 0.f, 0.f};
             // the A operand comes straight from the registers the rows were loaded into
+            // (all TPW slots, free of branches: an empty slot holds zeros on both sides; skipping
+            // it measured slower here, while the backward product below gains from skipping)
 #pragma unroll
             for (int tt = 0; tt < TPW; ++tt) {
 #pragma unroll
@@ -383,16 +388,20 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
         };
         // ---- logits, softmax, d logits: thread (b, o) = (tid / 16, tid % 16) ------------
         // Every thread with o < C fetches its own logit: the G tagged words of element
-        // (b, o).  To keep the memory system quiet while the peers are still computing,
-        // a wave first watches one word per record and batch tile (the last one its owner
-        // stores) and fetches the elements only when those show the current tag; the
-        // element tags are still checked, and the fetch repeated if one is stale.
+        // (b, o).  Polling loads slow the peers' stores down (they meet in the same memory
+        // channels: a variant in which every thread polls its own words ran a quarter slower), so
+        // while the peers are still computing only wave 0 looks, and only at one word per
+        // record and batch tile (the last one its owner stores); the other waves wait at a
+        // workgroup barrier.  The elements are fetched when those words show the current tag;
+        // the element tags are still checked, and the fetch repeated if one is stale.  (A
+        // separate flag word per poster, stored after the logits, overtakes them on the way
+        // and makes the fetch fail: the watched word has to be one of the data words.)
         {
             const int b = tid >> 4, o = tid & 15;
             const bool mine = b < B && o < C;
             float z = 0.f;
             int spins = 0;
-            {
+            if (wave == 0) {
                 // lane -> (record, batch tile); the word of sample 16*bt+15, class C-1
                 const int gg = lane % G, bt = lane / G;
                 const bool watch = bt < NBT;
@@ -410,6 +419,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
                     }
                 }
             }
+            __syncthreads();
             if (mine) {
                 const unsigned long long *src = rec + b * C + o;
                 constexpr int GC = 8;  // records fetched per batch of loads
@@ -519,31 +529,33 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
             for (int s = 0; s < 4 * NBT; ++s) dhb[s] = dhs[(16 * (s >> 2) + (s & 3) + 4 * lg) * 16 + li];
             float xb[2][4 * NBT];
             const float *xcol = Xs + opaque(4 * lg * ld + col0 + li);
+            if (FULL || nt > 0) {
 #pragma unroll
-            for (int s = 0; s < 4 * NBT; ++s) xb[0][s] = xcol[(16 * (s >> 2) + (s & 3)) * ld];
+                for (int s = 0; s < 4 * NBT; ++s) xb[0][s] = xcol[(16 * (s >> 2) + (s & 3)) * ld];
+            }
             const float eb = p.eta * invB;
 #pragma unroll
             for (int tt = 0; tt < TPW; ++tt) {
-                if (tt + 1 < TPW) {
+                if (tt + 1 < TPW && (FULL || tt + 1 < nt)) {
 #pragma unroll
                     for (int s = 0; s < 4 * NBT; ++s) xb[(tt + 1) & 1][s] = xcol[(16 * (s >> 2) + (s & 3)) * ld + 16 * (tt + 1)];
                 }
-                // two independent accumulation chains per tile
-                // (the first product of each chain takes the constant zero as its addend)
-                f4 acc0 = mfma16(xb[tt & 1][0], dhb[0], f4{0.f, 0.f, 0.f, 0.f});
-                f4 acc1 = mfma16(xb[tt & 1][1], dhb[1], f4{0.f, 0.f, 0.f, 0.f});
+                if (FULL || tt < nt) {
+                    // two independent accumulation chains per tile
+                    // (the first product of each chain takes the constant zero as its addend)
+                    f4 acc0 = mfma16(xb[tt & 1][0], dhb[0], f4{0.f, 0.f, 0.f, 0.f});
+                    f4 acc1 = mfma16(xb[tt & 1][1], dhb[1], f4{0.f, 0.f, 0.f, 0.f});
 #pragma unroll
-                for (int s = 2; s < 4 * NBT; s += 2) {
-                    acc0 = mfma16(xb[tt & 1][s], dhb[s], acc0);
-                    acc1 = mfma16(xb[tt & 1][s + 1], dhb[s + 1], acc1);
-                }
-                // (pad tiles: their rows are zeros, so the product is zero and the zero
-                // weights stay zero)
+                    for (int s = 2; s < 4 * NBT; s += 2) {
+                        acc0 = mfma16(xb[tt & 1][s], dhb[s], acc0);
+                        acc1 = mfma16(xb[tt & 1][s + 1], dhb[s + 1], acc1);
+                    }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const float gsum = acc0[r] + acc1[r];
-                    W1r[tt][r] -= eb * gsum;
-                    U1r[tt][r] += invB * gsum;
+                    for (int r = 0; r < 4; ++r) {
+                        const float gsum = acc0[r] + acc1[r];
+                        W1r[tt][r] -= eb * gsum;
+                        U1r[tt][r] += invB * gsum;
+                    }
                 }
                 // this tile's share of the next recursion's row loads
 #pragma unroll
