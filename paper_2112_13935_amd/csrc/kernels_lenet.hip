@@ -304,35 +304,105 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         __syncthreads();
 
         tq = opaque(tq);
-        // ---- conv 2 + ReLU + pool: item = (sample, pair of channels, window); a wave holds 16
-        // windows x 4 channel pairs of one sample, so patch reads are broadcast over the pairs and
-        // every patch value feeds the products of two channels ------------------------------------
+        // ---- conv 2 + ReLU + pool on the matrix cores ------------------------------------------
+        // out[c][pos] = sum_k w[c][k] patch[k][pos] as 16 x 16 x 4 products: the rows are the 16
+        // channels, the columns 16 output positions (four pooling windows, the four positions
+        // of a window in neighbouring lanes), the contraction runs over the 150 (ci, ky, kx)
+        // in an order that keeps every operand address "lane constant + step constant":
+        //   30 steps (ci, ky) with kx = 0..3 over the four lane groups,
+        //    6 steps (ci)     with kx = 4 and ky = 0..3 over the lane groups,
+        //    2 steps          with ky = kx = 4 and ci = 0..3 / 4, 5 (two idle groups) over them.
+        // A wave takes two tiles at a time (two independent accumulators, one read of the
+        // weights); the pooled value and the winner are found with quad permutations.
+        {
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4;
+            const int npos = H2 * H2, ntile = npos >> 2;      // tiles of 16 positions over the 4 own samples
+            const float *wa1 = wc2 + n * 152 + kq;
+            const float *wa2 = wc2 + n * 152 + 5 * kq + 4;
+            const float *wa3 = wc2 + n * 152 + 25 * kq + 24;
+            const float *wa4 = wc2 + n * 152 + 25 * (4 + (kq & 1)) + 24;
+            const bool last2 = kq < 2;
 #pragma unroll 1
-        for (int it = tq; it < 32 * nwin2; it += kLnThreads) {
-            const int cp4 = it & 3, r = it >> 2, win = r % nwin2, ch = (r / nwin2) & 1, s = r / (2 * nwin2);
-            const int c = 2 * (4 * ch + cp4), oy = win / P2, ox = win % P2;
-            const float b0 = wc2b[c], b1 = wc2b[c + 1];
-            float acc0[4] = {b0, b0, b0, b0}, acc1[4] = {b1, b1, b1, b1};
+            for (int t0 = wave; t0 < ntile; t0 += 2 * (kLnThreads / 64)) {
+                const int t1 = t0 + kLnThreads / 64;
+                const bool two = t1 < ntile;
+                const float *pb[2];
+                int sj[2], winj[2], qj[2];
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int j = ((h == 0 || two) ? (h == 0 ? t0 : t1) : t0) * 16 + n;
+                    const int sl = j / npos, jj = j - sl * npos, win = jj >> 2, q = jj & 3;
+                    const int oy = win / P2, ox = win - oy * P2;
+                    sj[h] = sl; winj[h] = win; qj[h] = q;
+                    pb[h] = p1 + sl * P1S + (2 * oy + (q >> 1)) * P1 + 2 * ox + (q & 1);
+                }
+                f4 acc[2] = {f4{0.f, 0.f, 0.f, 0.f}, f4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll 1
-            for (int ci = 0; ci < 6; ++ci) {
-                float patch[6][6];
-                const float *pp = p1 + s * P1S + ci * nwin1 + (2 * oy) * P1 + 2 * ox;
+                for (int ci = 0; ci < 6; ++ci) {
+                    float wv[6], bv[2][6];
 #pragma unroll
-                for (int i = 0; i < 6; ++i)
+                    for (int ky = 0; ky < 5; ++ky) wv[ky] = wa1[ci * 25 + ky * 5];
+                    wv[5] = wa2[ci * 25];
 #pragma unroll
-                    for (int j = 0; j < 6; ++j) patch[i][j] = pp[i * P1 + j];
-                conv_window(patch, wc2 + c * 152 + ci * 25, acc0);
-                conv_window(patch, wc2 + (c + 1) * 152 + ci * 25, acc1);
-            }
+                    for (int h = 0; h < 2; ++h) {
+                        const float *q1 = pb[h] + ci * nwin1 + kq;
 #pragma unroll
-            for (int cc = 0; cc < 2; ++cc) {
-                int which;
-                const float v = cc == 0 ? relu_pool(acc0, which) : relu_pool(acc1, which);
-                const int f = (c + cc) * nwin2 + win;    // flattened C, H, W
-                a0[(4 * g + s) * F0P + f] = v;
-                off2[s * F0 + f] = (uint16_t)((2 * oy + (which >> 1)) * P1 + 2 * ox + (which & 1));
-                pos2[s * F0 + f] = (uint8_t)((2 * oy + (which >> 1)) * H2 + 2 * ox + (which & 1));
-                xpost(rec + kXA1 + (4 * g + s) * 256 + f, wt.tag, v);
+                        for (int ky = 0; ky < 5; ++ky) bv[h][ky] = q1[ky * P1];
+                        bv[h][5] = pb[h][ci * nwin1 + kq * P1 + 4];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int ky = 0; ky < 6; ++ky)
+#pragma unroll
+                        for (int h = 0; h < 2; ++h)
+                            acc[h] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[ky], bv[h][ky], acc[h], 0, 0, 0);
+                }
+                {
+                    const float w3 = wa3[0], w4r = wa4[0], w4 = last2 ? w4r : 0.f;
+                    float b3[2], b4[2];
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        b3[h] = pb[h][kq * nwin1 + 4 * P1 + 4];
+                        b4[h] = pb[h][(4 + (kq & 1)) * nwin1 + 4 * P1 + 4];
+                    }
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        acc[h] = __builtin_amdgcn_mfma_f32_16x16x4f32(w3, b3[h], acc[h], 0, 0, 0);
+                        acc[h] = __builtin_amdgcn_mfma_f32_16x16x4f32(w4, b4[h], acc[h], 0, 0, 0);
+                    }
+                }
+                // lane: position n of the tile, channels 4 kq .. 4 kq + 3.  ReLU, then the first
+                // maximum of the window in row-major order; the four lanes of a window share the
+                // four stores
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    if (h == 1 && !two) break;
+                    const int sl = sj[h], win = winj[h], q = qj[h];
+                    const int oy = win / P2, ox = win - oy * P2;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int c = 4 * kq + r;
+                        float v = acc[h][r] + wc2b[c];
+                        v = v > 0.f ? v : 0.f;
+                        const int vi = __builtin_bit_cast(int, v);
+                        const float v0 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, vi, 0x00, 0xF, 0xF, true));
+                        const float v1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, vi, 0x55, 0xF, 0xF, true));
+                        const float v2 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, vi, 0xAA, 0xF, 0xF, true));
+                        const float v3 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, vi, 0xFF, 0xF, 0xF, true));
+                        float best = v0;
+                        int which = 0;
+                        if (v1 > best) { best = v1; which = 1; }
+                        if (v2 > best) { best = v2; which = 2; }
+                        if (v3 > best) { best = v3; which = 3; }
+                        const int f = c * nwin2 + win;    // flattened C, H, W
+                        const int wy = 2 * oy + (which >> 1), wx = 2 * ox + (which & 1);
+                        if (q == 0) a0[(4 * g + sl) * F0P + f] = best;
+                        else if (q == 1) off2[sl * F0 + f] = (uint16_t)(wy * P1 + wx);
+                        else if (q == 2) pos2[sl * F0 + f] = (uint8_t)(wy * H2 + wx);
+                        else xpost(rec + kXA1 + (4 * g + sl) * 256 + f, wt.tag, best);
+                    }
+                }
             }
         }
         // the other workgroups' samples
