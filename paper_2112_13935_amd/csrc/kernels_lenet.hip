@@ -313,7 +313,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         //    6 steps (ci)     with kx = 4 and ky = 0..3 over the lane groups,
         //    2 steps          with ky = kx = 4 and ci = 0..3 / 4, 5 (two idle groups) over them.
         // A wave takes two tiles at a time (two independent accumulators, one read of the
-        // weights); the pooled value and the winner are found with quad permutations.
+        // weights).
         {
             const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
             const int n = lane & 15, kq = lane >> 4;
@@ -338,9 +338,10 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                     pb[h] = p1 + sl * P1S + (2 * oy + (q >> 1)) * P1 + 2 * ox + (q & 1);
                 }
                 f4 acc[2] = {f4{0.f, 0.f, 0.f, 0.f}, f4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll 1
-                for (int ci = 0; ci < 6; ++ci) {
-                    float wv[6], bv[2][6];
+                // operands of the six steps of one input channel (five filter rows with kx < 4,
+                // then kx = 4); the next channel's are fetched before the products of the
+                // current one are issued
+                auto fetch = [&](int ci, float (&wv)[6], float (&bv)[2][6]) {
 #pragma unroll
                     for (int ky = 0; ky < 5; ++ky) wv[ky] = wa1[ci * 25 + ky * 5];
                     wv[5] = wa2[ci * 25];
@@ -351,12 +352,26 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                         for (int ky = 0; ky < 5; ++ky) bv[h][ky] = q1[ky * P1];
                         bv[h][5] = pb[h][ci * nwin1 + kq * P1 + 4];
                     }
-                    __builtin_amdgcn_sched_barrier(0);
+                };
+                auto products = [&](const float (&wv)[6], const float (&bv)[2][6]) {
 #pragma unroll
                     for (int ky = 0; ky < 6; ++ky)
 #pragma unroll
                         for (int h = 0; h < 2; ++h)
                             acc[h] = __builtin_amdgcn_mfma_f32_16x16x4f32(wv[ky], bv[h][ky], acc[h], 0, 0, 0);
+                };
+                float wva[6], bva[2][6], wvb[6], bvb[2][6];
+                fetch(0, wva, bva);
+#pragma unroll 1
+                for (int ci = 0; ci < 6; ci += 2) {
+                    fetch(ci + 1, wvb, bvb);
+                    __builtin_amdgcn_sched_barrier(0);
+                    products(wva, bva);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (ci + 2 < 6) fetch(ci + 2, wva, bva);
+                    __builtin_amdgcn_sched_barrier(0);
+                    products(wvb, bvb);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
                 {
                     const float w3 = wa3[0], w4r = wa4[0], w4 = last2 ? w4r : 0.f;
@@ -372,36 +387,51 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                         acc[h] = __builtin_amdgcn_mfma_f32_16x16x4f32(w4, b4[h], acc[h], 0, 0, 0);
                     }
                 }
-                // lane: position n of the tile, channels 4 kq .. 4 kq + 3.  ReLU, then the first
-                // maximum of the window in row-major order; the four lanes of a window share the
-                // four stores
+                // A lane holds position n of the tile for channels 4 kq .. 4 kq + 3.  The four lanes
+                // of a window transpose their 4 x 4 values (two exchange steps), after which lane q
+                // of the window holds the four positions of channel 4 kq + q: bias, ReLU, the first
+                // maximum in row-major order, and the four stores of that output.
+                const float bias = wc2b[4 * kq + (n & 3)];
 #pragma unroll
                 for (int h = 0; h < 2; ++h) {
                     if (h == 1 && !two) break;
                     const int sl = sj[h], win = winj[h], q = qj[h];
                     const int oy = win / P2, ox = win - oy * P2;
+                    float t[4] = {acc[h][0], acc[h][1], acc[h][2], acc[h][3]};
+                    {   // exchange with lane q ^ 1 inside the register pairs (0, 1) and (2, 3)
+                        const bool odd = q & 1;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        const int c = 4 * kq + r;
-                        float v = acc[h][r] + wc2b[c];
-                        v = v > 0.f ? v : 0.f;
-                        const int vi = __builtin_bit_cast(int, v);
-                        const float v0 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, vi, 0x00, 0xF, 0xF, true));
-                        const float v1 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, vi, 0x55, 0xF, 0xF, true));
-                        const float v2 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, vi, 0xAA, 0xF, 0xF, true));
-                        const float v3 = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, vi, 0xFF, 0xF, 0xF, true));
-                        float best = v0;
-                        int which = 0;
-                        if (v1 > best) { best = v1; which = 1; }
-                        if (v2 > best) { best = v2; which = 2; }
-                        if (v3 > best) { best = v3; which = 3; }
-                        const int f = c * nwin2 + win;    // flattened C, H, W
-                        const int wy = 2 * oy + (which >> 1), wx = 2 * ox + (which & 1);
-                        if (q == 0) a0[(4 * g + sl) * F0P + f] = best;
-                        else if (q == 1) off2[sl * F0 + f] = (uint16_t)(wy * P1 + wx);
-                        else if (q == 2) pos2[sl * F0 + f] = (uint8_t)(wy * H2 + wx);
-                        else xpost(rec + kXA1 + (4 * g + sl) * 256 + f, wt.tag, best);
+                        for (int a2 = 0; a2 < 4; a2 += 2) {
+                            const float send = odd ? t[a2] : t[a2 + 1];
+                            const float got = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0xB1, 0xF, 0xF, true));
+                            if (odd) t[a2] = got; else t[a2 + 1] = got;
+                        }
                     }
+                    {   // exchange with lane q ^ 2 inside the register pairs (0, 2) and (1, 3)
+                        const bool up = q & 2;
+#pragma unroll
+                        for (int a2 = 0; a2 < 2; ++a2) {
+                            const float send = up ? t[a2] : t[a2 + 2];
+                            const float got = __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, send), 0x4E, 0xF, 0xF, true));
+                            if (up) t[a2] = got; else t[a2 + 2] = got;
+                        }
+                    }
+                    float best = t[0] + bias;
+                    best = best > 0.f ? best : 0.f;
+                    int which = 0;
+#pragma unroll
+                    for (int k = 1; k < 4; ++k) {
+                        float v = t[k] + bias;
+                        v = v > 0.f ? v : 0.f;
+                        if (v > best) { best = v; which = k; }
+                    }
+                    const int c = 4 * kq + q;
+                    const int f = c * nwin2 + win;    // flattened C, H, W
+                    const int wy = 2 * oy + (which >> 1), wx = 2 * ox + (which & 1);
+                    a0[(4 * g + sl) * F0P + f] = best;
+                    off2[sl * F0 + f] = (uint16_t)(wy * P1 + wx);
+                    pos2[sl * F0 + f] = (uint8_t)(wy * H2 + wx);
+                    xpost(rec + kXA1 + (4 * g + sl) * 256 + f, wt.tag, best);
                 }
             }
         }
