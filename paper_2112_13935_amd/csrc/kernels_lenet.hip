@@ -756,44 +756,67 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             const int s = e >> d.lgF0, f = e & (F0 - 1), c = f / nwin2;
             dc2[(s * 16 + c) * CS2 + pos2[e]] = dp2[e];
         }
-        // filter gradient over the own samples: thread = (channel, input channel, filter row);
-        // one position per window
-        if (tq < 480) {
-            // the channel varies fastest over the lanes: their rows start at the channels' own
-            // winner offsets and so fall into different LDS banks
-            const int c = tq & 15, r = tq >> 4, ci = r / 5, ky = r % 5;
-            float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-            for (int s = 0; s < 4; ++s) {
-                const float *base = p1 + s * P1S + ci * nwin1 + ky * P1;
-                const int e0 = s * F0 + c * nwin2;
-#pragma unroll 1
-                for (int w0 = 0; w0 < nwin2; w0 += 8) {
-                    // the deltas and winner offsets of eight windows first, then their rows
-                    float dl[8], rv[8][5];
-                    int of[8];
+        __syncthreads();
+        tq = opaque(tq);
+        // filter gradient over the own samples on the matrix cores:
+        //   gw[c][(ci, ky, kx)] = sum over (sample, position) of delta[c][pos] in[ci][pos + (ky, kx)]
+        // rows = the 16 channels, columns = the 150 filter entries of a channel in ten tiles of 16
+        // (the last one has 6 idle columns), contraction over the 4 x H2 x H2 positions, four
+        // consecutive positions of a map row per step (lane group kq takes position 4 t + kq).  The
+        // delta map is zero but at the window winners, which costs nothing here.  Waves 0 and 1
+        // take two tiles (one read of the deltas for both).
+        {
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4;
+            const int npos = H2 * H2, lgH2 = H2 == 8 ? 3 : H2 == 4 ? 2 : 1;
+            const float *abase = dc2 + n * CS2 + kq;
+            // where lane group kq sits inside a step: along the row, or (2 x 2 maps) in the map
+            const int kqoff = H2 >= 4 ? kq : (kq >> 1) * P1 + (kq & 1);
+            const bool two = wave + 8 < 10;
+            const float *bbase[2];
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int win = w0 + i < nwin2 ? w0 + i : nwin2 - 1;
-                        dl[i] = dp2[e0 + win];
-                        of[i] = off2[e0 + win];
+            for (int h = 0; h < 2; ++h) {
+                const int col = 16 * (wave + (two ? 8 * h : 0)) + n;
+                const int cc = col < 150 ? col : 149;     // idle columns read a valid entry
+                const int ci = cc / 25, r = cc - 25 * ci, ky = r / 5, kx = r - 5 * ky;
+                bbase[h] = p1 + ci * nwin1 + ky * P1 + kx + kqoff;
+            }
+            f4 acc[2] = {f4{0.f, 0.f, 0.f, 0.f}, f4{0.f, 0.f, 0.f, 0.f}};
+#pragma unroll 1
+            for (int sl = 0; sl < 4; ++sl) {
+#pragma unroll 1
+                for (int rem = 0; rem < npos; rem += 16) {
+                    const int nst = npos - rem >= 16 ? 4 : (npos - rem) >> 2;
+                    float av[4], bv[2][4];
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        const int ri = i < nst ? rem + 4 * i : rem;
+                        const int boff = sl * P1S + (H2 >= 4 ? (ri >> lgH2) * P1 + (ri & (H2 - 1)) : 0);
+                        av[i] = abase[sl * 16 * CS2 + ri];
+                        bv[0][i] = bbase[0][boff];
+                        bv[1][i] = two ? bbase[1][boff] : 0.f;
                     }
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-#pragma unroll
-                        for (int kx = 0; kx < 5; ++kx) rv[i][kx] = base[of[i] + kx];
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const float dv = w0 + i < nwin2 ? dl[i] : 0.f;
-#pragma unroll
-                        for (int kx = 0; kx < 5; ++kx) acc[kx] += dv * rv[i][kx];
+                    for (int i = 0; i < 4; ++i) {
+                        if (i < nst) {
+                            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[0][i], acc[0], 0, 0, 0);
+                            if (two) acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[1][i], acc[1], 0, 0, 0);
+                        }
                     }
                 }
             }
+            // lane: column n of the tile, channels 4 kq .. 4 kq + 3
 #pragma unroll
-            for (int kx = 0; kx < 5; ++kx) gsum[156 + c * 150 + ci * 25 + ky * 5 + kx] = acc[kx];
-        } else if (tq < 496) {
+            for (int h = 0; h < 2; ++h) {
+                const int col = 16 * (wave + 8 * h) + n;
+                if ((h == 0 || two) && col < 150) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) gsum[156 + (4 * kq + r) * 150 + col] = acc[h][r];
+                }
+            }
+        }
+        if (tq >= 480 && tq < 496) {
             const int c = tq - 480;
             float s = 0.f;
             if (nwin2 == 16) {
