@@ -29,6 +29,8 @@
 //
 // All workgroups of a client must be resident together; the wait for a peer's word is
 // bounded and raises an error flag instead of hanging (every workgroup still runs to the end).
+#include <type_traits>
+
 #include "aet_device.h"
 #include "aet_internal.h"
 
@@ -151,6 +153,10 @@ __device__ __forceinline__ float relu_pool(const float (&acc)[4], int &which) {
     return best;
 }
 
+// G28: the geometry of the 28 x 28 input (12 x 12 pooled maps, 8 x 8 conv-2 maps, 256 features)
+// as compile-time constants, so that the operand addresses of the convolution phases are
+// immediates; other input sizes take the sizes from d.
+template <bool G28>
 __global__ void __launch_bounds__(kLnThreads, 1)
 k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const float *Wg, const LenetDims d,
               u64 *__restrict__ xrec, uint32_t tag0, int *__restrict__ errflag) {
@@ -164,7 +170,8 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     const gci_ptr yg = as_global(p.y);
     const gf_ptr Wc = as_global(p.W), Uc = as_global(p.U);
     const int tid = threadIdx.x;
-    const int H0 = d.H0, P1 = d.P1, H2 = d.H2, P2 = d.P2, F0 = d.F0;
+    const int H0 = G28 ? 28 : d.H0, P1 = G28 ? 12 : d.P1, H2 = G28 ? 8 : d.H2, P2 = G28 ? 4 : d.P2, F0 = G28 ? 256 : d.F0;
+    const int lgF0 = G28 ? 8 : d.lgF0;
     const int nwin1 = P1 * P1, nwin2 = P2 * P2, npix = H0 * H0;
     const int P1S = 6 * nwin1 + 8;       // per-sample stride of the pooled conv-1 maps
     const int F0P = F0 + 4;              // row stride of arrays with F0 columns
@@ -445,7 +452,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             for (int i = 0; i < 8; ++i) {
                 const int e = e0 + kLnThreads * i;
                 const bool in = e < 16 * F0;
-                const int b = in ? e >> d.lgF0 : 0, f = in ? e & (F0 - 1) : 0;
+                const int b = in ? e >> lgF0 : 0, f = in ? e & (F0 - 1) : 0;
                 need[i] = in && (b >> 2) != g;
                 ptr[i] = rec + kXA1 + b * 256 + f;
                 dst[i] = b * F0P + f;
@@ -654,7 +661,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         // ---- backward through dense 1: partial d a0 over the own units -> exchange ---------------
         {
             // thread = (column f of a0, group of NB consecutive samples), NB = 16 F0 / 512 (at least 1)
-            const int f = tq & (F0 - 1), grp = tq >> d.lgF0;
+            const int f = tq & (F0 - 1), grp = tq >> lgF0;
             const int nb = F0 >= 32 ? (16 * F0) / kLnThreads : 1;       // 8, 2 or 1 samples per thread
             if (nb == 8) {
                 float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -691,7 +698,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         // dense 1: w <- w - eta g, U <- U + g on the own rows; the thread's entries share their
         // column k, so its 16 inputs are read once
         {
-            const int k = tq & (F0 - 1), ul0 = tq >> d.lgF0, ustep = kLnThreads >> d.lgF0;
+            const int k = tq & (F0 - 1), ul0 = tq >> lgF0, ustep = kLnThreads >> lgF0;
             float av[kLnB];
 #pragma unroll
             for (int b = 0; b < kLnB; ++b) av[b] = a0[b * F0P + k];
@@ -753,7 +760,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         for (int i = tq; i < 64 * CS2; i += kLnThreads) dc2[i] = 0.f;
         __syncthreads();
         for (int e = tq; e < 4 * F0; e += kLnThreads) {
-            const int s = e >> d.lgF0, f = e & (F0 - 1), c = f / nwin2;
+            const int s = e >> lgF0, f = e & (F0 - 1), c = f / nwin2;
             dc2[(s * 16 + c) * CS2 + pos2[e]] = dp2[e];
         }
         __syncthreads();
@@ -768,7 +775,6 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         {
             const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
             const int n = lane & 15, kq = lane >> 4;
-            const int npos = H2 * H2, lgH2 = H2 == 8 ? 3 : H2 == 4 ? 2 : 1;
             const float *abase = dc2 + n * CS2 + kq;
             // where lane group kq sits inside a step: along the row, or (2 x 2 maps) in the map
             const int kqoff = H2 >= 4 ? kq : (kq >> 1) * P1 + (kq & 1);
@@ -782,29 +788,45 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 bbase[h] = p1 + ci * nwin1 + ky * P1 + kx + kqoff;
             }
             f4 acc[2] = {f4{0.f, 0.f, 0.f, 0.f}, f4{0.f, 0.f, 0.f, 0.f}};
-#pragma unroll 1
-            for (int sl = 0; sl < 4; ++sl) {
-#pragma unroll 1
-                for (int rem = 0; rem < npos; rem += 16) {
-                    const int nst = npos - rem >= 16 ? 4 : (npos - rem) >> 2;
-                    float av[4], bv[2][4];
+            // the steps of one sample: 8 x 8 maps take them eight at a time (four map rows, two steps
+            // per row, every offset an immediate), smaller maps one map row (4 x 4) or the whole map
+            // (2 x 2) per step
+            auto sample_steps = [&](auto twoc, const float *ap, const float *bp0, const float *bp1) {
+                constexpr bool TWO = decltype(twoc)::value;
+                if (H2 == 8) {
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        const int ri = i < nst ? rem + 4 * i : rem;
-                        const int boff = sl * P1S + (H2 >= 4 ? (ri >> lgH2) * P1 + (ri & (H2 - 1)) : 0);
-                        av[i] = abase[sl * 16 * CS2 + ri];
-                        bv[0][i] = bbase[0][boff];
-                        bv[1][i] = two ? bbase[1][boff] : 0.f;
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                    for (int y0 = 0; y0 < 8; y0 += 4) {
+                        float av[8], b0[8], b1[8];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        if (i < nst) {
-                            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[0][i], acc[0], 0, 0, 0);
-                            if (two) acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], bv[1][i], acc[1], 0, 0, 0);
+                        for (int i = 0; i < 8; ++i) {
+                            const int y = y0 + (i >> 1), x0 = 4 * (i & 1);
+                            av[i] = ap[8 * y + x0];
+                            b0[i] = bp0[y * P1 + x0];
+                            if (TWO) b1[i] = bp1[y * P1 + x0];
                         }
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], b0[i], acc[0], 0, 0, 0);
+                            if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], b1[i], acc[1], 0, 0, 0);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                } else {
+                    const int rows = H2 == 4 ? 4 : 1;
+#pragma unroll 1
+                    for (int y = 0; y < rows; ++y) {
+                        const float a1 = ap[4 * y], c0 = bp0[y * P1];
+                        acc[0] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, c0, acc[0], 0, 0, 0);
+                        if (TWO) acc[1] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, bp1[y * P1], acc[1], 0, 0, 0);
                     }
                 }
+            };
+#pragma unroll 1
+            for (int sl = 0; sl < 4; ++sl) {
+                const float *ap = abase + sl * 16 * CS2, *bp0 = bbase[0] + sl * P1S, *bp1 = bbase[1] + sl * P1S;
+                if (two) sample_steps(std::true_type{}, ap, bp0, bp1);
+                else sample_steps(std::false_type{}, ap, bp0, bp1);
             }
             // lane: column n of the tile, channels 4 kq .. 4 kq + 3
 #pragma unroll
@@ -1019,7 +1041,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
 
     // ---- end of round: the replica and the message payload go to HBM ------------------------------
     {
-        const int k = tid & (F0 - 1), ul0 = tid >> d.lgF0, ustep = kLnThreads >> d.lgF0;
+        const int k = tid & (F0 - 1), ul0 = tid >> lgF0, ustep = kLnThreads >> lgF0;
 #pragma unroll
         for (int j = 0; j < 15; ++j) {
             const int ul = ul0 + ustep * j;
@@ -1108,7 +1130,7 @@ size_t lenet_lds_bytes(const LenetDims &d) {
     return fl * 4;
 }
 
-int g_lenet_per_cu = 0;
+int g_lenet_per_cu[2] = {0, 0};
 
 }  // namespace
 
@@ -1142,8 +1164,10 @@ hipError_t launch_lenet_round(hipStream_t s, Profiler *prof, const RoundParams *
     if (!lenet_dims(lay, L, B, &d)) return hipErrorInvalidValue;
     const size_t lds = lenet_lds_bytes(d);
     hipError_t e;
-    if (g_lenet_per_cu == 0) {
-        e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_lenet_round), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    const bool g28 = d.H0 == 28 && d.P1 == 12 && d.H2 == 8 && d.P2 == 4 && d.F0 == 256 && d.lgF0 == 8;
+    const void *fn = g28 ? reinterpret_cast<const void *>(k_lenet_round<true>) : reinterpret_cast<const void *>(k_lenet_round<false>);
+    if (g_lenet_per_cu[g28] == 0) {
+        e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
     }
     int dev = 0, cus = 0, per_cu = 0;
@@ -1151,9 +1175,10 @@ hipError_t launch_lenet_round(hipStream_t s, Profiler *prof, const RoundParams *
     if (e != hipSuccess) return e;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
-    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_lenet_round, kLnThreads, lds);
+    e = g28 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_lenet_round<true>, kLnThreads, lds)
+            : hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k_lenet_round<false>, kLnThreads, lds);
     if (e != hipSuccess) return e;
-    g_lenet_per_cu = per_cu;
+    g_lenet_per_cu[g28] = per_cu;
     // clusters per launch: every workgroup that polls must be resident together with its peers
     const int per_launch = cus * per_cu / kLnG;
     if (per_launch < 1) return hipErrorLaunchOutOfResources;
@@ -1174,7 +1199,8 @@ hipError_t launch_lenet_round(hipStream_t s, Profiler *prof, const RoundParams *
         const int here = nact - a0 < per_launch ? nact - a0 : per_launch;
         const unsigned grid = (unsigned)(8 * ((here + 7) / 8) * kLnG);
         if (prof && prof->on[F_LENET_ROUND]) prof->before(F_LENET_ROUND, s);
-        k_lenet_round<<<grid, kLnThreads, lds, s>>>(dp + a0, here, a0, Wg, d, xrec, tag0, errflag);
+        if (g28) k_lenet_round<true><<<grid, kLnThreads, lds, s>>>(dp + a0, here, a0, Wg, d, xrec, tag0, errflag);
+        else k_lenet_round<false><<<grid, kLnThreads, lds, s>>>(dp + a0, here, a0, Wg, d, xrec, tag0, errflag);
         if (prof && prof->on[F_LENET_ROUND]) prof->after(F_LENET_ROUND, s);
         e = hipGetLastError();
         if (e != hipSuccess) return e;
