@@ -47,6 +47,7 @@ constexpr int kLnB = 16;             // mini-batch
 constexpr int kF1 = 120, kF2 = 84, kNC = 10;
 constexpr int kU1 = kF1 / kLnG, kU2 = kF2 / kLnG;   // units of the hidden layers per workgroup
 constexpr int kS1 = 124, kS2 = 88;   // LDS row strides of arrays with 120 / 84 columns
+constexpr int kDP = 32 * 17;         // floats of one wave's slice of partial dense outputs
 constexpr int kConvP = 2572;         // parameters of the two filter banks (150 + 6 + 2400 + 16)
 constexpr int kLnSpin = 1 << 22;     // bounded wait of the exchange poll
 
@@ -211,6 +212,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     float *dc2 = a0;                               // [4][16][CS2]    delta at the conv-2 outputs, over a0 .. d1own (after the dense backward)
     const int CS2 = H2 * H2 + 4;                   // its channel stride: the rows of consecutive channels start 4 banks apart
     float *dp1 = h1;                               // [4][P1S]        delta at the pooled conv-1 outputs
+    float *dpart = gsum;                           // [8][kDP]        partial sums of the dense forward products, one [32 units][17] slice per wave (over gsum, c1part)
 
     u64 *rec = xrec + (int64_t)(rec0 + a) * kXWords;
     Waiter wt{tag0, errflag, false};
@@ -465,19 +467,53 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         __syncthreads();
 
         tq = opaque(tq);
-        // ---- dense 1, own units: thread = (unit, sample) ----------------------------------------
+        // ---- dense 1, own units, on the matrix cores: rows = the 16 samples, columns = the 30 own
+        // units in two tiles (two idle columns), the F0 inputs dealt over the waves in runs of
+        // F0 / 32 steps of four; the waves' partial sums meet in LDS and are added in wave order ------
+        {
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4;
+            const int nstep = F0 >> 2, per = (nstep + 7) >> 3;      // steps in all, steps per wave
+            const int t0 = wave * per, t1 = t0 + per < nstep ? t0 + per : nstep;
+            const float *ap = a0 + n * F0P + kq;
+            const float *bp0 = w1s + n * F0P + kq, *bp1 = w1s + (16 + n < kU1 ? 16 + n : kU1 - 1) * F0P + kq;
+            f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+            if (F0 == 256) {
+                float av[8], b0[8], b1[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    av[i] = ap[4 * (t0 + i)];
+                    b0[i] = bp0[4 * (t0 + i)];
+                    b1[i] = bp1[4 * (t0 + i)];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], b0[i], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], b1[i], acc1, 0, 0, 0);
+                }
+            } else {
+#pragma unroll 1
+                for (int t = t0; t < t1; ++t) {
+                    const float av = ap[4 * t];
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp0[4 * t], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av, bp1[4 * t], acc1, 0, 0, 0);
+                }
+            }
+            // lane: unit n (and 16 + n), samples 4 kq .. 4 kq + 3; unit-major with a stride of 17
+            float *dst = dpart + wave * kDP + n * 17 + 4 * kq;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                dst[r] = acc0[r];
+                dst[16 * 17 + r] = acc1[r];
+            }
+        }
+        __syncthreads();
         if (tq < kU1 * 16) {
             const int ul = tq >> 4, b = tq & 15;
-            // four partial sums (one per position in the 16-byte pieces), so that consecutive
-            // multiply-adds do not wait for each other
-            f4 part = {b1s[ul], 0.f, 0.f, 0.f};
-            const float *wr = w1s + ul * F0P, *ar = a0 + b * F0P;
-#pragma unroll 4
-            for (int k = 0; k < F0; k += 4) {
-                const f4 wv = *reinterpret_cast<const f4 *>(wr + k), av = *reinterpret_cast<const f4 *>(ar + k);
-                part += wv * av;
-            }
-            const float acc = (part[0] + part[1]) + (part[2] + part[3]);
+            float acc = b1s[ul];
+#pragma unroll
+            for (int w = 0; w < kLnThreads / 64; ++w) acc += dpart[w * kDP + ul * 17 + b];
             const float h = acc > 0.f ? acc : 0.f;
             h1[b * kS1 + kU1 * g + ul] = h;
             xpost(rec + kXA2 + b * 128 + kU1 * g + ul, wt.tag, h);
