@@ -236,10 +236,10 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     if (tid < kNC) b3s[tid] = src[d.o_f3 + kNC * kF2 + tid];
     if (tid == 0) lossacc[0] = 0.f;
     // U of the weights this thread updates
-    float U1[15], U2[5], U3[2], UC[6];
+    float U1[16], U2[5], U3[2], UC[6];
     float U1b = 0.f, U2b = 0.f, U3b = 0.f;
 #pragma unroll
-    for (int j = 0; j < 15; ++j) U1[j] = 0.f;
+    for (int j = 0; j < 16; ++j) U1[j] = 0.f;
 #pragma unroll
     for (int j = 0; j < 5; ++j) U2[j] = 0.f;
 #pragma unroll
@@ -689,37 +689,43 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 s += val[2];
                 s += val[3];
                 d1own[ul * 16 + b] = h1[b * kS1 + k] > 0.f ? s : 0.f;
+            } else {
+                d1own[tq] = 0.f;   // rows 30 and 31: idle rows of the matrix-core products below
             }
         }
         __syncthreads();
 
         tq = opaque(tq);
-        // ---- backward through dense 1: partial d a0 over the own units -> exchange ---------------
+        // ---- backward through dense 1: partial d a0 over the own units -> exchange.  On the matrix
+        // cores: rows = the 16 samples, columns = the F0 features in tiles of 16 (tiles w and w + 8
+        // for wave w), contraction over the 30 own units in eight steps (the two idle units have
+        // zero deltas and read the last weight row) -------------------------------------------------
         {
-            // thread = (column f of a0, group of NB consecutive samples), NB = 16 F0 / 512 (at least 1)
-            const int f = tq & (F0 - 1), grp = tq >> lgF0;
-            const int nb = F0 >= 32 ? (16 * F0) / kLnThreads : 1;       // 8, 2 or 1 samples per thread
-            if (nb == 8) {
-                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll 2
-                for (int ul = 0; ul < kU1; ++ul) {
-                    const float wv = w1s[ul * F0P + f];
-                    const f4 da = *reinterpret_cast<const f4 *>(d1own + ul * 16 + 8 * grp);
-                    const f4 db = *reinterpret_cast<const f4 *>(d1own + ul * 16 + 8 * grp + 4);
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4;
+            const int ntile = F0 >> 4;
+            if (wave < ntile) {
+                const bool two = wave + 8 < ntile;
+                float av[8], b0[8], b1[8];
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        acc[i] += da[i] * wv;
-                        acc[4 + i] += db[i] * wv;
-                    }
+                for (int t = 0; t < 8; ++t) {
+                    const int ul = 4 * t + kq, ulc = ul < kU1 ? ul : kU1 - 1;
+                    av[t] = d1own[ul * 16 + n];
+                    b0[t] = w1s[ulc * F0P + 16 * wave + n];
+                    b1[t] = two ? w1s[ulc * F0P + 16 * (wave + 8) + n] : 0.f;
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int i = 0; i < 8; ++i) xpost(rec + kXB2 + g * 4096 + (8 * grp + i) * 256 + f, wt.tag, acc[i]);
-            } else if (grp * nb < kLnB) {
-                for (int i = 0; i < nb; ++i) {
-                    const int b = grp * nb + i;
-                    float acc = 0.f;
-                    for (int ul = 0; ul < kU1; ++ul) acc += d1own[ul * 16 + b] * w1s[ul * F0P + f];
-                    xpost(rec + kXB2 + g * 4096 + b * 256 + f, wt.tag, acc);
+                for (int t = 0; t < 8; ++t) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], b0[t], acc0, 0, 0, 0);
+                    if (two) acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], b1[t], acc1, 0, 0, 0);
+                }
+                // lane: feature n of the tile, samples 4 kq .. 4 kq + 3
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    xpost(rec + kXB2 + g * 4096 + (4 * kq + r) * 256 + 16 * wave + n, wt.tag, acc0[r]);
+                    if (two) xpost(rec + kXB2 + g * 4096 + (4 * kq + r) * 256 + 16 * (wave + 8) + n, wt.tag, acc1[r]);
                 }
             }
         }
@@ -731,29 +737,52 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             alive2[j] = e < 4 * F0 && a0[(4 * g + e / F0) * F0P + e % F0] > 0.f;
         }
         __syncthreads();
-        // dense 1: w <- w - eta g, U <- U + g on the own rows; the thread's entries share their
-        // column k, so its 16 inputs are read once
+        // dense 1: w <- w - eta g, U <- U + g on the own rows.  g^T = delta^T a0 on the matrix cores:
+        // rows = the own units in two tiles, columns = the F0 inputs in tiles of 16 (tiles w and
+        // w + 8 for wave w), contraction over the 16 samples.  A lane ends up with the gradient of
+        // the weights (unit 16 mt + 4 kq + r, input 16 nt + n) and keeps their U.
         {
-            const int k = tq & (F0 - 1), ul0 = tq >> lgF0, ustep = kLnThreads >> lgF0;
-            float av[kLnB];
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4;
+            const int ntile = F0 >> 4;
+            if (wave < ntile) {
+                const bool two = wave + 8 < ntile;
+                float av[2][4], bv[2][4];
 #pragma unroll
-            for (int b = 0; b < kLnB; ++b) av[b] = a0[b * F0P + k];
+                for (int t = 0; t < 4; ++t) {
+                    av[0][t] = d1own[n * 16 + 4 * t + kq];
+                    av[1][t] = d1own[(16 + n) * 16 + 4 * t + kq];
+                    bv[0][t] = a0[(4 * t + kq) * F0P + 16 * wave + n];
+                    bv[1][t] = two ? a0[(4 * t + kq) * F0P + 16 * (wave + 8) + n] : 0.f;
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                f4 acc[2][2];
 #pragma unroll
-            for (int j = 0; j < 15; ++j) {
-                const int ul = ul0 + ustep * j;
-                if (ul < kU1) {
-                    float s = 0.f;
+                for (int nl = 0; nl < 2; ++nl)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const f4 dv = *reinterpret_cast<const f4 *>(d1own + ul * 16 + 4 * q);
-                        s += dv[0] * av[4 * q];
-                        s += dv[1] * av[4 * q + 1];
-                        s += dv[2] * av[4 * q + 2];
-                        s += dv[3] * av[4 * q + 3];
+                    for (int mt = 0; mt < 2; ++mt) acc[nl][mt] = f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt) {
+                        acc[0][mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][t], bv[0][t], acc[0][mt], 0, 0, 0);
+                        if (two) acc[1][mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][t], bv[1][t], acc[1][mt], 0, 0, 0);
                     }
-                    const float gv = s * invB;
-                    w1s[ul * F0P + k] -= eta * gv;
-                    U1[j] += gv;
+#pragma unroll
+                for (int nl = 0; nl < 2; ++nl) {
+                    if (nl == 1 && !two) break;
+                    const int k = 16 * (wave + 8 * nl) + n;
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const int ul = 16 * mt + 4 * kq + r;
+                            if (ul < kU1) {
+                                const float gv = acc[nl][mt][r] * invB;
+                                w1s[ul * F0P + k] -= eta * gv;
+                                U1[(2 * nl + mt) * 4 + r] += gv;
+                            }
+                        }
                 }
             }
         }
@@ -1076,15 +1105,24 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     }
 
     // ---- end of round: the replica and the message payload go to HBM ------------------------------
-    {
-        const int k = tid & (F0 - 1), ul0 = tid >> lgF0, ustep = kLnThreads >> lgF0;
+    {   // dense 1 in the ownership of its update: lane (n, kq) of wave w, input tiles w and w + 8
+        const int wave = tid >> 6, n = tid & 15, kq = (tid & 63) >> 4, ntile = F0 >> 4;
 #pragma unroll
-        for (int j = 0; j < 15; ++j) {
-            const int ul = ul0 + ustep * j;
-            if (ul < kU1) {
-                const int64_t o = d.o_f1 + (int64_t)(kU1 * g + ul) * F0 + k;
-                Wc[o] = w1s[ul * F0P + k];
-                Uc[o] = U1[j];
+        for (int nl = 0; nl < 2; ++nl) {
+            const int nt = wave + 8 * nl;
+            if (nt < ntile) {
+                const int k = 16 * nt + n;
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int ul = 16 * mt + 4 * kq + r;
+                        if (ul < kU1) {
+                            const int64_t o = d.o_f1 + (int64_t)(kU1 * g + ul) * F0 + k;
+                            Wc[o] = w1s[ul * F0P + k];
+                            Uc[o] = U1[(2 * nl + mt) * 4 + r];
+                        }
+                    }
             }
         }
     }
