@@ -236,12 +236,12 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     if (tid < kNC) b3s[tid] = src[d.o_f3 + kNC * kF2 + tid];
     if (tid == 0) lossacc[0] = 0.f;
     // U of the weights this thread updates
-    float U1[16], U2[5], U3[2], UC[6];
+    float U1[16], U2[8], U3[2], UC[6];
     float U1b = 0.f, U2b = 0.f, U3b = 0.f;
 #pragma unroll
     for (int j = 0; j < 16; ++j) U1[j] = 0.f;
 #pragma unroll
-    for (int j = 0; j < 5; ++j) U2[j] = 0.f;
+    for (int j = 0; j < 8; ++j) U2[j] = 0.f;
 #pragma unroll
     for (int j = 0; j < 2; ++j) U3[j] = 0.f;
 #pragma unroll
@@ -540,17 +540,44 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         __syncthreads();
 
         tq = opaque(tq);
-        // ---- dense 2, own units ------------------------------------------------------------------
+        // ---- dense 2, own units, on the matrix cores like dense 1: the 30 steps of four inputs are
+        // dealt over the waves (four each), the 21 own units fill two column tiles ------------------
+        {
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4;
+            const int t0 = 4 * wave;
+            const float *ap = h1 + n * kS1 + kq;
+            const float *bp0 = w2s + n * kS1 + kq, *bp1 = w2s + (16 + n < kU2 ? 16 + n : kU2 - 1) * kS1 + kq;
+            float av[4], b0[4], b1[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = t0 + i < kF1 / 4 ? t0 + i : kF1 / 4 - 1;
+                av[i] = ap[4 * t];
+                b0[i] = bp0[4 * t];
+                b1[i] = bp1[4 * t];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (t0 + i < kF1 / 4) {
+                    acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], b0[i], acc0, 0, 0, 0);
+                    acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av[i], b1[i], acc1, 0, 0, 0);
+                }
+            }
+            float *dst = dpart + wave * kDP + n * 17 + 4 * kq;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                dst[r] = acc0[r];
+                dst[16 * 17 + r] = acc1[r];
+            }
+        }
+        __syncthreads();
         if (tq < kU2 * 16) {
             const int ul = tq >> 4, b = tq & 15;
-            f4 part = {b2s[ul], 0.f, 0.f, 0.f};
-            const float *wr = w2s + ul * kS1, *ar = h1 + b * kS1;
-#pragma unroll 5
-            for (int k = 0; k < kF1; k += 4) {
-                const f4 wv = *reinterpret_cast<const f4 *>(wr + k), av = *reinterpret_cast<const f4 *>(ar + k);
-                part += wv * av;
-            }
-            const float acc = (part[0] + part[1]) + (part[2] + part[3]);
+            float acc = b2s[ul];
+#pragma unroll
+            for (int w = 0; w < kLnThreads / 64; ++w) acc += dpart[w * kDP + ul * 17 + b];
             const float h = acc > 0.f ? acc : 0.f;
             h2[b * kS2 + kU2 * g + ul] = h;
             xpost(rec + kXA3 + b * 96 + kU2 * g + ul, wt.tag, h);
@@ -609,6 +636,9 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
 #pragma unroll
             for (int o = 0; o < kNC; ++o) acc += dz[b * 16 + o] * w3s[o * kS2 + k];
             d2own[b * 24 + ul] = h2[b * kS2 + k] > 0.f ? acc : 0.f;
+        } else if (tq < kU2 * 16 + 48) {   // columns 21 .. 23: idle steps of the matrix-core product below
+            const int i = tq - kU2 * 16;
+            d2own[(i & 15) * 24 + kU2 + (i >> 4)] = 0.f;
         }
         if (g == 0 && tq == 511) {
             float s = 0.f;
@@ -619,12 +649,26 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
 
         tq = opaque(tq);
         // ---- backward through dense 2: partial d h1 over the own units -> exchange ---------------
-        for (int e = tq; e < 16 * kF1; e += kLnThreads) {
-            const int b = e / kF1, k = e % kF1;
-            float acc = 0.f;
+        // on the matrix cores: rows = the 16 samples, columns = the 120 inputs (wave w takes tile
+        // w), contraction over the 21 own units in six steps (idle units: zero deltas)
+        {
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4, k = 16 * wave + n;
+            float av[6], bv[6];
 #pragma unroll
-            for (int ul = 0; ul < kU2; ++ul) acc += d2own[b * 24 + ul] * w2s[ul * kS1 + k];
-            xpost(rec + kXB1 + g * 2048 + b * 128 + k, wt.tag, acc);
+            for (int t = 0; t < 6; ++t) {
+                const int ul = 4 * t + kq, ulc = ul < kU2 ? ul : kU2 - 1;
+                av[t] = d2own[n * 24 + ul];
+                bv[t] = w2s[ulc * kS1 + k];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            f4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < 6; ++t) acc = __builtin_amdgcn_mfma_f32_16x16x4f32(av[t], bv[t], acc, 0, 0, 0);
+            if (k < kF1) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) xpost(rec + kXB1 + g * 2048 + (4 * kq + r) * 128 + k, wt.tag, acc[r]);
+            }
         }
         // dense 3: w <- w - eta g, U <- U + g (the same in every workgroup)
 #pragma unroll
@@ -649,17 +693,37 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             U3b += gv;
         }
         __syncthreads();
+        // dense 2: g^T = delta^T h1 on the matrix cores (rows = the own units in two tiles, columns =
+        // the 120 inputs, wave w takes tile w, contraction over the 16 samples); a lane keeps U of
+        // the weights (unit 16 mt + 4 kq + r, input 16 w + n)
+        {
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4, k = 16 * wave + n;
+            float av[2][4], bv[4];
 #pragma unroll
-        for (int j = 0; j < 5; ++j) {
-            const int e = tq + kLnThreads * j;
-            if (e < kU2 * kF1) {
-                const int ul = e / kF1, k = e % kF1;
-                float s = 0.f;
+            for (int t = 0; t < 4; ++t) {
+                av[0][t] = d2own[(4 * t + kq) * 24 + n];
+                av[1][t] = d2own[(4 * t + kq) * 24 + (16 + n < 24 ? 16 + n : 23)];
+                bv[t] = h1[(4 * t + kq) * kS1 + k];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            f4 acc[2] = {f4{0.f, 0.f, 0.f, 0.f}, f4{0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-                for (int b = 0; b < kLnB; ++b) s += d2own[b * 24 + ul] * h1[b * kS1 + k];
-                const float gv = s * invB;
-                w2s[ul * kS1 + k] -= eta * gv;
-                U2[j] += gv;
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) acc[mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][t], bv[t], acc[mt], 0, 0, 0);
+            if (k < kF1) {
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int ul = 16 * mt + 4 * kq + r;
+                        if (ul < kU2) {
+                            const float gv = acc[mt][r] * invB;
+                            w2s[ul * kS1 + k] -= eta * gv;
+                            U2[4 * mt + r] += gv;
+                        }
+                    }
             }
         }
         if (tq < kU2) {
@@ -1131,14 +1195,20 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         Wc[o] = b1s[tid];
         Uc[o] = U1b;
     }
+    {   // dense 2 in the ownership of its update
+        const int wave = tid >> 6, n = tid & 15, kq = (tid & 63) >> 4, k = 16 * wave + n;
+        if (k < kF1) {
 #pragma unroll
-    for (int j = 0; j < 5; ++j) {
-        const int e = tid + kLnThreads * j;
-        if (e < kU2 * kF1) {
-            const int ul = e / kF1, k = e % kF1;
-            const int64_t o = d.o_f2 + (int64_t)(kU2 * g + ul) * kF1 + k;
-            Wc[o] = w2s[ul * kS1 + k];
-            Uc[o] = U2[j];
+            for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int ul = 16 * mt + 4 * kq + r;
+                    if (ul < kU2) {
+                        const int64_t o = d.o_f2 + (int64_t)(kU2 * g + ul) * kF1 + k;
+                        Wc[o] = w2s[ul * kS1 + k];
+                        Uc[o] = U2[4 * mt + r];
+                    }
+                }
         }
     }
     if (tid < kU2) {
