@@ -1080,6 +1080,16 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         __syncthreads();
 
         tq = opaque(tq);
+        // the four partial conv-2 gradients were posted before the last phase: ask for them now, the
+        // words are looked at after the conv-1 gradient below (thread: elements 156 + tq + 512 j)
+        u64 early[5][4];
+#pragma unroll
+        for (int j = 0; j < 5; ++j) {
+            const int e = 156 + tq + kLnThreads * j;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                early[j][i] = __hip_atomic_load(rec + kXB3 + i * 2576 + (e < kConvP ? e : 156), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         // ---- conv-1 filter gradient over the own samples: thread = (window group, channel,
         // filter row or bias); one position per window ---------------------------------------------
         if (tq < 14 * 36) {
@@ -1135,34 +1145,57 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         }
         // the next recursion's rows and labels (xs and labs are not read any more)
         if (more) store_rows(xr, labr);
+        {   // the conv-1 part: threads 0 .. 155
+            const bool act = tq < 156;
+            const u64 *ptr[4];
+            bool need[4];
+            float val[4];
 #pragma unroll
-        for (int j0 = 0; j0 < 6; j0 += 3) {
-            const u64 *ptr[12];
-            bool need[12];
-            float val[12];
+            for (int i = 0; i < 4; ++i) {
+                ptr[i] = rec + kXB3 + i * 2576 + (act ? tq : 0);
+                need[i] = act;
+            }
+            xfetch<4>(ptr, need, val, wt);
+            if (act) {
+                float t = val[0];
+                t += val[1];
+                t += val[2];
+                t += val[3];
+                const float gv = t * invB;
+                wc1[tq] -= eta * gv;
+                UC[0] += gv;
+            }
+        }
 #pragma unroll
-            for (int jj = 0; jj < 3; ++jj) {
-                const int e = tq + kLnThreads * (j0 + jj);
+        for (int j = 0; j < 5; ++j) {   // the conv-2 part and its biases: the words asked for earlier
+            const int e = 156 + tq + kLnThreads * j;
+            const bool act = e < kConvP;
+            float val[4];
+            bool ok = true;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ok = ok && (uint32_t)(early[j][i] >> 32) == wt.tag;
+                val[i] = __uint_as_float((uint32_t)early[j][i]);
+            }
+            if (act && !ok) {   // not there yet when asked: fetch again (rare)
+                const u64 *ptr[4];
+                bool need[4];
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    ptr[4 * jj + i] = rec + kXB3 + i * 2576 + (e < kConvP ? e : 0);
-                    need[4 * jj + i] = e < kConvP;
+                    ptr[i] = rec + kXB3 + i * 2576 + e;
+                    need[i] = true;
                 }
+                xfetch<4>(ptr, need, val, wt);
             }
-            xfetch<12>(ptr, need, val, wt);
-#pragma unroll
-            for (int jj = 0; jj < 3; ++jj) {
-                const int e = tq + kLnThreads * (j0 + jj);
-                if (e < kConvP) {
-                    float t = val[4 * jj];
-                    t += val[4 * jj + 1];
-                    t += val[4 * jj + 2];
-                    t += val[4 * jj + 3];
-                    const float gv = t * invB;
-                    float *w = e < 156 ? wc1 + e : e < 2556 ? wc2 + ((e - 156) / 150) * 152 + (e - 156) % 150 : wc2b + (e - 2556);
-                    *w -= eta * gv;
-                    UC[j0 + jj] += gv;
-                }
+            if (act) {
+                float t = val[0];
+                t += val[1];
+                t += val[2];
+                t += val[3];
+                const float gv = t * invB;
+                float *w = e < 2556 ? wc2 + ((e - 156) / 150) * 152 + (e - 156) % 150 : wc2b + (e - 2556);
+                *w -= eta * gv;
+                UC[1 + j] += gv;
             }
         }
         __syncthreads();
@@ -1229,12 +1262,16 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             Wc[d.o_f3 + kNC * kF2 + tid] = b3s[tid];
             Uc[d.o_f3 + kNC * kF2 + tid] = U3b;
         }
+        if (tid < 156) {   // the filter banks in the ownership of their update
+            Wc[tid] = wc1[tid];
+            Uc[tid] = UC[0];
+        }
 #pragma unroll
-        for (int j = 0; j < 6; ++j) {
-            const int e = tid + kLnThreads * j;
+        for (int j = 0; j < 5; ++j) {
+            const int e = 156 + tid + kLnThreads * j;
             if (e < kConvP) {
-                Wc[e] = e < 156 ? wc1[e] : e < 2556 ? wc2[((e - 156) / 150) * 152 + (e - 156) % 150] : wc2b[e - 2556];
-                Uc[e] = UC[j];
+                Wc[e] = e < 2556 ? wc2[((e - 156) / 150) * 152 + (e - 156) % 150] : wc2b[e - 2556];
+                Uc[e] = UC[1 + j];
             }
         }
         if (tid == 0) *as_global(p.loss) = lossacc[0];
