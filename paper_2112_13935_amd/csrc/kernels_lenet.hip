@@ -997,11 +997,81 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             if (e < kConvP) xpost(rec + kXB3 + g * 2576 + e, wt.tag, gsum[e]);
         }
         // delta at the pooled conv-1 outputs (dense correlation with the flipped filters), masked
-        // by the ReLU.  A wave takes one output row yy and two input channels: lane = (channels c
-        // and c + 8, sample, input channel); the filter rows that reach row yy are the same
-        // for the whole wave (scalar loop bounds), whole delta rows are read without guards, and
-        // the eight channel groups of a lane octet are added in a fixed tree.
-        {
+        // by the ReLU.
+        if constexpr (G28) {
+            // On the matrix cores, in two stages.  With the input channel alone as the row index a
+            // 16-row tile would hold 6 rows; so the filter column kx joins it:
+            //   T[(ci, kx)][s][yy][x'] = sum over (c, ky) of w[c][ci][ky][kx] delta[s][c][yy - ky][x']
+            // (30 rows in two tiles; columns = two samples x the 8 positions of a delta row;
+            // contraction over the 16 channels, four per step, and the filter rows that reach yy),
+            // and then  d[s][ci][yy][xx] = sum over kx of T[(ci, kx)][s][yy][xx - kx],  added in
+            // the order of kx through a slice of LDS that belongs to the wave.
+            // Work item = (output row yy, sample pair); rows yy and 11 - yy together cost the same
+            // for yy = 4, 5 (ten filter-row passes), and rows {3, 8, 0, 11} and {2, 9, 1, 10} as
+            // well: every wave gets ten passes.
+            __syncthreads();    // gsum has been posted: its space now holds the waves' slices
+            const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
+            const int n = lane & 15, kq = lane >> 4;
+            const int nt = wave & 1, wq = wave >> 1;                       // sample pair; 0..3
+            const int ya = wq == 0 ? 4 : wq == 1 ? 5 : wq == 2 ? 3 : 2;    // rows ya, 11 - ya, and
+            const int yb = wq == 2 ? 0 : wq == 3 ? 1 : -1;                 // yb, 11 - yb (if any)
+            const int m0 = n, m1 = 16 + n < 30 ? 16 + n : 29;              // rows (ci, kx) of the two tiles
+            const float *wa0 = wc2 + kq * 152 + (m0 / 5) * 25 + m0 % 5;
+            const float *wa1 = wc2 + kq * 152 + (m1 / 5) * 25 + m1 % 5;
+            const float *bbase = dc2 + ((2 * nt + (n >> 3)) * 16 + kq) * CS2 + (n & 7);
+            float *scr = dpart + wave * kDP;
+#pragma unroll 1
+            for (int it = 0; it < 4; ++it) {
+                const int ysel = it < 2 ? ya : yb;
+                if (ysel < 0) break;
+                const int yy = (it & 1) ? 11 - ysel : ysel;
+                const int ky_lo = yy - 7 > 0 ? yy - 7 : 0, ky_hi = yy < 4 ? yy : 4;
+                f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+                for (int ky = ky_lo; ky <= ky_hi; ++ky) {
+                    const float *ap0 = wa0 + ky * 5, *ap1 = wa1 + ky * 5, *bp = bbase + (yy - ky) * 8;
+                    float av0[4], av1[4], bv[4];
+#pragma unroll
+                    for (int tc = 0; tc < 4; ++tc) {
+                        av0[tc] = ap0[tc * 4 * 152];
+                        av1[tc] = ap1[tc * 4 * 152];
+                        bv[tc] = bp[tc * 4 * CS2];
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int tc = 0; tc < 4; ++tc) {
+                        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av0[tc], bv[tc], acc0, 0, 0, 0);
+                        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av1[tc], bv[tc], acc1, 0, 0, 0);
+                    }
+                }
+                // lane: column n = (sample of the pair, x'), rows 4 kq + r of both tiles
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    scr[(4 * kq + r) * 17 + n] = acc0[r];
+                    if (16 + 4 * kq + r < 30) scr[(16 + 4 * kq + r) * 17 + n] = acc1[r];
+                }
+                // (the wave's LDS operations are carried out in order: no barrier is needed)
+#pragma unroll
+                for (int j = 0; j < 3; ++j) {
+                    const int o = lane + 64 * j;
+                    if (o < 144) {
+                        const int sl = o / 72, rem = o - 72 * sl, ci = rem / 12, xx = rem - 12 * ci;
+                        float t = 0.f;
+#pragma unroll
+                        for (int kx = 0; kx < 5; ++kx) {
+                            const int xp = xx - kx;
+                            if (xp >= 0 && xp < 8) t += scr[(ci * 5 + kx) * 17 + sl * 8 + xp];
+                        }
+                        const int oi = (2 * nt + sl) * P1S + ci * nwin1 + yy * P1 + xx;
+                        dp1[oi] = p1[oi] > 0.f ? t : 0.f;
+                    }
+                }
+            }
+        } else {
+            // A wave takes one output row yy and two input channels: lane = (channels c
+            // and c + 8, sample, input channel); the filter rows that reach row yy are the same
+            // for the whole wave (scalar loop bounds), whole delta rows are read without guards, and
+            // the eight channel groups of a lane octet are added in a fixed tree.
             const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
             const int cq = lane & 7, s = (lane >> 3) & 3, cil = lane >> 5;
 #pragma unroll 1
