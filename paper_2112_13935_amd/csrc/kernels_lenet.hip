@@ -47,6 +47,7 @@ constexpr int kLnB = 16;             // mini-batch
 constexpr int kF1 = 120, kF2 = 84, kNC = 10;
 constexpr int kU1 = kF1 / kLnG, kU2 = kF2 / kLnG;   // units of the hidden layers per workgroup
 constexpr int kS1 = 124, kS2 = 88;   // LDS row strides of arrays with 120 / 84 columns
+constexpr int kWS = 164;              // LDS row stride of the conv-2 filters (150 used; 4 mod 32: the rows of 8 channels cover all banks)
 constexpr int kDP = 32 * 17;         // floats of one wave's slice of partial dense outputs
 constexpr int kConvP = 2572;         // parameters of the two filter banks (150 + 6 + 2400 + 16)
 constexpr int kLnSpin = 1 << 22;     // bounded wait of the exchange poll
@@ -191,8 +192,8 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     uint16_t *off2 = off1 + up4(4 * 6 * nwin1);                          // [4][F0]       in the P1 x P1 pooled conv-1 map
     uint8_t *pos2 = reinterpret_cast<uint8_t *>(off2 + up4(4 * F0));     // [4][F0]       in the H2 x H2 conv-2 map
     float *wc1 = reinterpret_cast<float *>(pos2 + up4(4 * F0));          // [150] + bias [6] (+ pad)
-    float *wc2 = wc1 + 160;                        // [16][152]
-    float *wc2b = wc2 + 16 * 152;                  // [16]
+    float *wc2 = wc1 + 160;                        // [16][kWS]
+    float *wc2b = wc2 + 16 * kWS;                  // [16]
     float *w1s = wc2b + 16;                        // [30][F0P]
     float *b1s = w1s + kU1 * F0P;                  // [32]
     float *w2s = b1s + 32;                         // [21][kS1]
@@ -220,7 +221,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
     // ---- adopt the global model (server form) or go on from the own replica (Wg == NULL) ----
     const float *src = Wg ? Wg : p.W;
     for (int i = tid; i < 156; i += kLnThreads) wc1[i] = src[i];
-    for (int i = tid; i < 2400; i += kLnThreads) wc2[(i / 150) * 152 + i % 150] = src[156 + i];
+    for (int i = tid; i < 2400; i += kLnThreads) wc2[(i / 150) * kWS + i % 150] = src[156 + i];
     if (tid < 16) wc2b[tid] = src[2556 + tid];
     for (int i = tid; i < kU1 * F0; i += kLnThreads) {
         const int ul = i / F0, k = i % F0;
@@ -327,10 +328,10 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
             const int n = lane & 15, kq = lane >> 4;
             const int npos = H2 * H2, ntile = npos >> 2;      // tiles of 16 positions over the 4 own samples
-            const float *wa1 = wc2 + n * 152 + kq;
-            const float *wa2 = wc2 + n * 152 + 5 * kq + 4;
-            const float *wa3 = wc2 + n * 152 + 25 * kq + 24;
-            const float *wa4 = wc2 + n * 152 + 25 * (4 + (kq & 1)) + 24;
+            const float *wa1 = wc2 + n * kWS + kq;
+            const float *wa2 = wc2 + n * kWS + 5 * kq + 4;
+            const float *wa3 = wc2 + n * kWS + 25 * kq + 24;
+            const float *wa4 = wc2 + n * kWS + 25 * (4 + (kq & 1)) + 24;
             const bool last2 = kq < 2;
 #pragma unroll 1
             for (int t0 = wave; t0 < ntile; t0 += 2 * (kLnThreads / 64)) {
@@ -1006,64 +1007,104 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             // contraction over the 16 channels, four per step, and the filter rows that reach yy),
             // and then  d[s][ci][yy][xx] = sum over kx of T[(ci, kx)][s][yy][xx - kx],  added in
             // the order of kx through a slice of LDS that belongs to the wave.
-            // Work item = (output row yy, sample pair); rows yy and 11 - yy together cost the same
-            // for yy = 4, 5 (ten filter-row passes), and rows {3, 8, 0, 11} and {2, 9, 1, 10} as
-            // well: every wave gets ten passes.
+            // Work item = output row yy, both sample pairs (one read of the filters for the two
+            // column tiles); the rows are dealt so that every wave gets five filter-row passes:
+            // {4}, {5}, {6}, {7}, {3, 0}, {8, 11}, {2, 1}, {9, 10}.
+            // A step's four lane groups take channels base + 2 kq (base = 0, 1, 8, 9): with the
+            // delta maps 68 floats apart their rows then start 8 banks apart.
             __syncthreads();    // gsum has been posted: its space now holds the waves' slices
             const int wave = __builtin_amdgcn_readfirstlane(tq >> 6), lane = tq & 63;
             const int n = lane & 15, kq = lane >> 4;
-            const int nt = wave & 1, wq = wave >> 1;                       // sample pair; 0..3
-            const int ya = wq == 0 ? 4 : wq == 1 ? 5 : wq == 2 ? 3 : 2;    // rows ya, 11 - ya, and
-            const int yb = wq == 2 ? 0 : wq == 3 ? 1 : -1;                 // yb, 11 - yb (if any)
+            const int ya = wave < 4 ? 4 + wave : wave == 4 ? 3 : wave == 5 ? 8 : wave == 6 ? 2 : 9;
+            const int yb = wave < 4 ? -1 : wave == 4 ? 0 : wave == 5 ? 11 : wave == 6 ? 1 : 10;
             const int m0 = n, m1 = 16 + n < 30 ? 16 + n : 29;              // rows (ci, kx) of the two tiles
-            const float *wa0 = wc2 + kq * 152 + (m0 / 5) * 25 + m0 % 5;
-            const float *wa1 = wc2 + kq * 152 + (m1 / 5) * 25 + m1 % 5;
-            const float *bbase = dc2 + ((2 * nt + (n >> 3)) * 16 + kq) * CS2 + (n & 7);
+            const float *wa0 = wc2 + 2 * kq * kWS + (m0 / 5) * 25 + m0 % 5;
+            const float *wa1 = wc2 + 2 * kq * kWS + (m1 / 5) * 25 + m1 % 5;
+            const float *bbase = dc2 + ((n >> 3) * 16 + 2 * kq) * CS2 + (n & 7);   // sample n / 8 of a pair
             float *scr = dpart + wave * kDP;
+            // second stage, the same for every item: lane -> three outputs (sample of the pair,
+            // input channel, xx); their five addends sit 16 floats apart in the slice
+            int rd[3], oo[3];
+            uint32_t vm[3];
+#pragma unroll
+            for (int j = 0; j < 3; ++j) {
+                const int o = lane + 64 * j, oc = o < 144 ? o : 0;
+                const int sl = oc / 72, rem = oc - 72 * sl, ci = rem / 12, xx = rem - 12 * ci;
+                rd[j] = ci * 85 + sl * 8 + xx;
+                oo[j] = sl * P1S + ci * nwin1 + xx;
+                uint32_t m = 0;
+#pragma unroll
+                for (int kx = 0; kx < 5; ++kx)
+                    if (o < 144 && xx - kx >= 0 && xx - kx < 8) m |= 1u << kx;
+                vm[j] = m;
+            }
 #pragma unroll 1
-            for (int it = 0; it < 4; ++it) {
-                const int ysel = it < 2 ? ya : yb;
-                if (ysel < 0) break;
-                const int yy = (it & 1) ? 11 - ysel : ysel;
+            for (int it = 0; it < 2; ++it) {
+                const int yy = it == 0 ? ya : yb;
+                if (yy < 0) break;
                 const int ky_lo = yy - 7 > 0 ? yy - 7 : 0, ky_hi = yy < 4 ? yy : 4;
-                f4 acc0 = {0.f, 0.f, 0.f, 0.f}, acc1 = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 1
-                for (int ky = ky_lo; ky <= ky_hi; ++ky) {
+                f4 acc[2][2];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[i >> 1][i & 1] = f4{0.f, 0.f, 0.f, 0.f};
+                // operands of one filter row (four steps of four channels); the next row's are
+                // fetched before the products of the current one are issued
+                auto fetch = [&](int ky, float (&av)[2][4], float (&bv)[2][4]) {
                     const float *ap0 = wa0 + ky * 5, *ap1 = wa1 + ky * 5, *bp = bbase + (yy - ky) * 8;
-                    float av0[4], av1[4], bv[4];
 #pragma unroll
                     for (int tc = 0; tc < 4; ++tc) {
-                        av0[tc] = ap0[tc * 4 * 152];
-                        av1[tc] = ap1[tc * 4 * 152];
-                        bv[tc] = bp[tc * 4 * CS2];
+                        const int cb = (tc & 1) + 8 * (tc >> 1);     // 0, 1, 8, 9
+                        av[0][tc] = ap0[cb * kWS];
+                        av[1][tc] = ap1[cb * kWS];
+                        bv[0][tc] = bp[cb * CS2];
+                        bv[1][tc] = bp[(32 + cb) * CS2];
+                    }
+                };
+                auto products = [&](const float (&av)[2][4], const float (&bv)[2][4]) {
+#pragma unroll
+                    for (int tc = 0; tc < 4; ++tc)
+#pragma unroll
+                        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+                            for (int mt = 0; mt < 2; ++mt)
+                                acc[nt][mt] = __builtin_amdgcn_mfma_f32_16x16x4f32(av[mt][tc], bv[nt][tc], acc[nt][mt], 0, 0, 0);
+                };
+                float xa[2][4], xb[2][4], ya4[2][4], yb4[2][4];
+                fetch(ky_lo, xa, xb);
+#pragma unroll 1
+                for (int ky = ky_lo;; ky += 2) {
+                    if (ky + 1 <= ky_hi) fetch(ky + 1, ya4, yb4);
+                    __builtin_amdgcn_sched_barrier(0);
+                    products(xa, xb);
+                    if (ky + 1 > ky_hi) break;
+                    if (ky + 2 <= ky_hi) fetch(ky + 2, xa, xb);
+                    __builtin_amdgcn_sched_barrier(0);
+                    products(ya4, yb4);
+                    if (ky + 2 > ky_hi) break;
+                }
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    // lane: column n = (sample of the pair, x'), rows 4 kq + r of both row tiles
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        scr[(4 * kq + r) * 17 + n] = acc[nt][0][r];
+                        if (16 + 4 * kq + r < 30) scr[(16 + 4 * kq + r) * 17 + n] = acc[nt][1][r];
+                    }
+                    // (the wave's LDS operations are carried out in order: no barrier is needed)
+                    // (all loads first, then the sums and the stores)
+                    float v[3][5], pm[3];
+#pragma unroll
+                    for (int j = 0; j < 3; ++j) {
+#pragma unroll
+                        for (int kx = 0; kx < 5; ++kx) v[j][kx] = scr[((vm[j] >> kx) & 1u) ? rd[j] + 16 * kx : 0];
+                        pm[j] = p1[oo[j] + 2 * nt * P1S + yy * P1];
                     }
                     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int tc = 0; tc < 4; ++tc) {
-                        acc0 = __builtin_amdgcn_mfma_f32_16x16x4f32(av0[tc], bv[tc], acc0, 0, 0, 0);
-                        acc1 = __builtin_amdgcn_mfma_f32_16x16x4f32(av1[tc], bv[tc], acc1, 0, 0, 0);
-                    }
-                }
-                // lane: column n = (sample of the pair, x'), rows 4 kq + r of both tiles
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    scr[(4 * kq + r) * 17 + n] = acc0[r];
-                    if (16 + 4 * kq + r < 30) scr[(16 + 4 * kq + r) * 17 + n] = acc1[r];
-                }
-                // (the wave's LDS operations are carried out in order: no barrier is needed)
-#pragma unroll
-                for (int j = 0; j < 3; ++j) {
-                    const int o = lane + 64 * j;
-                    if (o < 144) {
-                        const int sl = o / 72, rem = o - 72 * sl, ci = rem / 12, xx = rem - 12 * ci;
+                    for (int j = 0; j < 3; ++j) {
                         float t = 0.f;
 #pragma unroll
-                        for (int kx = 0; kx < 5; ++kx) {
-                            const int xp = xx - kx;
-                            if (xp >= 0 && xp < 8) t += scr[(ci * 5 + kx) * 17 + sl * 8 + xp];
-                        }
-                        const int oi = (2 * nt + sl) * P1S + ci * nwin1 + yy * P1 + xx;
-                        dp1[oi] = p1[oi] > 0.f ? t : 0.f;
+                        for (int kx = 0; kx < 5; ++kx) t += ((vm[j] >> kx) & 1u) ? v[j][kx] : 0.f;
+                        if (vm[j]) dp1[oo[j] + 2 * nt * P1S + yy * P1] = pm[j] > 0.f ? t : 0.f;
                     }
                 }
             }
@@ -1089,7 +1130,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                     for (int cc = 0; cc < 2; ++cc) {
                         const int c = cq + 8 * cc;
                         const float *row = dc2 + (s * 16 + c) * CS2 + (yy - ky) * H2;
-                        const float *wrow = wc2 + c * 152 + ci * 25 + ky * 5;
+                        const float *wrow = wc2 + c * kWS + ci * 25 + ky * 5;
                         if (H2 == 8) {
                             const f4 lo = *reinterpret_cast<const f4 *>(row), hi = *reinterpret_cast<const f4 *>(row + 4);
 #pragma unroll
@@ -1263,7 +1304,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 t += val[2];
                 t += val[3];
                 const float gv = t * invB;
-                float *w = e < 2556 ? wc2 + ((e - 156) / 150) * 152 + (e - 156) % 150 : wc2b + (e - 2556);
+                float *w = e < 2556 ? wc2 + ((e - 156) / 150) * kWS + (e - 156) % 150 : wc2b + (e - 2556);
                 *w -= eta * gv;
                 UC[1 + j] += gv;
             }
@@ -1340,7 +1381,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         for (int j = 0; j < 5; ++j) {
             const int e = 156 + tid + kLnThreads * j;
             if (e < kConvP) {
-                Wc[e] = e < 2556 ? wc2[((e - 156) / 150) * 152 + (e - 156) % 150] : wc2b[e - 2556];
+                Wc[e] = e < 2556 ? wc2[((e - 156) / 150) * kWS + (e - 156) % 150] : wc2b[e - 2556];
                 Uc[e] = UC[1 + j];
             }
         }
@@ -1376,7 +1417,7 @@ size_t lenet_lds_bytes(const LenetDims &d) {
     const int nwin1 = d.P1 * d.P1, P1S = 6 * nwin1 + 8, F0P = d.F0 + 4;
     size_t fl = up4(4 * d.H0 * d.H0) + 4 * P1S + 16 * F0P;
     fl += (2 * up4(4 * 6 * nwin1) + 2 * up4(4 * d.F0) + up4(4 * d.F0)) / 4;
-    fl += 160 + 16 * 152 + 16 + kU1 * F0P + 32 + kU2 * kS1 + 32 + kNC * kS2 + 16;
+    fl += 160 + 16 * kWS + 16 + kU1 * F0P + 32 + kU2 * kS1 + 32 + kNC * kS2 + 16;
     fl += 16 * kS1 + 16 * kS2 + 256 + 16 * kS2 + 16 * 24 + 16 * 32 + up4(4 * d.F0) + 2576 + 14 * 160 + 16 + 16 + 4;
     return fl * 4;
 }
