@@ -294,11 +294,17 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
         for (int it = tq; it < 8 * nwin1; it += kLnThreads) {
             const int half = it & 1, w = it >> 1, px = w % P1, py = (w / P1) % P1, s = w / nwin1;
             float patch[6][6];
+            // (H0 is even and the patch starts at an even column: its rows are three aligned pairs)
+            typedef float f2 __attribute__((ext_vector_type(2)));
             const float *xp = xs + s * npix + (2 * py) * H0 + 2 * px;
 #pragma unroll
             for (int i = 0; i < 6; ++i)
 #pragma unroll
-                for (int j = 0; j < 6; ++j) patch[i][j] = xp[i * H0 + j];
+                for (int j = 0; j < 6; j += 2) {
+                    const f2 v = *reinterpret_cast<const f2 *>(xp + i * H0 + j);
+                    patch[i][j] = v[0];
+                    patch[i][j + 1] = v[1];
+                }
 #pragma unroll
             for (int cc = 0; cc < 3; ++cc) {
                 const int c = 3 * half + cc;
