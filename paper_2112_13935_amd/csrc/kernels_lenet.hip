@@ -24,8 +24,15 @@
 // step u of it.
 //
 // Max pooling keeps, per window, which of its four inputs won; the backward pass through a
-// convolution + ReLU + pool stage touches only that input (the other three get no gradient),
-// so the filter gradients are sums over one position per window instead of four.
+// convolution + ReLU + pool stage touches only that input (the other three get no gradient).
+// The conv-1 filter gradient is therefore a sum over one position per window (vector ALU); for
+// conv 2 the window winners are scattered into a delta map that is zero elsewhere, and the
+// filter gradient and the backward-data pass are dense products over it.
+//
+// The second convolution (forward, filter gradient, backward-data) and the products of the two
+// hidden dense layers (forward, backward-data, weight gradient) run on the matrix cores
+// (fp32 16 x 16 x 4 products); the first convolution (6 channels) and the 10-class layer on
+// the vector ALU.
 //
 // All workgroups of a client must be resident together; the wait for a peer's word is
 // bounded and raises an error flag instead of hanging (every workgroup still runs to the end).
