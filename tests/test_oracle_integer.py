@@ -65,7 +65,7 @@ def test_sample_index_range_purity_and_map(oracle_libs):
 
 
 def test_sample_index_uniform(oracle_libs):
-    """'Sample uniformly at random from D_c': chi-square on 200,000 draws over 100 bins
+    """Algorithm 2, sampling step (a uniform draw from the client's shard): chi-square on 200,000 draws over 100 bins
     (99 degrees of freedom; 160 is far beyond the 99.99th percentile)."""
     lib = oracle_libs.load("f64")
     N, draws = 100, 200000
