@@ -540,6 +540,7 @@ k_mlp_round(const MlpPack pack, int nhere, int rec0, const float *Wg,
 #pragma unroll
                     for (int s = 0; s < 4 * NBT; ++s) xb[(tt + 1) & 1][s] = xcol[(16 * (s >> 2) + (s & 3)) * ld + 16 * (tt + 1)];
                 }
+                __builtin_amdgcn_sched_barrier(0);   // the next tile's operands are on their way before the products
                 if (FULL || tt < nt) {
                     // two independent accumulation chains per tile
                     // (the first product of each chain takes the constant zero as its addend)
