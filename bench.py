@@ -334,7 +334,7 @@ def main():
                     help="also run a plain 256 MiB device copy (calibrates the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)",
+        print("bench.py: the library runs on one GPU; --gpus must be 1 (there is no multi-GPU path)",
               file=sys.stderr)
         sys.exit(2)
 
