@@ -872,27 +872,34 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
             b1s[tq] -= eta * gv;
             U1b += gv;
         }
-        // delta at the own samples' pooled conv-2 outputs (masked by the ReLU)
+        // delta at the own samples' pooled conv-2 outputs (masked by the ReLU): both elements of
+        // a thread in one batch of loads
+        {
+            const u64 *ptr[8];
+            bool need[8];
+            float val[8];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int e = tq + kLnThreads * j;
-            const bool act = e < 4 * F0;
-            const int s = act ? e / F0 : 0, f = act ? e % F0 : 0;
-            const u64 *ptr[4];
-            bool need[4];
-            float val[4];
+            for (int j = 0; j < 2; ++j) {
+                const int e = tq + kLnThreads * j;
+                const bool act = e < 4 * F0;
+                const int s = act ? e / F0 : 0, f = act ? e % F0 : 0;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                ptr[i] = rec + kXB2 + i * 4096 + (4 * g + s) * 256 + f;
-                need[i] = act;
+                for (int i = 0; i < 4; ++i) {
+                    ptr[4 * j + i] = rec + kXB2 + i * 4096 + (4 * g + s) * 256 + f;
+                    need[4 * j + i] = act;
+                }
             }
-            xfetch<4>(ptr, need, val, wt);
-            if (act) {
-                float t = val[0];
-                t += val[1];
-                t += val[2];
-                t += val[3];
-                dp2[e] = alive2[j] ? t : 0.f;
+            xfetch<8>(ptr, need, val, wt);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int e = tq + kLnThreads * j;
+                if (e < 4 * F0) {
+                    float t = val[4 * j];
+                    t += val[4 * j + 1];
+                    t += val[4 * j + 2];
+                    t += val[4 * j + 3];
+                    dp2[e] = alive2[j] ? t : 0.f;
+                }
             }
         }
         __syncthreads();
@@ -1215,12 +1222,14 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 early[j][i] = __hip_atomic_load(rec + kXB3 + i * 2576 + (e < kConvP ? e : 156), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // ---- conv-1 filter gradient over the own samples: thread = (window group, channel,
-        // filter row or bias); one position per window ---------------------------------------------
+        // filter row); one position per window; the bias gradient is the sum of the deltas the
+        // thread of filter row 0 reads anyway ------------------------------------------------------
         if (tq < 14 * 36) {
             const int grp = tq / 36, r = tq % 36;
             if (r < 30) {
                 const int c = r / 5, ky = r % 5;
                 float acc[5] = {0.f, 0.f, 0.f, 0.f, 0.f};
+                float bsum = 0.f;    // the deltas themselves: the bias gradient (kept by the ky = 0 thread)
 #pragma unroll 1
                 for (int s = 0; s < 4; ++s) {
                     const float *dl_p = dp1 + s * P1S + c * nwin1;
@@ -1244,6 +1253,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
 #pragma unroll
                         for (int i = 0; i < 4; ++i) {
                             const float dv = w0 + 14 * i < nwin1 ? dl[i] : 0.f;
+                            bsum += dv;
 #pragma unroll
                             for (int kx = 0; kx < 5; ++kx) acc[kx] += dv * rv[i][kx];
                         }
@@ -1251,12 +1261,7 @@ k_lenet_round(const RoundParams *__restrict__ rp, int nhere, int rec0, const flo
                 }
 #pragma unroll
                 for (int kx = 0; kx < 5; ++kx) c1part[grp * 160 + c * 25 + ky * 5 + kx] = acc[kx];
-            } else {
-                const int c = r - 30;
-                float s = 0.f;
-                for (int i = 0; i < 4; ++i)
-                    for (int win = grp; win < nwin1; win += 14) s += dp1[i * P1S + c * nwin1 + win];
-                c1part[grp * 160 + 150 + c] = s;
+                if (ky == 0) c1part[grp * 160 + 150 + c] = bsum;
             }
         }
         __syncthreads();
