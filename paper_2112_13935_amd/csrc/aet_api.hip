@@ -496,8 +496,11 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         return fail(ctx, AET_ENOMEM, "no free U slot: more than max_inflight messages of a client in flight");
 
     if (nact > 0) {
-        // staging: the layer engine copies the records to the device from a pinned ring;
-        // the dense-ReLU-dense engine takes them in its kernel arguments from plain host memory
+        // staging: the layer engine copies the records to the device from a pinned ring; the
+        // dense-ReLU-dense engine takes them in its kernel arguments from plain host memory; the
+        // other two fused engines read them where they are, in the pinned ring (every workgroup
+        // reads its own record once, at its start: no copy in the stream ahead of the kernel)
+        const bool direct = !ctx->static_ws && (ctx->engine == ENGINE_SOFTMAX || ctx->engine == ENGINE_LENET);
         const int ring = ctx->ring_p;
         RoundParams *hp = ctx->static_ws ? ctx->v_params.data() : ctx->h_params[ring];
         if (ctx->engine != ENGINE_MLP && !ctx->static_ws) {
@@ -519,7 +522,9 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
         RoundParams *dp = hp;
         if (ctx->engine != ENGINE_MLP) {
             dp = reinterpret_cast<RoundParams *>(ctx->ws + ctx->lo.params);
-            if (ctx->static_ws) {
+            if (direct) {
+                dp = hp;
+            } else if (ctx->static_ws) {
                 for (int a0 = 0; a0 < nact; a0 += kPutParams) {
                     const int here = std::min(kPutParams, nact - a0);
                     ParamsPut put;
@@ -548,6 +553,7 @@ aet_status aet_run_round(aet_ctx *ctx, const aet_threshold *thr, const aet_eta *
             for (int64_t u = 0; u < max_m; ++u)
                 AET_HIP(ctx, launch_layer_step(ctx->stream, ctx->profp(), dp, nact, (int)u, ctx->lay, ctx->L, ctx->B, ctx->sc));
         }
+        if (direct) AET_HIP(ctx, hipEventRecord(ctx->ev_params[ring], ctx->stream));   // the ring slot is free after the kernel
         for (int a = 0; a < nact; ++a) {
             const int c = act[a];
             Msg msg;
